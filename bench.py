@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu]
+
+One step = encode the database rows (bundle layout) + encode the queries + exhaustive
+top-K search, all through the C-ABI library, with the fp32 inputs already resident in
+HBM.  Prints ONE JSON line: queries/s of the whole step, the roofline position of the
+dominant kernel (the XOR + population-count scan, timed with HIP events inside the
+library on the stream it runs on), and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def cpu_baseline(w, bits, k, scale, budget_s=15.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same
+    workload: the whole database is encoded and the first q queries are searched, q
+    sized from a short probe so the search takes about budget_s seconds."""
+    import numpy as np
+    from oracle import scale as oc
+    from paper_2008_02002_amd import workloads as wl
+
+    X = wl.database(w)
+    t0 = time.perf_counter()
+    planes = oc.encode(X, bits, scale)
+    t_enc = time.perf_counter() - t0
+    del X
+    Q = wl.queries(w)
+    qplanes = oc.encode(Q, bits, scale)
+    probe = min(w.m, 4 * oc.threads())
+    t0 = time.perf_counter()
+    oc.search(planes, qplanes[:probe], w.d, k)
+    t_probe = time.perf_counter() - t0
+    q = int(min(w.m, max(probe, budget_s / max(t_probe, 1e-6) * probe)))
+    t0 = time.perf_counter()
+    oc.search(planes, qplanes[:q], w.d, k)
+    t_search = time.perf_counter() - t0
+    whole_job = t_enc + t_search * (w.m / q)
+    return {
+        "value": w.m / whole_job,
+        "unit": "queries/s",
+        "cores": oc.threads(),
+        "kind": "oracle",
+        "sample": (f"database of {w.n} rows encoded in {t_enc:.2f}s; first {q} of {w.m} queries searched "
+                   f"over all rows in {t_search:.2f}s; whole job extrapolated linearly in the query count"),
+    }
+
+
+def recall_at_k(Xdb_dev, Xq_dev, idx_dev, k, nq=256):
+    """Precision@K (Section 5) of the returned rows against exact fp32 cosine, first nq queries."""
+    import torch
+    nq = min(nq, Xq_dev.shape[0])
+    sim = Xq_dev[:nq] @ Xdb_dev.T
+    real = torch.topk(sim, k, dim=1).indices
+    hits = 0
+    for i in range(nq):
+        hits += len(set(real[i].tolist()) & set(idx_dev[i].tolist()))
+    return hits / float(nq * k), nq
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--bits", type=int, default=0)
+    ap.add_argument("--k", type=int, default=0)
+    ap.add_argument("--queries", type=int, default=0, help="use only the first N queries")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-recall", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (one process, one device, no collectives); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2008_02002_amd import costmodel as cm
+    from paper_2008_02002_amd import workloads as wl
+    from paper_2008_02002_amd import xbq
+
+    w = wl.WORKLOADS[args.workload]
+    if args.queries:
+        w = wl.scaled_down(w, m=args.queries)
+    bits = args.bits or w.bits[-1]
+    k = args.k or w.ks[-1]
+    torch.cuda.set_device(0)
+    xbq.lib()
+
+    scale = wl.workload_scale(w)
+    Xq = torch.from_numpy(wl.queries(w)).cuda()
+    Xdb = torch.empty((w.n, w.d), dtype=torch.float32, device="cuda")
+    slab = 1 << 20
+    for lo in range(0, w.n, slab):
+        hi = min(w.n, lo + slab)
+        Xdb[lo:hi] = torch.from_numpy(wl.database(w, lo, hi)).cuda()
+    db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
+    q = torch.empty(xbq.xbq_code_bytes(w.m, w.d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
+    ws = torch.empty(xbq.xbq_search_workspace_bytes(w.n, w.m, w.d, bits, k), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
+    score = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
+
+    def step():
+        xbq.xbq_encode(Xdb, bits, scale, xbq.BUNDLE64, out=db)
+        xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
+        xbq.xbq_search(db, w.n, q, w.m, w.d, bits, k, workspace=ws, idx=idx, score=score)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    xbq.xbq_trace_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    enc_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        enc_ev[i][0].record()
+        xbq.xbq_encode(Xdb, bits, scale, xbq.BUNDLE64, out=db)
+        enc_ev[i][1].record()
+        xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
+        xbq.xbq_search(db, w.n, q, w.m, w.d, bits, k, workspace=ws, idx=idx, score=score)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    scan_ms, launches, pairs = xbq.xbq_trace_read()
+    xbq.xbq_trace_enable(False)
+    enc_ms = sum(a.elapsed_time(b) for a, b in enc_ev) / args.steps
+    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+
+    ops = cm.credited_lane_ops_per_pair(w.d, bits, bits) * pairs          # credited XOR + popcount lane-ops
+    achieved = ops / (scan_ms * 1e-3) / 1e12
+    peak = cm.VALU_INT_LANE_OPS_PER_S / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "scan_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{w.name}_b{bits}_k{k}")
+        except Exception:
+            traffic = None
+    out = {
+        "metric": "queries/s, 1M x d128 4-bit K=100 (encode + XOR/popcount scan + top-K)"
+                  if w.name == "C2" else f"queries/s, {w.name}",
+        "value": w.m / (ms_per_step * 1e-3),
+        "unit": "queries/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: n={w.n} d={w.d} m={w.m} bits={bits} K={k} ({w.kind}, seed {w.seed})",
+                   "scale": scale},
+        "roofline": {
+            "bound": "alu",
+            "kernel": "scan (XOR + population count), all launches of one step",
+            "achieved": achieved,
+            "peak": peak,
+            "unit": "T lane-op/s (32-bit integer)",
+            "frac": achieved / peak,
+            "traffic": traffic,
+            "scan_ms_per_step": scan_ms / args.steps,
+            "launches_per_step": launches / args.steps,
+            "avg_launch_ms": scan_ms / max(launches, 1),
+            "scan_code_GBps": w.n * cm.code_bytes_per_row(w.d, bits) / 1e9 / (scan_ms / args.steps * 1e-3),
+        },
+        "encode": {"db_ms": enc_ms,
+                   "GBps": w.n * cm.encode_bytes_per_row(w.d, bits) / 1e9 / (enc_ms * 1e-3),
+                   "hbm_frac": w.n * cm.encode_bytes_per_row(w.d, bits) / (enc_ms * 1e-3) / cm.HBM_BYTES_PER_S},
+    }
+    if not args.no_recall:
+        r, nq = recall_at_k(Xdb, Xq, idx, k)
+        out["recall_at_k"] = {"value": r, "queries": nq, "against": "exact fp32 cosine (torch matmul + topk)"}
+    del Xdb
+    torch.cuda.empty_cache()
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, bits, k, scale)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

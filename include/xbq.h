@@ -1,0 +1,120 @@
+/*
+ * xbq -- XOR-friendly binary quantized exhaustive top-K cosine search on MI355X.
+ *
+ * C ABI of libxbq.so.  The library implements the search path of "Fast top-K
+ * Cosine Similarity Search through XOR-Friendly Binary Quantization on GPUs"
+ * (arXiv 2008.02002): encode fp32 vectors into B-bit codes stored as bit-planes,
+ * score every query against every database row with XOR + population count, and
+ * select the K best rows per query.
+ *
+ * Common rules for every entry point
+ *   - Every pointer named X, codes, db_codes, q_codes, idx, score or workspace is
+ *     a DEVICE pointer owned by the caller.  The library never allocates, frees
+ *     or keeps device memory, and never synchronises the stream or the device.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it and the call returns immediately.
+ *   - Return value: XBQ_OK (0) or a negative XBQ_E* code; xbq_strerror() names it.
+ *     On an argument error nothing is enqueued and no output is written.
+ *   - n == 0 or m == 0 is valid and does nothing.
+ *   - Inputs must be finite; NaN is outside the contract.  L2 normalisation is the
+ *     caller's business (Section 3: cosine = inner product of normalised vectors).
+ */
+#ifndef XBQ_H
+#define XBQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define XBQ_OK            0
+#define XBQ_EINVAL       (-1)  /* null pointer, bad size, bad k, misaligned pointer      */
+#define XBQ_EUNSUPPORTED (-2)  /* bits, d or layout outside what the kernels cover       */
+#define XBQ_EWORKSPACE   (-3)  /* workspace smaller than xbq_search_workspace_bytes()    */
+#define XBQ_EHIP         (-4)  /* a HIP launch or query failed; see xbq_last_hip_error() */
+
+/* Code layouts (both hold uint32 plane words, W = ceil(d/32) per plane, plane b =
+ * bit b of every coordinate's code, coordinate 32w+t at bit t of word w, pad bits 0;
+ * Section 3.3, Eq. 5):
+ *   XBQ_ROWS     [n][bits][W]                    exchange layout, used for queries
+ *   XBQ_BUNDLE64 [ceil(n/64)][bits][W][64]       scan layout, used for the database:
+ *                rows are grouped 64 at a time (one per wavefront lane) and stored
+ *                word-major so a wavefront reads one word of 64 rows as 256 contiguous
+ *                bytes.  Rows past n in the last bundle are written as zero words.
+ * (The bundle idea is the one Section 4.1 "Distance Calculation" describes for
+ * 32-wide warps, resized for 64-wide wavefronts.) */
+#define XBQ_ROWS     0
+#define XBQ_BUNDLE64 1
+
+#define XBQ_MAX_BITS 4      /* bits per coordinate: 1..4                              */
+#define XBQ_MAX_DIM  2048   /* d: 1..2048                                             */
+#define XBQ_MAX_K    1024   /* k: 1..min(n, 1024)  (Section 5 evaluates K up to 1000) */
+
+int xbq_version(void);
+const char* xbq_strerror(int code);
+/* hipError_t (as int) of the most recent XBQ_EHIP on this thread, 0 if none. */
+int xbq_last_hip_error(void);
+
+/* Bytes of a codes buffer for n rows in the given layout; 0 if arguments are invalid. */
+size_t xbq_code_bytes(int64_t n, int d, int bits, int layout);
+
+/*
+ * Encode (Section 3.2 quantizer f_B after the scaling of Section 3.5, then the
+ * bit-plane reconstruction of Section 3.3 / Eq. 5).
+ *   X      [n][d] fp32 row-major, device, read only
+ *   scale  finite, > 0; every coordinate is multiplied by it in binary32 (round to
+ *          nearest even) before quantizing; 1.0f gives the bare f_B
+ *   codes  device, xbq_code_bytes(n, d, bits, layout) bytes, fully overwritten
+ * The code of coordinate value t is chosen digit by digit, most significant first,
+ * with sign(0) = +1; stored bit 1 means digit -1.  Values at or beyond +-1 land in the
+ * outermost cell (no error).  n < 2^31.
+ */
+int xbq_encode(const float* X, int64_t n, int d, int bits, float scale, int layout,
+               uint32_t* codes, void* stream);
+
+/* Bytes of scratch xbq_search needs for these sizes; 0 if arguments are invalid.
+ * Depends on n only through min(n, small constant) and on m only up to an internal
+ * query batch, so it stays below ~1 GiB. */
+size_t xbq_search_workspace_bytes(int64_t n, int64_t m, int d, int bits, int k);
+
+/*
+ * Exhaustive top-K (Section 2 problem statement; Section 3.3 Eq. 6 for the distance,
+ * Eq. 2 for the score).
+ *   db_codes  XBQ_BUNDLE64 codes of the n database rows
+ *   q_codes   XBQ_ROWS codes of the m queries (same d, bits and scale as the database)
+ *   idx       [m][k] int32: database row numbers, best first
+ *   score     [m][k] int32: S = d*(2^bits-1)^2 - 2*D, D = sum_i sum_j POPCNT(x_i ^ y_j) << (i+j);
+ *             S is the integer inner product of the decoded codes scaled by 4^bits
+ *   workspace device scratch, 256-byte aligned, at least xbq_search_workspace_bytes(...);
+ *             contents are undefined afterwards; one workspace serves one call at a time
+ * Order: S descending, ties by ascending row number; the result is unique.
+ * 1 <= k <= min(n, XBQ_MAX_K), n < 2^31, else XBQ_EINVAL.
+ */
+int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int64_t m, int d,
+               int bits, int k, int32_t* idx, int32_t* score, void* workspace,
+               size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement aid.  While tracing is on, xbq_search brackets every launch of the scan
+ * kernel (the XOR + population-count loop) with HIP events on the caller's stream.
+ * xbq_trace_read waits for those events, returns the summed kernel time, the number of
+ * launches and the number of (query, row) pairs they scored, and clears the record.
+ * Not thread safe; at most 4096 launches are recorded between reads.
+ */
+int xbq_trace_enable(int on);
+int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
+
+/*
+ * Tuning knobs (process-wide, host side only).  name = "growth" (size ratio of
+ * successive database groups, default 2.0), "first" (rows scored densely before any
+ * threshold exists, default 1024), "qsplit" (queries per workgroup, 0 = automatic).
+ * Returns XBQ_EINVAL for an unknown name or a value out of range.
+ */
+int xbq_set_option(const char* name, double value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XBQ_H */

@@ -1,0 +1,354 @@
+// C ABI of libxbq.so: argument validation, the search schedule, workspace carving and
+// kernel launches.  No device memory is allocated here and nothing synchronises.
+//
+// Search schedule.  The database rows are split into groups of growing size.  The first,
+// small group is scored densely and its exact top-K gives every query a threshold (the
+// distance of its K-th best row).  Each later group is scanned with that threshold: only
+// rows strictly closer than the K-th best so far can enter the top-K (a row with an equal
+// distance has a higher row number than everything already seen, so it loses the tie),
+// and for rows in random order about K * (group size / rows seen) of them do.  After each
+// group one small kernel per query merges the survivors into the top-K and tightens the
+// threshold.  A query whose survivor list overflows its buffer is rescanned exactly by a
+// fallback kernel, so the result never depends on the data order.
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "xbq_internal.h"
+
+namespace {
+
+using namespace xbq;
+
+thread_local int g_last_hip_error = 0;
+
+struct Options {
+    double growth = 2.0;
+    int first = 1024;
+    int qsplit = 0;
+} g_opt;
+
+struct Trace {
+    bool on = false;
+    std::vector<hipEvent_t> ev;      // pairs: start, stop
+    int used = 0;                    // events used
+    double pairs = 0;
+} g_trace;
+constexpr int kTraceMaxLaunches = 4096;
+
+int fail_hip(hipError_t e)
+{
+    g_last_hip_error = static_cast<int>(e);
+    return XBQ_EHIP;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int next_pow2(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+bool valid_shape(int d, int bits) { return d >= 1 && d <= XBQ_MAX_DIM && bits >= 1 && bits <= XBQ_MAX_BITS; }
+
+constexpr int64_t kQueryBatch = 16384;
+
+struct Plan {
+    int W = 0, wc = 0, nchunks = 0;      // wc == 0: register-resident scan
+    int first = 0;                       // rows of the dense group
+    int cap = 0;                         // candidate slots per query
+    int64_t batch = 0;                   // queries per batch
+    size_t off_thr = 0, off_cnt = 0, off_ovf = 0, off_topk = 0, off_cand = 0, off_dense = 0, off_q = 0;
+    size_t total = 0;
+};
+
+Plan make_plan(int64_t n, int64_t m, int d, int bits, int k)
+{
+    Plan p;
+    p.W = words32(d);
+    if (!scan_is_resident(bits, p.W)) {
+        p.wc = scan_chunk_words(p.W);
+        p.nchunks = (p.W + p.wc - 1) / p.wc;
+    }
+    const int kpad = next_pow2(k);
+    int first = g_opt.first > 4 * kpad ? g_opt.first : 4 * kpad;
+    if (first > kSortCap) first = kSortCap;
+    first = first / kLanes * kLanes;
+    p.first = static_cast<int>(n < first ? n : first);
+    p.cap = 3 * kpad > 1024 ? 3 * kpad : 1024;
+    p.batch = m < kQueryBatch ? m : kQueryBatch;
+    const size_t b = static_cast<size_t>(p.batch);
+    size_t off = 0;
+    p.off_thr = off;   off = align_up(off + b * sizeof(uint32_t), 256);
+    p.off_cnt = off;   off = align_up(off + b * sizeof(uint32_t), 256);
+    p.off_ovf = off;   off = align_up(off + b * sizeof(uint32_t), 256);
+    p.off_topk = off;  off = align_up(off + b * k * sizeof(uint64_t), 256);
+    p.off_cand = off;  off = align_up(off + b * p.cap * sizeof(uint64_t), 256);
+    p.off_dense = off; off = align_up(off + b * static_cast<size_t>(p.first) * sizeof(uint32_t), 256);
+    p.off_q = off;
+    if (p.wc) off = align_up(off + b * p.nchunks * bits * p.wc * sizeof(uint32_t), 256);
+    p.total = off;
+    return p;
+}
+
+bool valid_search_sizes(int64_t n, int64_t m, int d, int bits, int k)
+{
+    if (!valid_shape(d, bits)) return false;
+    if (n < 0 || m < 0 || n >= (int64_t(1) << 31) || m >= (int64_t(1) << 31)) return false;
+    if (n > 0 && (k < 1 || k > XBQ_MAX_K || k > n)) return false;
+    if (n == 0 && k < 1) return false;
+    return true;
+}
+
+// Queries per workgroup for a group of `bundles` bundles.
+int choose_qsplit(int64_t bundles, int rows_per_lane, int m, int tile)
+{
+    if (g_opt.qsplit > 0) return (g_opt.qsplit + tile - 1) / tile * tile;
+    const int64_t waves = (bundles + rows_per_lane - 1) / rows_per_lane;
+    int64_t ranges = (32768 + waves - 1) / waves;            // aim for >= 32k wavefronts
+    const int64_t min_ranges = (m + 127) / 128;               // at most 128 queries per workgroup
+    if (ranges < min_ranges) ranges = min_ranges;
+    int qs = static_cast<int>((m + ranges - 1) / ranges);
+    if (qs < 16) qs = 16;
+    qs = (qs + tile - 1) / tile * tile;
+    if ((m + qs - 1) / qs > 65535) qs = (m + 65534) / 65535;
+    return qs;
+}
+
+hipError_t traced_scan(int bits, const ScanArgs& a, bool dense, hipStream_t s)
+{
+    const bool rec = g_trace.on && g_trace.used + 2 <= static_cast<int>(g_trace.ev.size());
+    if (rec) {
+        hipError_t e = hipEventRecord(g_trace.ev[g_trace.used], s);
+        if (e != hipSuccess) return e;
+    }
+    hipError_t e = launch_scan(bits, a, dense, s);
+    if (e != hipSuccess) return e;
+    if (rec) {
+        e = hipEventRecord(g_trace.ev[g_trace.used + 1], s);
+        if (e != hipSuccess) return e;
+        g_trace.used += 2;
+        g_trace.pairs += static_cast<double>(a.row_end - a.row_begin) * a.m;
+    }
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+int xbq_version(void) { return 100; }
+
+const char* xbq_strerror(int code)
+{
+    switch (code) {
+    case XBQ_OK: return "ok";
+    case XBQ_EINVAL: return "invalid argument";
+    case XBQ_EUNSUPPORTED: return "unsupported bits, dimension or layout";
+    case XBQ_EWORKSPACE: return "workspace too small";
+    case XBQ_EHIP: return "HIP runtime error";
+    default: return "unknown error code";
+    }
+}
+
+int xbq_last_hip_error(void) { return g_last_hip_error; }
+
+size_t xbq_code_bytes(int64_t n, int d, int bits, int layout)
+{
+    if (!valid_shape(d, bits) || n < 0 || n >= (int64_t(1) << 31)) return 0;
+    const size_t per_row = static_cast<size_t>(bits) * words32(d) * sizeof(uint32_t);
+    if (layout == XBQ_ROWS) return static_cast<size_t>(n) * per_row;
+    if (layout == XBQ_BUNDLE64) return static_cast<size_t>((n + kLanes - 1) / kLanes) * kLanes * per_row;
+    return 0;
+}
+
+int xbq_encode(const float* X, int64_t n, int d, int bits, float scale, int layout, uint32_t* codes, void* stream)
+{
+    if (d < 1 || bits < 1 || n < 0 || n >= (int64_t(1) << 31)) return XBQ_EINVAL;
+    if (!valid_shape(d, bits) || (layout != XBQ_ROWS && layout != XBQ_BUNDLE64)) return XBQ_EUNSUPPORTED;
+    if (!(scale > 0.0f) || !std::isfinite(scale)) return XBQ_EINVAL;
+    if (n == 0) return XBQ_OK;
+    if (X == nullptr || codes == nullptr) return XBQ_EINVAL;
+    if (reinterpret_cast<uintptr_t>(X) % 4 || reinterpret_cast<uintptr_t>(codes) % 4) return XBQ_EINVAL;
+    const hipError_t e = launch_encode(X, n, d, bits, scale, layout, codes, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XBQ_OK : fail_hip(e);
+}
+
+size_t xbq_search_workspace_bytes(int64_t n, int64_t m, int d, int bits, int k)
+{
+    if (!valid_search_sizes(n, m, d, bits, k)) return 0;
+    if (n == 0 || m == 0) return 256;
+    return make_plan(n, m, d, bits, k).total;
+}
+
+int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int64_t m, int d, int bits, int k,
+               int32_t* idx, int32_t* score, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (d < 1 || bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
+    if (!valid_shape(d, bits)) return XBQ_EUNSUPPORTED;
+    if (!valid_search_sizes(n, m, d, bits, k)) return XBQ_EINVAL;
+    if (n == 0 || m == 0) return XBQ_OK;
+    if (!db_codes || !q_codes || !idx || !score || !workspace) return XBQ_EINVAL;
+    if (reinterpret_cast<uintptr_t>(db_codes) % 4 || reinterpret_cast<uintptr_t>(q_codes) % 4 ||
+        reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(score) % 4 ||
+        reinterpret_cast<uintptr_t>(workspace) % 256)
+        return XBQ_EINVAL;
+    const Plan p = make_plan(n, m, d, bits, k);
+    if (workspace_bytes < p.total) return XBQ_EWORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    const int rpl_max = (p.wc == 0 && bits * p.W <= 16) ? 2 : 1;
+    const int tile = p.wc ? kTileQ : 1;
+
+    for (int64_t qb = 0; qb < m; qb += p.batch) {
+        const int mb = static_cast<int>(m - qb < p.batch ? m - qb : p.batch);
+        const uint32_t* q_rows = q_codes + qb * (static_cast<int64_t>(bits) * p.W);
+
+        ScanArgs sa{};
+        sa.db = db_codes;
+        sa.n = n;
+        sa.m = mb;
+        sa.W = p.W;
+        sa.wc = p.wc;
+        sa.nchunks = p.nchunks;
+        sa.thr = reinterpret_cast<uint32_t*>(ws + p.off_thr);
+        sa.cnt = reinterpret_cast<uint32_t*>(ws + p.off_cnt);
+        sa.cand = reinterpret_cast<uint64_t*>(ws + p.off_cand);
+        sa.cap = p.cap;
+        sa.dense = reinterpret_cast<uint32_t*>(ws + p.off_dense);
+        sa.dense_stride = p.first;
+        if (p.wc) {
+            uint32_t* qc = reinterpret_cast<uint32_t*>(ws + p.off_q);
+            const hipError_t e = launch_repack_queries(q_rows, mb, bits, p.W, p.wc, p.nchunks, qc, s);
+            if (e != hipSuccess) return fail_hip(e);
+            sa.q = qc;
+        } else {
+            sa.q = q_rows;
+        }
+
+        SelectArgs sel{};
+        sel.m = mb;
+        sel.k = k;
+        sel.d = d;
+        sel.bits = bits;
+        sel.topk = reinterpret_cast<uint64_t*>(ws + p.off_topk);
+        sel.thr = reinterpret_cast<uint32_t*>(ws + p.off_thr);
+        sel.cnt = reinterpret_cast<uint32_t*>(ws + p.off_cnt);
+        sel.ovf = reinterpret_cast<uint32_t*>(ws + p.off_ovf);
+        sel.cand = sa.cand;
+        sel.cap = p.cap;
+        sel.dense = sa.dense;
+        sel.dense_stride = p.first;
+        sel.idx = idx + qb * k;
+        sel.score = score + qb * k;
+
+        // group 0: dense
+        int64_t seen = p.first;
+        {
+            sa.row_begin = 0;
+            sa.row_end = seen;
+            const int64_t bundles = (seen + kLanes - 1) / kLanes;
+            sa.rows_per_lane = 1;
+            sa.qsplit = choose_qsplit(bundles, 1, mb, tile);
+            hipError_t e = traced_scan(bits, sa, true, s);
+            if (e != hipSuccess) return fail_hip(e);
+            sel.row_begin = 0;
+            sel.rows = p.first;
+            sel.final_group = seen >= n;
+            e = launch_select_dense(sel, s);
+            if (e != hipSuccess) return fail_hip(e);
+        }
+        // later groups: threshold scan, merge, exact rescan of overflowed queries
+        while (seen < n) {
+            int64_t size = static_cast<int64_t>(std::ceil(static_cast<double>(seen) * (g_opt.growth - 1.0)));
+            size = (size + 511) / 512 * 512;
+            int64_t end = seen + size;
+            if (end > n || n - end < 512) end = n;
+            sa.row_begin = seen;
+            sa.row_end = end;
+            const int64_t bundles = (end - seen + kLanes - 1) / kLanes;
+            sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
+            sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, tile);
+            hipError_t e = traced_scan(bits, sa, false, s);
+            if (e != hipSuccess) return fail_hip(e);
+            sel.row_begin = seen;
+            sel.final_group = end >= n;
+            e = launch_select_merge(sel, s);
+            if (e != hipSuccess) return fail_hip(e);
+            RescanArgs ra{};
+            ra.db = db_codes;
+            ra.n = n;
+            ra.row_begin = seen;
+            ra.row_end = end;
+            ra.q_rows = q_rows;
+            ra.W = p.W;
+            ra.sel = sel;
+            e = launch_rescan(ra, s);
+            if (e != hipSuccess) return fail_hip(e);
+            seen = end;
+        }
+    }
+    return XBQ_OK;
+}
+
+int xbq_trace_enable(int on)
+{
+    if (on && g_trace.ev.empty()) {
+        g_trace.ev.resize(2 * kTraceMaxLaunches);
+        for (auto& e : g_trace.ev) {
+            const hipError_t r = hipEventCreate(&e);
+            if (r != hipSuccess) { g_trace.ev.clear(); return fail_hip(r); }
+        }
+    }
+    g_trace.on = on != 0;
+    g_trace.used = 0;
+    g_trace.pairs = 0;
+    return XBQ_OK;
+}
+
+int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs)
+{
+    if (!scan_ms || !launches || !pairs) return XBQ_EINVAL;
+    double ms = 0;
+    for (int i = 0; i + 1 < g_trace.used; i += 2) {
+        hipError_t e = hipEventSynchronize(g_trace.ev[i + 1]);
+        if (e != hipSuccess) return fail_hip(e);
+        float t = 0;
+        e = hipEventElapsedTime(&t, g_trace.ev[i], g_trace.ev[i + 1]);
+        if (e != hipSuccess) return fail_hip(e);
+        ms += t;
+    }
+    *scan_ms = ms;
+    *launches = g_trace.used / 2;
+    *pairs = g_trace.pairs;
+    g_trace.used = 0;
+    g_trace.pairs = 0;
+    return XBQ_OK;
+}
+
+int xbq_set_option(const char* name, double value)
+{
+    if (!name) return XBQ_EINVAL;
+    if (!std::strcmp(name, "growth")) {
+        if (!(value >= 1.25 && value <= 64.0)) return XBQ_EINVAL;
+        g_opt.growth = value;
+        return XBQ_OK;
+    }
+    if (!std::strcmp(name, "first")) {
+        if (!(value >= 64 && value <= kSortCap)) return XBQ_EINVAL;
+        g_opt.first = static_cast<int>(value);
+        return XBQ_OK;
+    }
+    if (!std::strcmp(name, "qsplit")) {
+        if (!(value >= 0 && value <= 65536)) return XBQ_EINVAL;
+        g_opt.qsplit = static_cast<int>(value);
+        return XBQ_OK;
+    }
+    return XBQ_EINVAL;
+}
+
+}  // extern "C"

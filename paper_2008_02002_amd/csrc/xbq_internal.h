@@ -1,0 +1,94 @@
+// Internal declarations shared by the translation units of libxbq.so.
+// Nothing here is part of the C ABI (see include/xbq.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "xbq.h"
+
+namespace xbq {
+
+constexpr int kLanes = 64;        // wavefront width on gfx950
+constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts, one per SIMD)
+constexpr int kSortCap = 4096;    // most 64-bit keys one workgroup sorts in LDS
+constexpr int kTileQ = 16;        // queries per register tile of the word-chunked scan
+
+// A candidate is ordered by the 64-bit key (D << 32) | row: smaller key = better
+// (smaller distance D, then lower row number).  D is the Eq. 6 distance.
+__host__ __device__ inline uint64_t make_key(uint32_t D, uint32_t row)
+{
+    return (static_cast<uint64_t>(D) << 32) | row;
+}
+
+inline int words32(int d) { return (d + 31) / 32; }
+
+// One launch of the scan over database rows [row_begin, row_end) for queries [0, m).
+struct ScanArgs {
+    const uint32_t* db;      // XBQ_BUNDLE64 codes of the whole database
+    int64_t n;               // rows in the database
+    int64_t row_begin;       // multiple of 64
+    int64_t row_end;         // <= n
+    const uint32_t* q;       // XBQ_ROWS codes (register-resident scan) or chunk-major
+                             // padded codes [m][nchunks][B][WC] (word-chunked scan)
+    int m;                   // queries in this batch
+    int qsplit;              // queries per workgroup (grid.y = ceil(m / qsplit))
+    int W;                   // 32-bit words per plane
+    int rows_per_lane;       // 1 or 2 (register-resident scan only)
+    int wc;                  // words per chunk, 0 = register-resident scan
+    int nchunks;             // ceil(W / wc)
+    // threshold mode: a row passes when D < thr[q]; passing keys are appended to cand[q]
+    const uint32_t* thr;     // [m]
+    uint32_t* cnt;           // [m] number of keys appended (may exceed cap: overflow)
+    uint64_t* cand;          // [m][cap]
+    int cap;
+    // dense mode: every D is stored
+    uint32_t* dense;         // [m][dense_stride], column = row - row_begin
+    int dense_stride;
+};
+
+// True if (bits, W) is served by the register-resident scan.
+bool scan_is_resident(int bits, int W);
+// Chunk width the word-chunked scan uses for W words per plane.
+int scan_chunk_words(int W);
+
+hipError_t launch_scan(int bits, const ScanArgs& a, bool dense, hipStream_t s);
+
+hipError_t launch_repack_queries(const uint32_t* q_rows, int m, int bits, int W, int wc,
+                                 int nchunks, uint32_t* q_chunked, hipStream_t s);
+
+hipError_t launch_encode(const float* X, int64_t n, int d, int bits, float scale, int layout,
+                         uint32_t* codes, hipStream_t s);
+
+struct SelectArgs {
+    int m, k, d, bits;
+    uint64_t* topk;          // [m][k] best keys so far, ascending
+    uint32_t* thr;           // [m] D of the k-th best key
+    uint32_t* cnt;           // [m]
+    uint32_t* ovf;           // [m] 1 = candidate list overflowed for the current group
+    const uint64_t* cand;    // [m][cap]
+    int cap;
+    const uint32_t* dense;   // [m][dense_stride]
+    int dense_stride;
+    int64_t row_begin;       // first row of the group just scanned
+    int rows;                // rows in the dense group
+    int final_group;         // 1 = also write idx / score
+    int32_t* idx;            // [m][k]
+    int32_t* score;          // [m][k]
+};
+
+hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s);
+hipError_t launch_select_merge(const SelectArgs& a, hipStream_t s);
+
+// Exact rescan of rows [row_begin, row_end) for the queries whose candidate list
+// overflowed (ovf[q] != 0); other workgroups exit at once.
+struct RescanArgs {
+    const uint32_t* db;
+    int64_t n, row_begin, row_end;
+    const uint32_t* q_rows;  // XBQ_ROWS
+    int W;
+    SelectArgs sel;
+};
+hipError_t launch_rescan(const RescanArgs& a, hipStream_t s);
+
+}  // namespace xbq

@@ -1,0 +1,308 @@
+// Scan kernels: Eq. 6 of Section 3.3, D = sum_i sum_j POPCNT(xhat_i ^ yhat_j) << (i + j),
+// for every (query, database row) pair of a row range, on the vector ALUs of gfx950.
+//
+// Mapping.  One lane owns one database row (two when the code is short): its plane
+// words sit in VGPRs.  The query is uniform across the wavefront, so its words are read
+// with scalar loads and reach v_xor_b32 as SGPR operands; v_bcnt_u32_b32 adds the
+// population count into an accumulator in the same instruction.  One accumulator per
+// weight class i + j, combined by shift-adds once per pair.  The loop keeps no selection
+// state: a pair either stores its distance (dense mode) or is compared with the query's
+// current threshold and, if it beats it, is appended to that query's candidate list
+// (threshold mode).  Nothing here uses the matrix cores: the work is bitwise.
+//
+// Two kernel families:
+//   scan_resident  - whole code of the row(s) in registers, all queries stream past it;
+//                    the database is read from memory exactly once per query range.
+//   scan_chunked   - for long codes: the row is processed in chunks of WC words per
+//                    plane against a register tile of kTileQ queries, partial distances
+//                    accumulated per query; the database chunk comes from L2.
+
+#include "xbq_internal.h"
+
+namespace xbq {
+
+typedef const uint32_t __attribute__((address_space(4))) * uniform_ptr;  // scalar-load path
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
+
+// Append the keys of the lanes with `pass` set to cand[q]; one atomic per wavefront.
+__device__ __forceinline__ void emit(bool pass, uint32_t D, uint32_t row, int q, uint32_t* cnt,
+                                     uint64_t* cand, int cap)
+{
+    const uint64_t mask = __ballot(pass);
+    if (mask == 0) return;
+    const int lane = lane_id();
+    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(&cnt[q], static_cast<uint32_t>(__popcll(mask)));
+    base = __shfl(base, leader);
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+    const uint32_t pos = base + rank;
+    if (pass && pos < static_cast<uint32_t>(cap)) cand[static_cast<size_t>(q) * cap + pos] = make_key(D, row);
+}
+
+// Eq. 6 for one row held in x against the B*WC uniform words y (plane-major, stride ystride).
+template <int B, int WC>
+__device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[B][WC], const uint32_t (&y)[B][WC])
+{
+    uint32_t acc[2 * B - 1];
+#pragma unroll
+    for (int c = 0; c < 2 * B - 1; ++c) acc[c] = 0;
+#pragma unroll
+    for (int i = 0; i < B; ++i)
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+#pragma unroll
+            for (int w = 0; w < WC; ++w) acc[i + j] += __builtin_popcount(x[i][w] ^ y[j][w]);
+    uint32_t D = acc[2 * B - 2];
+#pragma unroll
+    for (int c = 2 * B - 3; c >= 0; --c) D = (D << 1) + acc[c];
+    return D;
+}
+
+// ---------------------------------------------------------------------------------------
+// Register-resident scan.  grid.x: groups of 4*R bundles, grid.y: query ranges.
+// ---------------------------------------------------------------------------------------
+template <int B, int W, int R, bool DENSE>
+__global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
+{
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int64_t bundle0 = a.row_begin / kLanes + (static_cast<int64_t>(blockIdx.x) * 4 + wave) * R;
+    if (bundle0 * kLanes >= a.row_end) return;
+    const int64_t last_bundle = (a.n - 1) / kLanes;
+
+    uint32_t x[R][B][W];
+    uint32_t row[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t bundle = bundle0 + r;
+        const int64_t ld = bundle <= last_bundle ? bundle : last_bundle;   // stay inside the buffer
+        const uint32_t* p = a.db + ld * (B * W * kLanes) + lane;
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+#pragma unroll
+            for (int w = 0; w < W; ++w) x[r][b][w] = p[(b * W + w) * kLanes];
+        row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
+    }
+
+    const int q0 = blockIdx.y * a.qsplit;
+    const int q1 = q0 + a.qsplit < a.m ? q0 + a.qsplit : a.m;
+    for (int q = q0; q < q1; ++q) {
+        uniform_ptr yq = (uniform_ptr)(a.q + static_cast<size_t>(q) * (B * W));
+        uint32_t y[B][W];
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+#pragma unroll
+            for (int w = 0; w < W; ++w) y[b][w] = yq[b * W + w];
+        uint32_t D[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) D[r] = xor_popcount<B, W>(x[r], y);
+
+        if (DENSE) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (row[r] < a.row_end)
+                    a.dense[static_cast<size_t>(q) * a.dense_stride + (row[r] - a.row_begin)] = D[r];
+        } else {
+            const uint32_t t = ((uniform_ptr)a.thr)[q];
+            bool any = false;
+#pragma unroll
+            for (int r = 0; r < R; ++r) any |= D[r] < t;
+            if (__builtin_expect(__ballot(any) != 0, 0)) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    emit(D[r] < t && row[r] < a.row_end, D[r], row[r], q, a.cnt, a.cand, a.cap);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Word-chunked scan.  Queries come from the chunk-major padded copy [m][nchunks][B][WC],
+// so the B*WC words a (query, chunk) step needs are contiguous.  Words past W are zero on
+// both sides and add nothing to D.
+// ---------------------------------------------------------------------------------------
+template <int B, int WC, bool DENSE>
+__global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
+{
+    constexpr int TQ = kTileQ;
+    const int lane = lane_id();
+    const int wave = threadIdx.x >> 6;
+    const int64_t bundle = a.row_begin / kLanes + static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    if (bundle * kLanes >= a.row_end) return;
+    const int W = a.W;
+    const uint32_t* xb = a.db + bundle * (static_cast<int64_t>(B) * W * kLanes) + lane;
+    const uint32_t row = static_cast<uint32_t>(bundle * kLanes + lane);
+    const bool valid = row < a.row_end;
+
+    const int q0 = blockIdx.y * a.qsplit;
+    const int q1 = q0 + a.qsplit < a.m ? q0 + a.qsplit : a.m;
+    for (int qt = q0; qt < q1; qt += TQ) {
+        uint32_t acc[TQ];
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) acc[t] = 0;
+        for (int c = 0; c < a.nchunks; ++c) {
+            uint32_t x[B][WC];
+#pragma unroll
+            for (int b = 0; b < B; ++b)
+#pragma unroll
+                for (int w = 0; w < WC; ++w) {
+                    const int ww = c * WC + w;
+                    x[b][w] = ww < W ? xb[(b * W + ww) * kLanes] : 0u;
+                }
+#pragma unroll
+            for (int t = 0; t < TQ; ++t) {
+                const int q = qt + t < a.m ? qt + t : a.m - 1;     // clamp: tail tiles reread the last query
+                uniform_ptr yq = (uniform_ptr)(a.q + (static_cast<size_t>(q) * a.nchunks + c) * (B * WC));
+                uint32_t y[B][WC];
+#pragma unroll
+                for (int b = 0; b < B; ++b)
+#pragma unroll
+                    for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
+                acc[t] += xor_popcount<B, WC>(x, y);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) {
+            const int q = qt + t;
+            if (q < q1) {
+                if (DENSE) {
+                    if (valid) a.dense[static_cast<size_t>(q) * a.dense_stride + (row - a.row_begin)] = acc[t];
+                } else {
+                    const uint32_t thr = ((uniform_ptr)a.thr)[q];
+                    emit(acc[t] < thr && valid, acc[t], row, q, a.cnt, a.cand, a.cap);
+                }
+            }
+        }
+    }
+}
+
+// XBQ_ROWS [m][B][W] -> chunk-major padded [m][nchunks][B][WC]; words past W become zero.
+__global__ void repack_queries(const uint32_t* __restrict__ src, int m, int B, int W, int wc, int nchunks,
+                               uint32_t* __restrict__ dst)
+{
+    const int64_t per = static_cast<int64_t>(nchunks) * B * wc;
+    const int64_t total = static_cast<int64_t>(m) * per;
+    for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < total;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        const int64_t q = i / per;
+        int rem = static_cast<int>(i - q * per);
+        const int c = rem / (B * wc);
+        rem -= c * B * wc;
+        const int b = rem / wc;
+        const int w = c * wc + (rem - b * wc);
+        dst[i] = w < W ? src[(q * B + b) * W + w] : 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Dispatch
+// ---------------------------------------------------------------------------------------
+bool scan_is_resident(int bits, int W) { return bits >= 1 && bits <= XBQ_MAX_BITS && W >= 1 && W <= 8; }
+
+int scan_chunk_words(int W)
+{
+    int best = 8, best_padded = 1 << 30;
+    for (int wc = 5; wc <= 8; ++wc) {
+        const int padded = (W + wc - 1) / wc * wc;
+        if (padded <= best_padded) { best_padded = padded; best = wc; }
+    }
+    return best;
+}
+
+template <int B, int W, int R>
+static hipError_t launch_resident_brw(const ScanArgs& a, bool dense, dim3 grid, hipStream_t s)
+{
+    if (dense) hipLaunchKernelGGL((scan_resident<B, W, R, true>), grid, dim3(kBlock), 0, s, a);
+    else       hipLaunchKernelGGL((scan_resident<B, W, R, false>), grid, dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int B, int W>
+static hipError_t launch_resident_bw(const ScanArgs& a, bool dense, int64_t bundles, int qranges, hipStream_t s)
+{
+    if constexpr (B * W <= 16) {
+        if (a.rows_per_lane == 2) {
+            dim3 grid(static_cast<unsigned>((bundles + 7) / 8), static_cast<unsigned>(qranges));
+            return launch_resident_brw<B, W, 2>(a, dense, grid, s);
+        }
+    }
+    dim3 grid(static_cast<unsigned>((bundles + 3) / 4), static_cast<unsigned>(qranges));
+    return launch_resident_brw<B, W, 1>(a, dense, grid, s);
+}
+
+template <int B>
+static hipError_t launch_resident_b(const ScanArgs& a, bool dense, int64_t bundles, int qranges, hipStream_t s)
+{
+    switch (a.W) {
+    case 1: return launch_resident_bw<B, 1>(a, dense, bundles, qranges, s);
+    case 2: return launch_resident_bw<B, 2>(a, dense, bundles, qranges, s);
+    case 3: return launch_resident_bw<B, 3>(a, dense, bundles, qranges, s);
+    case 4: return launch_resident_bw<B, 4>(a, dense, bundles, qranges, s);
+    case 5: return launch_resident_bw<B, 5>(a, dense, bundles, qranges, s);
+    case 6: return launch_resident_bw<B, 6>(a, dense, bundles, qranges, s);
+    case 7: return launch_resident_bw<B, 7>(a, dense, bundles, qranges, s);
+    case 8: return launch_resident_bw<B, 8>(a, dense, bundles, qranges, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <int B, int WC>
+static hipError_t launch_chunked_bw(const ScanArgs& a, bool dense, dim3 grid, hipStream_t s)
+{
+    if (dense) hipLaunchKernelGGL((scan_chunked<B, WC, true>), grid, dim3(kBlock), 0, s, a);
+    else       hipLaunchKernelGGL((scan_chunked<B, WC, false>), grid, dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int B>
+static hipError_t launch_chunked_b(const ScanArgs& a, bool dense, dim3 grid, hipStream_t s)
+{
+    switch (a.wc) {
+    case 5: return launch_chunked_bw<B, 5>(a, dense, grid, s);
+    case 6: return launch_chunked_bw<B, 6>(a, dense, grid, s);
+    case 7: return launch_chunked_bw<B, 7>(a, dense, grid, s);
+    case 8: return launch_chunked_bw<B, 8>(a, dense, grid, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_scan(int bits, const ScanArgs& a, bool dense, hipStream_t s)
+{
+    if (a.row_end <= a.row_begin || a.m <= 0) return hipSuccess;
+    if (a.row_begin % kLanes != 0 || a.qsplit < 1) return hipErrorInvalidValue;
+    const int64_t bundles = (a.row_end - a.row_begin + kLanes - 1) / kLanes;
+    const int qranges = (a.m + a.qsplit - 1) / a.qsplit;
+    if (qranges > 65535) return hipErrorInvalidValue;
+    if (a.wc == 0) {
+        switch (bits) {
+        case 1: return launch_resident_b<1>(a, dense, bundles, qranges, s);
+        case 2: return launch_resident_b<2>(a, dense, bundles, qranges, s);
+        case 3: return launch_resident_b<3>(a, dense, bundles, qranges, s);
+        case 4: return launch_resident_b<4>(a, dense, bundles, qranges, s);
+        default: return hipErrorInvalidValue;
+        }
+    }
+    dim3 grid(static_cast<unsigned>((bundles + 3) / 4), static_cast<unsigned>(qranges));
+    switch (bits) {
+    case 1: return launch_chunked_b<1>(a, dense, grid, s);
+    case 2: return launch_chunked_b<2>(a, dense, grid, s);
+    case 3: return launch_chunked_b<3>(a, dense, grid, s);
+    case 4: return launch_chunked_b<4>(a, dense, grid, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_repack_queries(const uint32_t* q_rows, int m, int bits, int W, int wc, int nchunks,
+                                 uint32_t* q_chunked, hipStream_t s)
+{
+    if (m <= 0) return hipSuccess;
+    const int64_t total = static_cast<int64_t>(m) * nchunks * bits * wc;
+    const int blocks = static_cast<int>((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(repack_queries, dim3(blocks), dim3(256), 0, s, q_rows, m, bits, W, wc, nchunks, q_chunked);
+    return hipGetLastError();
+}
+
+}  // namespace xbq

@@ -18,6 +18,8 @@ descriptors.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -98,12 +100,21 @@ def rows(w: Workload, stream: int, start: int, stop: int) -> np.ndarray:
         raise ValueError("row range outside the workload")
     mix = _centres(w) if w.kind == "mixture" else None
     out = np.empty((stop - start, w.d), dtype=np.float32)
-    for i in range(start // BLOCK, (max(stop, 1) - 1) // BLOCK + 1):
+
+    def fill(i):
         lo, hi = i * BLOCK, min((i + 1) * BLOCK, total)
         blk = _block(w, stream, i, hi - lo, mix)
         a, b = max(lo, start), min(hi, stop)
         if a < b:
             out[a - start:b - start] = blk[a - lo:b - lo]
+
+    blocks = range(start // BLOCK, (max(stop, 1) - 1) // BLOCK + 1)
+    if len(blocks) > 1:          # blocks are independent: generate them on a few threads
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+            list(pool.map(fill, blocks))
+    else:
+        for i in blocks:
+            fill(i)
     return out
 
 

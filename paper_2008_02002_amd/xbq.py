@@ -1,0 +1,146 @@
+"""ctypes binding of libxbq.so: same names as the C ABI in ``include/xbq.h``.
+
+Argument marshalling only.  Tensors are torch CUDA tensors used as device memory; the
+current torch stream is handed to the library.  Every step of the path runs in the HIP
+kernels behind the C ABI; there is no CPU fallback, and a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libxbq.so")
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+ROWS, BUNDLE64 = 0, 1
+MAX_BITS, MAX_DIM, MAX_K = 4, 2048, 1024
+
+EXPORTS = (
+    "xbq_version", "xbq_strerror", "xbq_last_hip_error", "xbq_code_bytes", "xbq_encode",
+    "xbq_search_workspace_bytes", "xbq_search", "xbq_trace_enable", "xbq_trace_read",
+    "xbq_set_option",
+)
+
+_lib = None
+
+
+class XbqError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().xbq_strerror(code).decode()
+        if code == EHIP:
+            msg += f" (hipError {lib().xbq_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libxbq.so (built by ``python -m paper_2008_02002_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2008_02002_amd.build`; "
+                "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, i32, vp, f32, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
+        L.xbq_version.restype = i32
+        L.xbq_strerror.argtypes = [i32]
+        L.xbq_strerror.restype = ctypes.c_char_p
+        L.xbq_last_hip_error.restype = i32
+        L.xbq_code_bytes.argtypes = [i64, i32, i32, i32]
+        L.xbq_code_bytes.restype = sz
+        L.xbq_encode.argtypes = [vp, i64, i32, i32, f32, i32, vp, vp]
+        L.xbq_encode.restype = i32
+        L.xbq_search_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
+        L.xbq_search_workspace_bytes.restype = sz
+        L.xbq_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.xbq_search.restype = i32
+        L.xbq_trace_enable.argtypes = [i32]
+        L.xbq_trace_enable.restype = i32
+        L.xbq_trace_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64),
+                                     ctypes.POINTER(ctypes.c_double)]
+        L.xbq_trace_read.restype = i32
+        L.xbq_set_option.argtypes = [ctypes.c_char_p, ctypes.c_double]
+        L.xbq_set_option.restype = i32
+        _lib = L
+    return _lib
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(code: int, where: str):
+    if code != OK:
+        raise XbqError(code, where)
+
+
+def xbq_version() -> int:
+    return lib().xbq_version()
+
+
+def xbq_code_bytes(n: int, d: int, bits: int, layout: int) -> int:
+    return lib().xbq_code_bytes(n, d, bits, layout)
+
+
+def xbq_search_workspace_bytes(n: int, m: int, d: int, bits: int, k: int) -> int:
+    return lib().xbq_search_workspace_bytes(n, m, d, bits, k)
+
+
+def xbq_set_option(name: str, value: float):
+    _check(lib().xbq_set_option(name.encode(), float(value)), "xbq_set_option")
+
+
+def xbq_encode(X, bits: int, scale: float = 1.0, layout: int = ROWS, out=None):
+    """X: fp32 CUDA tensor [n, d] (contiguous).  Returns an int32 CUDA tensor holding the
+    uint32 plane words (flat, xbq_code_bytes / 4 elements)."""
+    import torch
+    if not (X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and X.dim() == 2):
+        raise ValueError("X must be a contiguous fp32 CUDA tensor [n, d]")
+    n, d = X.shape
+    nbytes = xbq_code_bytes(n, d, bits, layout)
+    if nbytes == 0 and n != 0:
+        raise XbqError(EUNSUPPORTED, "xbq_code_bytes")
+    if out is None:
+        out = torch.empty(nbytes // 4, dtype=torch.int32, device=X.device)
+    elif not (out.is_cuda and out.is_contiguous() and out.numel() * out.element_size() >= nbytes):
+        raise ValueError("out too small")
+    rc = lib().xbq_encode(ctypes.c_void_p(X.data_ptr()), n, d, bits, scale, layout,
+                          ctypes.c_void_p(out.data_ptr()), _stream())
+    _check(rc, "xbq_encode")
+    return out
+
+
+def xbq_search(db_codes, n: int, q_codes, m: int, d: int, bits: int, k: int, workspace=None,
+               idx=None, score=None):
+    """Returns (idx int32 [m, k], score int32 [m, k]) CUDA tensors."""
+    import torch
+    dev = db_codes.device
+    need = xbq_search_workspace_bytes(n, m, d, bits, k)
+    if need == 0:
+        raise XbqError(EINVAL, "xbq_search_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    if idx is None:
+        idx = torch.empty((m, k), dtype=torch.int32, device=dev)
+    if score is None:
+        score = torch.empty((m, k), dtype=torch.int32, device=dev)
+    rc = lib().xbq_search(ctypes.c_void_p(db_codes.data_ptr()), n, ctypes.c_void_p(q_codes.data_ptr()), m,
+                          d, bits, k, ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(score.data_ptr()),
+                          ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                          _stream())
+    _check(rc, "xbq_search")
+    return idx, score
+
+
+def xbq_trace_enable(on: bool):
+    _check(lib().xbq_trace_enable(1 if on else 0), "xbq_trace_enable")
+
+
+def xbq_trace_read():
+    """(scan kernel milliseconds, launches, pairs scored) since the last read."""
+    ms, n, pairs = ctypes.c_double(), ctypes.c_int64(), ctypes.c_double()
+    _check(lib().xbq_trace_read(ctypes.byref(ms), ctypes.byref(n), ctypes.byref(pairs)), "xbq_trace_read")
+    return ms.value, n.value, pairs.value

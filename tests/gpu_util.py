@@ -1,0 +1,72 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C-ABI binding and the
+oracle on the same inputs.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import scale as oc
+from paper_2008_02002_amd import xbq
+
+
+def to_dev(a: np.ndarray):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def gpu_encode(X: np.ndarray, bits: int, scale: float, layout: int) -> np.ndarray:
+    """uint32 plane words as the library wrote them (flat)."""
+    import torch
+    codes = xbq.xbq_encode(to_dev(X.astype(np.float32)), bits, scale, layout)
+    torch.cuda.synchronize()
+    return codes.cpu().numpy().view(np.uint32)
+
+
+def bundle_as_rows(flat: np.ndarray, n: int, bits: int, W: int) -> np.ndarray:
+    """[ceil(n/64)][bits][W][64] -> [ceil(n/64)*64][bits][W] (pure re-indexing)."""
+    nb = (n + 63) // 64
+    return np.ascontiguousarray(flat.reshape(nb, bits, W, 64).transpose(0, 3, 1, 2).reshape(nb * 64, bits, W))
+
+
+def oracle_rows(X: np.ndarray, bits: int, scale: float) -> np.ndarray:
+    return oc.planes_as_u32(oc.encode(X, bits, scale), X.shape[1])
+
+
+def gpu_search(Xdb: np.ndarray, Xq: np.ndarray, bits: int, k: int, scale: float):
+    """Encode both sides on the GPU and search; returns numpy (idx, score) and the device codes."""
+    import torch
+    n, d = Xdb.shape
+    m = Xq.shape[0]
+    db = xbq.xbq_encode(to_dev(Xdb), bits, scale, xbq.BUNDLE64)
+    q = xbq.xbq_encode(to_dev(Xq), bits, scale, xbq.ROWS)
+    idx, score = xbq.xbq_search(db, n, q, m, d, bits, k)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), score.cpu().numpy()
+
+
+def oracle_search(Xdb: np.ndarray, Xq: np.ndarray, bits: int, k: int, scale: float):
+    d = Xdb.shape[1]
+    return oc.search(oc.encode(Xdb, bits, scale), oc.encode(Xq, bits, scale), d, k)
+
+
+def assert_same(got, want, what=""):
+    gi, gs = got
+    wi, ws = want
+    if not np.array_equal(gs, ws):
+        bad = np.argwhere(gs != ws)
+        raise AssertionError(f"{what}: {len(bad)} score mismatches, first at {bad[0]}: "
+                             f"gpu {gs[tuple(bad[0])]} oracle {ws[tuple(bad[0])]}")
+    if not np.array_equal(gi, wi):
+        bad = np.argwhere(gi != wi)
+        raise AssertionError(f"{what}: {len(bad)} index mismatches, first at {bad[0]}: "
+                             f"gpu {gi[tuple(bad[0])]} oracle {wi[tuple(bad[0])]}")
+
+
+def check_order_properties(idx: np.ndarray, score: np.ndarray, n: int):
+    """What holds at any size: rows in range and distinct, (score desc, idx asc) order."""
+    assert idx.min() >= 0 and idx.max() < n
+    srt = np.sort(idx, axis=1)
+    assert (srt[:, 1:] != srt[:, :-1]).all(), "duplicate row in a result"
+    ds = np.diff(score.astype(np.int64), axis=1)
+    assert (ds <= 0).all(), "scores not descending"
+    di = np.diff(idx.astype(np.int64), axis=1)
+    assert (di[ds == 0] > 0).all(), "tie not broken by lower index"

@@ -1,0 +1,124 @@
+"""Host-only checks of the C-ABI library: it loads, exports what the header declares,
+and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2008_02002_amd import xbq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(xbq.LIB_PATH):
+        from paper_2008_02002_amd.build import build_library
+        build_library(verbose=False)
+    return xbq.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    header = open(os.path.join(ROOT, "include", "xbq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(xbq_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(xbq.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_version_and_strerror(L):
+    assert L.xbq_version() >= 100
+    assert L.xbq_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(L.xbq_strerror(code)) > 0
+
+
+def test_code_bytes(L):
+    assert L.xbq_code_bytes(1000, 128, 4, xbq.ROWS) == 1000 * 4 * 4 * 4
+    assert L.xbq_code_bytes(1000, 128, 4, xbq.BUNDLE64) == 1024 * 4 * 4 * 4      # 16 bundles
+    assert L.xbq_code_bytes(64, 200, 3, xbq.BUNDLE64) == 64 * 3 * 7 * 4
+    assert L.xbq_code_bytes(0, 128, 4, xbq.ROWS) == 0
+    assert L.xbq_code_bytes(10, 128, 5, xbq.ROWS) == 0                           # bits out of range
+    assert L.xbq_code_bytes(10, 0, 4, xbq.ROWS) == 0
+    assert L.xbq_code_bytes(10, 4096, 4, xbq.ROWS) == 0
+    assert L.xbq_code_bytes(10, 128, 4, 7) == 0
+    assert L.xbq_code_bytes(-1, 128, 4, xbq.ROWS) == 0
+
+
+def test_encode_argument_errors(L):
+    fake = ctypes.c_void_p(0x1000)      # never dereferenced: validation fails first
+    null = ctypes.c_void_p(0)
+    enc = L.xbq_encode
+    assert enc(null, 10, 128, 4, 1.0, xbq.ROWS, fake, null) == xbq.EINVAL
+    assert enc(fake, 10, 128, 4, 1.0, xbq.ROWS, null, null) == xbq.EINVAL
+    assert enc(fake, -1, 128, 4, 1.0, xbq.ROWS, fake, null) == xbq.EINVAL
+    assert enc(fake, 10, 0, 4, 1.0, xbq.ROWS, fake, null) == xbq.EINVAL
+    assert enc(fake, 10, 128, 0, 1.0, xbq.ROWS, fake, null) == xbq.EINVAL
+    assert enc(fake, 10, 128, 5, 1.0, xbq.ROWS, fake, null) == xbq.EUNSUPPORTED
+    assert enc(fake, 10, 4096, 4, 1.0, xbq.ROWS, fake, null) == xbq.EUNSUPPORTED
+    assert enc(fake, 10, 128, 4, 1.0, 9, fake, null) == xbq.EUNSUPPORTED
+    assert enc(fake, 10, 128, 4, 0.0, xbq.ROWS, fake, null) == xbq.EINVAL
+    assert enc(fake, 10, 128, 4, -1.0, xbq.ROWS, fake, null) == xbq.EINVAL
+    assert enc(fake, 10, 128, 4, float("inf"), xbq.ROWS, fake, null) == xbq.EINVAL
+    assert enc(fake, 10, 128, 4, float("nan"), xbq.ROWS, fake, null) == xbq.EINVAL
+    assert enc(ctypes.c_void_p(0x1002), 10, 128, 4, 1.0, xbq.ROWS, fake, null) == xbq.EINVAL   # misaligned
+    assert enc(null, 0, 128, 4, 1.0, xbq.ROWS, null, null) == xbq.OK                           # n = 0: no-op
+
+
+def test_search_argument_errors(L):
+    fake = ctypes.c_void_p(0x1000)
+    null = ctypes.c_void_p(0)
+    big = 1 << 40
+
+    def s(db=fake, n=1000, q=fake, m=10, d=128, bits=4, k=10, idx=fake, score=fake, ws=fake, wsb=big):
+        return L.xbq_search(db, n, q, m, d, bits, k, idx, score, ws, wsb, null)
+
+    assert s(db=null) == xbq.EINVAL
+    assert s(q=null) == xbq.EINVAL
+    assert s(idx=null) == xbq.EINVAL
+    assert s(score=null) == xbq.EINVAL
+    assert s(ws=null) == xbq.EINVAL
+    assert s(k=0) == xbq.EINVAL
+    assert s(k=1001) == xbq.EINVAL                  # k > n
+    assert s(n=5000, k=1025) == xbq.EINVAL          # k > XBQ_MAX_K
+    assert s(n=-1) == xbq.EINVAL
+    assert s(m=-1) == xbq.EINVAL
+    assert s(n=1 << 31) == xbq.EINVAL
+    assert s(bits=5) == xbq.EUNSUPPORTED
+    assert s(d=2049) == xbq.EUNSUPPORTED
+    assert s(d=0) == xbq.EINVAL
+    assert s(ws=ctypes.c_void_p(0x1010)) == xbq.EINVAL          # workspace not 256-byte aligned
+    need = L.xbq_search_workspace_bytes(1000, 10, 128, 4, 10)
+    assert need > 0
+    assert s(wsb=need - 1) == xbq.EWORKSPACE
+    assert s(n=0) == xbq.OK and s(m=0) == xbq.OK                # empty inputs are no-ops
+
+
+def test_workspace_bytes(L):
+    f = L.xbq_search_workspace_bytes
+    assert f(1000, 10, 128, 4, 0) == 0
+    assert f(1000, 10, 128, 4, 1001) == 0
+    assert f(1000, 10, 128, 9, 10) == 0
+    a = f(1_000_000, 10_000, 128, 4, 100)
+    b = f(10_000_000, 10_000, 128, 4, 100)
+    assert a == b and 0 < a < (1 << 30)             # independent of n once n is large
+    assert f(1_000_000, 1_000_000, 128, 4, 100) < (1 << 30)      # bounded in m (internal batches)
+    assert f(1_000_000, 1000, 960, 4, 10) > f(1_000_000, 1000, 128, 4, 10)   # repacked queries
+
+
+def test_options(L):
+    assert L.xbq_set_option(b"growth", 2.0) == xbq.OK
+    assert L.xbq_set_option(b"growth", 1.0) == xbq.EINVAL
+    assert L.xbq_set_option(b"nonsense", 1.0) == xbq.EINVAL
+    assert L.xbq_set_option(None, 1.0) == xbq.EINVAL
+    assert L.xbq_set_option(b"first", 1024) == xbq.OK
+    assert L.xbq_set_option(b"qsplit", 0) == xbq.OK
+
+
+def test_missing_library_is_loud(monkeypatch):
+    monkeypatch.setattr(xbq, "_lib", None)
+    monkeypatch.setattr(xbq, "LIB_PATH", "/nonexistent/libxbq.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        xbq.lib()

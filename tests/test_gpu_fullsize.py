@@ -1,0 +1,86 @@
+"""Parity at the full benchmark sizes, in the launch configuration the benchmark times.
+
+The oracle cannot score every query of the large workloads in the time a test may
+take, so each workload is checked three ways: (1) a fixed subset of queries (first and
+last ones) searched by the oracle over the whole database, compared bit for bit;
+(2) for every query, every returned (row, score) pair re-scored by the oracle;
+(3) for every query, the order properties that hold at any size.
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import scale as oc
+from paper_2008_02002_amd import workloads as wl
+from paper_2008_02002_amd import xbq
+from tests import gpu_util as gu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _run(name, bits, ks, oracle_queries):
+    import torch
+    w = wl.WORKLOADS[name]
+    t0 = time.time()
+    Xq = wl.queries(w)
+    scale = wl.workload_scale(w)
+    # encode the database in slabs so the fp32 rows never sit in memory all at once
+    slab = 1 << 20
+    nb = xbq.xbq_code_bytes(w.n, w.d, bits, xbq.BUNDLE64)
+    db = torch.empty(nb // 4, dtype=torch.int32, device="cuda")
+    W = (w.d + 31) // 32
+    planes = np.empty((w.n, bits, (w.d + 63) // 64), dtype=np.uint64)
+    for lo in range(0, w.n, slab):
+        hi = min(w.n, lo + slab)
+        X = wl.database(w, lo, hi)
+        xbq.xbq_encode(torch.from_numpy(X).cuda(), bits, scale, xbq.BUNDLE64,
+                       out=db[lo // 64 * 64 * bits * W:])
+        planes[lo:hi] = oc.encode(X, bits, scale)
+        _say(f"{name}: rows {lo}..{hi} generated and encoded ({time.time() - t0:.0f}s)")
+    q = xbq.xbq_encode(torch.from_numpy(Xq).cuda(), bits, scale, xbq.ROWS)
+    qplanes = oc.encode(Xq, bits, scale)
+    # database codes themselves: compare a strided sample of bundles
+    got = db.cpu().numpy().view(np.uint32).reshape(-1, bits, W, 64)
+    for b in range(0, got.shape[0], max(1, got.shape[0] // 97)):
+        rows = slice(b * 64, min(w.n, b * 64 + 64))
+        want = oc.planes_as_u32(planes[rows], w.d)
+        assert np.array_equal(got[b].transpose(2, 0, 1)[:want.shape[0]], want), f"bundle {b}"
+    sub = np.unique(np.concatenate([np.arange(oracle_queries // 2), w.m - 1 - np.arange(oracle_queries // 2)]))
+    for k in ks:
+        idx, score = xbq.xbq_search(db, w.n, q, w.m, w.d, bits, k)
+        torch.cuda.synchronize()
+        idx, score = idx.cpu().numpy(), score.cpu().numpy()
+        _say(f"{name}: bits={bits} k={k} searched on the GPU ({time.time() - t0:.0f}s)")
+        gu.check_order_properties(idx, score, w.n)
+        qi = np.repeat(np.arange(w.m), k)
+        assert np.array_equal(oc.scores_at(planes, qplanes, w.d, qi, idx.ravel()), score.ravel())
+        ridx, rscore = oc.search(planes, qplanes[sub], w.d, k)
+        _say(f"{name}: oracle searched {len(sub)} queries ({time.time() - t0:.0f}s)")
+        gu.assert_same((idx[sub], score[sub]), (ridx, rscore), f"{name} bits={bits} k={k}")
+
+
+def test_c2_full_size():
+    _run("C2", 4, (100,), 400)
+
+
+def test_c3_full_size_3bit():
+    _run("C3", 3, (10,), 40)
+
+
+def test_c3_full_size_4bit():
+    _run("C3", 4, (10,), 40)
+
+
+def test_c4_full_size():
+    _run("C4", 3, (10, 100), 200)
+
+
+def test_c5_full_size():
+    _run("C5", 4, (100,), 60)

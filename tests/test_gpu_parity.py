@@ -1,0 +1,229 @@
+"""GPU parity: the HIP path (through the C-ABI binding) against the CPU oracle, bit-exact.
+
+Codes, integer scores and top-K rows must be identical; ties go to the lower row.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import definition as od
+from oracle import scale as oc
+from paper_2008_02002_amd import workloads as wl
+from paper_2008_02002_amd import xbq
+from tests import gpu_util as gu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    xbq.lib()
+    yield
+
+
+def _rand(n, d, seed, lo=-0.5, hi=0.5):
+    return np.random.default_rng(seed).uniform(lo, hi, size=(n, d)).astype(np.float32)
+
+
+# ----------------------------------------------------------------------------- encode
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("n,d", [(1, 1), (5, 31), (64, 32), (65, 33), (130, 64), (257, 65), (300, 96),
+                                 (1000, 128), (513, 200), (200, 960), (70, 2048), (3, 1000)])
+def test_encode_matches_oracle(bits, n, d):
+    _say(f"encode bits={bits} n={n} d={d}")
+    X = _rand(n, d, seed=bits * 7919 + n * 31 + d)
+    for scale in (1.0, 2.95):
+        want = gu.oracle_rows(X, bits, scale)
+        W = (d + 31) // 32
+        got_rows = gu.gpu_encode(X, bits, scale, xbq.ROWS).reshape(n, bits, W)
+        assert np.array_equal(got_rows, want)
+        got_b = gu.bundle_as_rows(gu.gpu_encode(X, bits, scale, xbq.BUNDLE64), n, bits, W)
+        assert np.array_equal(got_b[:n], want)
+        assert (got_b[n:] == 0).all()                      # rows past n in the last bundle are zero words
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+def test_encode_cell_boundaries_denormals_and_saturation(bits):
+    pts = []
+    for k in range(-(1 << bits) - 2, (1 << bits) + 3):
+        c = np.float32(k / float(1 << bits))
+        pts += [c, np.nextafter(c, np.float32(9)), np.nextafter(c, np.float32(-9))]
+    pts += [0.0, -0.0, 1e-45, -1e-45, 1e-39, -1e-39, 1.1754944e-38, -1.1754944e-38, 3e38, -3e38,
+            np.inf, -np.inf, 0.99999994, -0.99999994, 123.0, -123.0]
+    X = np.array(pts, dtype=np.float32)
+    X = np.concatenate([X, np.zeros((-len(X)) % 8, np.float32)]).reshape(-1, 8)
+    for scale in (1.0, 1.0000001, 3.0, 0.33333334, 2.95):
+        want = gu.oracle_rows(X, bits, scale)
+        got = gu.gpu_encode(X, bits, scale, xbq.ROWS).reshape(want.shape)
+        assert np.array_equal(got, want), (bits, scale)
+    # a product that only lands on the cell boundary after rounding to binary32
+    x = np.full((4, 16), np.float32(0.083333336))
+    assert np.array_equal(gu.gpu_encode(x, bits, 3.0, xbq.ROWS).reshape(4, bits, 1), gu.oracle_rows(x, bits, 3.0))
+
+
+def test_encode_random_bits_sweep():
+    # every fp32 bit pattern class: random words reinterpreted as floats (NaN removed)
+    rng = np.random.default_rng(99)
+    raw = rng.integers(0, 1 << 32, size=200_000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    raw = raw[np.isfinite(raw)][:160_000].reshape(-1, 160)
+    small = (rng.standard_normal((500, 160)) * 0.3).astype(np.float32)
+    X = np.concatenate([raw, small])
+    for bits in (3, 4):
+        want = gu.oracle_rows(X, bits, 1.7)
+        got = gu.gpu_encode(X, bits, 1.7, xbq.ROWS).reshape(want.shape)
+        assert np.array_equal(got, want)
+
+
+# ----------------------------------------------------------------------------- search
+SMALL = [
+    # n, d, m, bits, k
+    (1, 8, 3, 4, 1),
+    (63, 16, 5, 4, 10),
+    (64, 128, 7, 4, 64),
+    (65, 128, 7, 3, 65),
+    (1000, 128, 33, 4, 10),
+    (1024, 128, 9, 4, 100),
+    (1025, 128, 9, 4, 100),
+    (4097, 128, 17, 4, 100),
+    (5000, 96, 40, 4, 100),
+    (5000, 200, 40, 3, 10),
+    (5000, 200, 40, 3, 100),
+    (20000, 128, 100, 4, 1),
+    (20000, 128, 50, 4, 1024),
+    (9000, 64, 30, 2, 50),
+    (9000, 32, 30, 1, 50),
+    (7000, 256, 20, 4, 10),
+    (7000, 250, 20, 3, 10),
+    (3000, 960, 24, 3, 10),
+    (3000, 960, 24, 4, 10),
+    (3000, 300, 50, 4, 33),
+    (2000, 2048, 18, 4, 5),
+    (2000, 1000, 18, 2, 5),
+    (2500, 320, 17, 1, 7),
+]
+
+
+@pytest.mark.parametrize("n,d,m,bits,k", SMALL)
+def test_search_matches_oracle_small(n, d, m, bits, k):
+    _say(f"search n={n} d={d} m={m} bits={bits} k={k}")
+    Xdb = _rand(n, d, seed=n + d)
+    Xq = _rand(m, d, seed=n + d + 1)
+    scale = 1.9
+    gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, scale), gu.oracle_search(Xdb, Xq, bits, k, scale),
+                   f"n={n} d={d} bits={bits} k={k}")
+
+
+def test_config_c1_full():
+    w = wl.WORKLOADS["C1"]
+    _say("C1 full")
+    Xdb, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
+    got = gu.gpu_search(Xdb, Xq, 4, 10, scale)
+    gu.assert_same(got, gu.oracle_search(Xdb, Xq, 4, 10, scale), "C1")
+    # and against the definition-level oracle directly
+    ridx, rsc = od.search(Xdb, Xq, 4, 10, scale)
+    assert np.array_equal(got[0], ridx) and np.array_equal(got[1], rsc)
+
+
+@pytest.mark.parametrize("name,n,m", [("C2", 150_000, 200), ("C3", 40_000, 64), ("C4", 200_000, 150),
+                                      ("C5", 300_000, 150)])
+def test_configs_scaled_down(name, n, m):
+    w = wl.scaled_down(wl.WORKLOADS[name], n=n, m=m)
+    Xdb, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
+    for bits in w.bits:
+        for k in w.ks:
+            _say(f"{name} scaled n={n} m={m} bits={bits} k={k}")
+            got = gu.gpu_search(Xdb, Xq, bits, k, scale)
+            gu.assert_same(got, gu.oracle_search(Xdb, Xq, bits, k, scale), f"{name} bits={bits} k={k}")
+            gu.check_order_properties(got[0], got[1], n)
+
+
+def test_all_scores_tied():
+    # non-negative data at scale 1: every coordinate falls in the same cell, all scores equal
+    w = wl.scaled_down(wl.WORKLOADS["C3"], n=30_000, m=16)
+    Xdb, Xq = wl.database(w), wl.queries(w)
+    idx, score = gu.gpu_search(Xdb, Xq, 3, 10, 1.0)
+    gu.assert_same((idx, score), gu.oracle_search(Xdb, Xq, 3, 10, 1.0), "all tied")
+    assert (idx == np.arange(10)[None, :]).all()
+
+
+def test_duplicated_rows_and_few_distinct_scores():
+    base = _rand(500, 24, seed=5)
+    Xdb = np.tile(base, (40, 1))                        # every row occurs 40 times
+    Xq = _rand(12, 24, seed=6)
+    for bits, k in ((1, 100), (2, 257), (4, 64)):
+        gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 1.5), gu.oracle_search(Xdb, Xq, bits, k, 1.5), "dups")
+
+
+def test_rows_sorted_by_similarity_forces_exact_rescan():
+    # later rows are ever closer to the queries: every group floods the candidate lists,
+    # which must overflow and take the exact rescan path
+    rng = np.random.default_rng(17)
+    d, n, m = 64, 40_000, 6
+    target = rng.standard_normal(d).astype(np.float32)
+    target /= np.linalg.norm(target)
+    noise = rng.standard_normal((n, d)).astype(np.float32)
+    amount = np.linspace(3.0, 0.0, n, dtype=np.float32)[:, None]
+    Xdb = target[None, :] + amount * noise / np.sqrt(d)
+    Xdb = (Xdb / np.linalg.norm(Xdb, axis=1, keepdims=True)).astype(np.float32)
+    Xq = target[None, :] + 0.05 * rng.standard_normal((m, d)).astype(np.float32)
+    Xq /= np.linalg.norm(Xq, axis=1, keepdims=True)
+    Xq = Xq.astype(np.float32)
+    for bits, k in ((4, 10), (3, 100), (4, 1024)):
+        _say(f"sorted rows bits={bits} k={k}")
+        gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 3.0), gu.oracle_search(Xdb, Xq, bits, k, 3.0), "sorted")
+
+
+def test_many_queries_cross_the_internal_batch():
+    n, d, m = 3000, 32, 20_000                          # more queries than one internal batch
+    Xdb = _rand(n, d, seed=1)
+    Xq = _rand(m, d, seed=2)
+    gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 5, 2.0), gu.oracle_search(Xdb, Xq, 4, 5, 2.0), "batches")
+
+
+def test_empty_inputs_are_noops():
+    import torch
+    db = torch.zeros(64 * 16, dtype=torch.int32, device="cuda")
+    q = torch.zeros(16, dtype=torch.int32, device="cuda")
+    idx, score = xbq.xbq_search(db, 0, q, 1, 128, 4, 1)
+    idx, score = xbq.xbq_search(db, 64, q, 0, 128, 4, 1)
+    assert idx.shape == (0, 1)
+    out = xbq.xbq_encode(torch.zeros((0, 128), device="cuda"), 4)
+    assert out.numel() == 0
+    torch.cuda.synchronize()
+
+
+def test_options_do_not_change_results():
+    Xdb = _rand(30_000, 128, seed=3)
+    Xq = _rand(64, 128, seed=4)
+    want = gu.oracle_search(Xdb, Xq, 4, 100, 2.0)
+    try:
+        for growth, first, qsplit in ((1.5, 1024, 0), (4.0, 512, 16), (8.0, 4096, 1000), (2.0, 64, 7)):
+            xbq.xbq_set_option("growth", growth)
+            xbq.xbq_set_option("first", first)
+            xbq.xbq_set_option("qsplit", qsplit)
+            gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 100, 2.0), want, f"growth={growth} first={first}")
+    finally:
+        xbq.xbq_set_option("growth", 2.0)
+        xbq.xbq_set_option("first", 1024)
+        xbq.xbq_set_option("qsplit", 0)
+
+
+def test_trace_reports_scan_time():
+    Xdb = _rand(50_000, 128, seed=8)
+    Xq = _rand(256, 128, seed=9)
+    xbq.xbq_trace_enable(True)
+    try:
+        gu.gpu_search(Xdb, Xq, 4, 10, 2.0)
+        ms, launches, pairs = xbq.xbq_trace_read()
+    finally:
+        xbq.xbq_trace_enable(False)
+    assert launches >= 2 and ms > 0
+    assert pairs == 50_000 * 256
