@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--queries", type=int, default=0, help="use only the first N queries")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-recall", action="store_true")
+    ap.add_argument("--set", action="append", default=[], metavar="NAME=VALUE",
+                    help="library tuning option (xbq_set_option), e.g. --set growth=4")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one process, one device, no collectives); "
@@ -99,6 +101,9 @@ def main():
     k = args.k or w.ks[-1]
     torch.cuda.set_device(0)
     xbq.lib()
+    for kv in args.set:
+        name, value = kv.split("=")
+        xbq.xbq_set_option(name, float(value))
 
     scale = wl.workload_scale(w)
     Xq = torch.from_numpy(wl.queries(w)).cuda()
@@ -167,7 +172,7 @@ def main():
         "dtype": "u32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: n={w.n} d={w.d} m={w.m} bits={bits} K={k} ({w.kind}, seed {w.seed})",
-                   "scale": scale},
+                   "scale": scale, "options": args.set},
         "roofline": {
             "bound": "alu",
             "kernel": "scan (XOR + population count), all launches of one step",

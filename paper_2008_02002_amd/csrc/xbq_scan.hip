@@ -42,19 +42,36 @@ __device__ __forceinline__ void emit(bool pass, uint32_t D, uint32_t row, int q,
     if (pass && pos < static_cast<uint32_t>(cap)) cand[static_cast<size_t>(q) * cap + pos] = make_key(D, row);
 }
 
-// Eq. 6 for one row held in x against the B*WC uniform words y (plane-major, stride ystride).
+// acc + POPCNT(v) in one instruction.  Written as an instruction so the compiler keeps one
+// running sum per weight class; left to itself it re-associates the sums into trees of
+// three-input adds, which costs a fifth more vector instructions.
+__device__ __forceinline__ uint32_t popcount_add(uint32_t v, uint32_t acc)
+{
+    uint32_t r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(v), "v"(acc));
+    return r;
+}
+
+// Eq. 6 for one row held in x against the B*WC uniform words y (both plane-major).
 template <int B, int WC>
 __device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[B][WC], const uint32_t (&y)[B][WC])
 {
     uint32_t acc[2 * B - 1];
 #pragma unroll
-    for (int c = 0; c < 2 * B - 1; ++c) acc[c] = 0;
+    for (int c = 0; c < 2 * B - 1; ++c) {
+        bool first = true;
 #pragma unroll
-    for (int i = 0; i < B; ++i)
+        for (int i = 0; i < B; ++i) {
+            const int j = c - i;
+            if (j < 0 || j >= B) continue;
 #pragma unroll
-        for (int j = 0; j < B; ++j)
-#pragma unroll
-            for (int w = 0; w < WC; ++w) acc[i + j] += __builtin_popcount(x[i][w] ^ y[j][w]);
+            for (int w = 0; w < WC; ++w) {
+                const uint32_t v = x[i][w] ^ y[j][w];
+                acc[c] = first ? static_cast<uint32_t>(__builtin_popcount(v)) : popcount_add(v, acc[c]);
+                first = false;
+            }
+        }
+    }
     uint32_t D = acc[2 * B - 2];
 #pragma unroll
     for (int c = 2 * B - 3; c >= 0; --c) D = (D << 1) + acc[c];
@@ -89,6 +106,7 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
 
     const int q0 = blockIdx.y * a.qsplit;
     const int q1 = q0 + a.qsplit < a.m ? q0 + a.qsplit : a.m;
+    __builtin_amdgcn_s_waitcnt(0);      // row words have landed: no per-load waits inside the loop
     for (int q = q0; q < q1; ++q) {
         uniform_ptr yq = (uniform_ptr)(a.q + static_cast<size_t>(q) * (B * W));
         uint32_t y[B][W];

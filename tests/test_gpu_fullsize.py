@@ -67,20 +67,20 @@ def _run(name, bits, ks, oracle_queries):
 
 
 def test_c2_full_size():
-    _run("C2", 4, (100,), 400)
+    _run("C2", 4, (100,), 1000)
 
 
 def test_c3_full_size_3bit():
-    _run("C3", 3, (10,), 40)
+    _run("C3", 3, (10,), 200)
 
 
 def test_c3_full_size_4bit():
-    _run("C3", 4, (10,), 40)
+    _run("C3", 4, (10,), 200)
 
 
 def test_c4_full_size():
-    _run("C4", 3, (10, 100), 200)
+    _run("C4", 3, (10, 100), 400)
 
 
 def test_c5_full_size():
-    _run("C5", 4, (100,), 60)
+    _run("C5", 4, (100,), 300)
