@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--queries", type=int, default=0, help="use only the first N queries")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-recall", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="run one 256 MiB device-to-device copy first (reference for HBM byte counters)")
     ap.add_argument("--set", action="append", default=[], metavar="NAME=VALUE",
                     help="library tuning option (xbq_set_option), e.g. --set growth=4")
     args = ap.parse_args()
@@ -123,6 +125,12 @@ def main():
         xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
         xbq.xbq_search(db, w.n, q, w.m, w.d, bits, k, workspace=ws, idx=idx, score=score)
 
+    if args.calib_copy:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device="cuda")      # 256 MiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -150,13 +158,14 @@ def main():
     ops = cm.credited_lane_ops_per_pair(w.d, bits, bits) * pairs          # credited XOR + popcount lane-ops
     achieved = ops / (scan_ms * 1e-3) / 1e12
     peak = cm.VALU_INT_LANE_OPS_PER_S / 1e12
+    # HBM-side bytes per scan launch come from the committed rocprofv3 --pmc summary of this
+    # same command (they cannot be read from inside the process)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "scan_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(f"{w.name}_b{bits}_k{k}")
-        except Exception:
-            traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"bench_{w.name}.md")
+    if os.path.exists(tpath) and not args.queries:
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_scan_launch:"):
+                traffic = float(line.split(":")[1])
     out = {
         "metric": "queries/s, 1M x d128 4-bit K=100 (encode + XOR/popcount scan + top-K)"
                   if w.name == "C2" else f"queries/s, {w.name}",

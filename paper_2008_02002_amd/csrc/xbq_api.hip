@@ -114,7 +114,6 @@ int choose_qsplit(int64_t bundles, int rows_per_lane, int m, int tile)
     int qs = static_cast<int>((m + ranges - 1) / ranges);
     if (qs < 16) qs = 16;
     qs = (qs + tile - 1) / tile * tile;
-    if ((m + qs - 1) / qs > 65535) qs = (m + 65534) / 65535;
     return qs;
 }
 

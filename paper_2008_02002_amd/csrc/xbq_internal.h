@@ -32,7 +32,9 @@ struct ScanArgs {
     const uint32_t* q;       // XBQ_ROWS codes (register-resident scan) or chunk-major
                              // padded codes [m][nchunks][B][WC] (word-chunked scan)
     int m;                   // queries in this batch
-    int qsplit;              // queries per workgroup (grid.y = ceil(m / qsplit))
+    int qsplit;              // queries per workgroup
+    int qranges;             // ceil(m / qsplit)            (filled in by launch_scan)
+    int row_blocks;          // row blocks of one workgroup (filled in by launch_scan)
     int W;                   // 32-bit words per plane
     int rows_per_lane;       // 1 or 2 (register-resident scan only)
     int wc;                  // words per chunk, 0 = register-resident scan

@@ -42,6 +42,23 @@ __device__ __forceinline__ void emit(bool pass, uint32_t D, uint32_t row, int q,
     if (pass && pos < static_cast<uint32_t>(cap)) cand[static_cast<size_t>(q) * cap + pos] = make_key(D, row);
 }
 
+// Workgroup -> (row block, query range).  The grid is one-dimensional.  Hardware hands
+// consecutive workgroup ids to the 8 XCDs in turn, each XCD with its own L2, so the id is
+// split as (id % 8, id / 8): XCD c works through row blocks c, c + 8, c + 16, ... and for each
+// of them through all query ranges back to back.  A row block is then fetched from HBM by
+// one XCD only and stays in that L2 while its query ranges run; the (small) query array is
+// what every XCD shares.  If the hardware assigned ids differently the result would be the
+// same, only the locality would be lost.
+constexpr int kXcds = 8;
+__device__ __forceinline__ bool decode_tile(int row_blocks, int qranges, int& row_block, int& qrange)
+{
+    const unsigned id = blockIdx.x;
+    const unsigned xcd = id % kXcds, j = id / kXcds;
+    row_block = static_cast<int>((j / qranges) * kXcds + xcd);
+    qrange = static_cast<int>(j % qranges);
+    return row_block < row_blocks;
+}
+
 // acc + POPCNT(v) in one instruction.  Written as an instruction so the compiler keeps one
 // running sum per weight class; left to itself it re-associates the sums into trees of
 // three-input adds, which costs a fifth more vector instructions.
@@ -79,14 +96,16 @@ __device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[B][WC], con
 }
 
 // ---------------------------------------------------------------------------------------
-// Register-resident scan.  grid.x: groups of 4*R bundles, grid.y: query ranges.
+// Register-resident scan.  One workgroup = 4*R bundles of rows x one query range.
 // ---------------------------------------------------------------------------------------
 template <int B, int W, int R, bool DENSE>
 __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
 {
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
-    const int64_t bundle0 = a.row_begin / kLanes + (static_cast<int64_t>(blockIdx.x) * 4 + wave) * R;
+    int row_block, qrange;
+    if (!decode_tile(a.row_blocks, a.qranges, row_block, qrange)) return;
+    const int64_t bundle0 = a.row_begin / kLanes + (static_cast<int64_t>(row_block) * 4 + wave) * R;
     if (bundle0 * kLanes >= a.row_end) return;
     const int64_t last_bundle = (a.n - 1) / kLanes;
 
@@ -104,7 +123,7 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
         row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
     }
 
-    const int q0 = blockIdx.y * a.qsplit;
+    const int q0 = qrange * a.qsplit;
     const int q1 = q0 + a.qsplit < a.m ? q0 + a.qsplit : a.m;
     __builtin_amdgcn_s_waitcnt(0);      // row words have landed: no per-load waits inside the loop
     for (int q = q0; q < q1; ++q) {
@@ -148,14 +167,16 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
     constexpr int TQ = kTileQ;
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
-    const int64_t bundle = a.row_begin / kLanes + static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    int row_block, qrange;
+    if (!decode_tile(a.row_blocks, a.qranges, row_block, qrange)) return;
+    const int64_t bundle = a.row_begin / kLanes + static_cast<int64_t>(row_block) * 4 + wave;
     if (bundle * kLanes >= a.row_end) return;
     const int W = a.W;
     const uint32_t* xb = a.db + bundle * (static_cast<int64_t>(B) * W * kLanes) + lane;
     const uint32_t row = static_cast<uint32_t>(bundle * kLanes + lane);
     const bool valid = row < a.row_end;
 
-    const int q0 = blockIdx.y * a.qsplit;
+    const int q0 = qrange * a.qsplit;
     const int q1 = q0 + a.qsplit < a.m ? q0 + a.qsplit : a.m;
     for (int qt = q0; qt < q1; qt += TQ) {
         uint32_t acc[TQ];
@@ -230,85 +251,95 @@ int scan_chunk_words(int W)
     return best;
 }
 
-template <int B, int W, int R>
-static hipError_t launch_resident_brw(const ScanArgs& a, bool dense, dim3 grid, hipStream_t s)
+// One-dimensional grid covering row_blocks x qranges tiles, padded to whole XCD rounds.
+static bool tile_grid(ScanArgs& a, int64_t bundles, int bundles_per_block, dim3& grid)
 {
+    const int64_t row_blocks = (bundles + bundles_per_block - 1) / bundles_per_block;
+    const int64_t total = (row_blocks + kXcds - 1) / kXcds * kXcds * a.qranges;
+    if (row_blocks > 0x7fffffff || total > 0x7fffffff) return false;
+    a.row_blocks = static_cast<int>(row_blocks);
+    grid = dim3(static_cast<unsigned>(total));
+    return true;
+}
+
+template <int B, int W, int R>
+static hipError_t launch_resident_brw(ScanArgs a, bool dense, int64_t bundles, hipStream_t s)
+{
+    dim3 grid;
+    if (!tile_grid(a, bundles, 4 * R, grid)) return hipErrorInvalidValue;
     if (dense) hipLaunchKernelGGL((scan_resident<B, W, R, true>), grid, dim3(kBlock), 0, s, a);
     else       hipLaunchKernelGGL((scan_resident<B, W, R, false>), grid, dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
 template <int B, int W>
-static hipError_t launch_resident_bw(const ScanArgs& a, bool dense, int64_t bundles, int qranges, hipStream_t s)
+static hipError_t launch_resident_bw(const ScanArgs& a, bool dense, int64_t bundles, hipStream_t s)
 {
     if constexpr (B * W <= 16) {
-        if (a.rows_per_lane == 2) {
-            dim3 grid(static_cast<unsigned>((bundles + 7) / 8), static_cast<unsigned>(qranges));
-            return launch_resident_brw<B, W, 2>(a, dense, grid, s);
-        }
+        if (a.rows_per_lane == 2) return launch_resident_brw<B, W, 2>(a, dense, bundles, s);
     }
-    dim3 grid(static_cast<unsigned>((bundles + 3) / 4), static_cast<unsigned>(qranges));
-    return launch_resident_brw<B, W, 1>(a, dense, grid, s);
+    return launch_resident_brw<B, W, 1>(a, dense, bundles, s);
 }
 
 template <int B>
-static hipError_t launch_resident_b(const ScanArgs& a, bool dense, int64_t bundles, int qranges, hipStream_t s)
+static hipError_t launch_resident_b(const ScanArgs& a, bool dense, int64_t bundles, hipStream_t s)
 {
     switch (a.W) {
-    case 1: return launch_resident_bw<B, 1>(a, dense, bundles, qranges, s);
-    case 2: return launch_resident_bw<B, 2>(a, dense, bundles, qranges, s);
-    case 3: return launch_resident_bw<B, 3>(a, dense, bundles, qranges, s);
-    case 4: return launch_resident_bw<B, 4>(a, dense, bundles, qranges, s);
-    case 5: return launch_resident_bw<B, 5>(a, dense, bundles, qranges, s);
-    case 6: return launch_resident_bw<B, 6>(a, dense, bundles, qranges, s);
-    case 7: return launch_resident_bw<B, 7>(a, dense, bundles, qranges, s);
-    case 8: return launch_resident_bw<B, 8>(a, dense, bundles, qranges, s);
+    case 1: return launch_resident_bw<B, 1>(a, dense, bundles, s);
+    case 2: return launch_resident_bw<B, 2>(a, dense, bundles, s);
+    case 3: return launch_resident_bw<B, 3>(a, dense, bundles, s);
+    case 4: return launch_resident_bw<B, 4>(a, dense, bundles, s);
+    case 5: return launch_resident_bw<B, 5>(a, dense, bundles, s);
+    case 6: return launch_resident_bw<B, 6>(a, dense, bundles, s);
+    case 7: return launch_resident_bw<B, 7>(a, dense, bundles, s);
+    case 8: return launch_resident_bw<B, 8>(a, dense, bundles, s);
     default: return hipErrorInvalidValue;
     }
 }
 
 template <int B, int WC>
-static hipError_t launch_chunked_bw(const ScanArgs& a, bool dense, dim3 grid, hipStream_t s)
+static hipError_t launch_chunked_bw(ScanArgs a, bool dense, int64_t bundles, hipStream_t s)
 {
+    dim3 grid;
+    if (!tile_grid(a, bundles, 4, grid)) return hipErrorInvalidValue;
     if (dense) hipLaunchKernelGGL((scan_chunked<B, WC, true>), grid, dim3(kBlock), 0, s, a);
     else       hipLaunchKernelGGL((scan_chunked<B, WC, false>), grid, dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
 template <int B>
-static hipError_t launch_chunked_b(const ScanArgs& a, bool dense, dim3 grid, hipStream_t s)
+static hipError_t launch_chunked_b(const ScanArgs& a, bool dense, int64_t bundles, hipStream_t s)
 {
     switch (a.wc) {
-    case 5: return launch_chunked_bw<B, 5>(a, dense, grid, s);
-    case 6: return launch_chunked_bw<B, 6>(a, dense, grid, s);
-    case 7: return launch_chunked_bw<B, 7>(a, dense, grid, s);
-    case 8: return launch_chunked_bw<B, 8>(a, dense, grid, s);
+    case 5: return launch_chunked_bw<B, 5>(a, dense, bundles, s);
+    case 6: return launch_chunked_bw<B, 6>(a, dense, bundles, s);
+    case 7: return launch_chunked_bw<B, 7>(a, dense, bundles, s);
+    case 8: return launch_chunked_bw<B, 8>(a, dense, bundles, s);
     default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_scan(int bits, const ScanArgs& a, bool dense, hipStream_t s)
+hipError_t launch_scan(int bits, const ScanArgs& args, bool dense, hipStream_t s)
 {
+    ScanArgs a = args;
     if (a.row_end <= a.row_begin || a.m <= 0) return hipSuccess;
-    if (a.row_begin % kLanes != 0 || a.qsplit < 1) return hipErrorInvalidValue;
+    if (a.row_begin % kLanes != 0 || a.qsplit < 1 || a.row_end > a.n) return hipErrorInvalidValue;
     const int64_t bundles = (a.row_end - a.row_begin + kLanes - 1) / kLanes;
-    const int qranges = (a.m + a.qsplit - 1) / a.qsplit;
-    if (qranges > 65535) return hipErrorInvalidValue;
+    a.qranges = (a.m + a.qsplit - 1) / a.qsplit;
     if (a.wc == 0) {
         switch (bits) {
-        case 1: return launch_resident_b<1>(a, dense, bundles, qranges, s);
-        case 2: return launch_resident_b<2>(a, dense, bundles, qranges, s);
-        case 3: return launch_resident_b<3>(a, dense, bundles, qranges, s);
-        case 4: return launch_resident_b<4>(a, dense, bundles, qranges, s);
+        case 1: return launch_resident_b<1>(a, dense, bundles, s);
+        case 2: return launch_resident_b<2>(a, dense, bundles, s);
+        case 3: return launch_resident_b<3>(a, dense, bundles, s);
+        case 4: return launch_resident_b<4>(a, dense, bundles, s);
         default: return hipErrorInvalidValue;
         }
     }
-    dim3 grid(static_cast<unsigned>((bundles + 3) / 4), static_cast<unsigned>(qranges));
     switch (bits) {
-    case 1: return launch_chunked_b<1>(a, dense, grid, s);
-    case 2: return launch_chunked_b<2>(a, dense, grid, s);
-    case 3: return launch_chunked_b<3>(a, dense, grid, s);
-    case 4: return launch_chunked_b<4>(a, dense, grid, s);
+    case 1: return launch_chunked_b<1>(a, dense, bundles, s);
+    case 2: return launch_chunked_b<2>(a, dense, bundles, s);
+    case 3: return launch_chunked_b<3>(a, dense, bundles, s);
+    case 4: return launch_chunked_b<4>(a, dense, bundles, s);
     default: return hipErrorInvalidValue;
     }
 }
