@@ -107,9 +107,11 @@ int xbq_trace_enable(int on);
 int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
 
 /*
- * Tuning knobs (process-wide, host side only).  name = "growth" (size ratio of
- * successive database groups, default 2.0), "first" (rows scored densely before any
- * threshold exists, default 1024), "qsplit" (queries per workgroup, 0 = automatic).
+ * Tuning knobs (process-wide, host side only):
+ *   "growth"  upper bound on rows-after-a-group / rows-before-it (default 4.0; lowered
+ *             automatically for large k so the survivor lists stay short)
+ *   "first"   rows scored densely before any threshold exists (default 1024)
+ *   "qsplit"  queries per workgroup (0 = automatic)
  * Returns XBQ_EINVAL for an unknown name or a value out of range.
  */
 int xbq_set_option(const char* name, double value);

@@ -8,8 +8,8 @@
 // distance has a higher row number than everything already seen, so it loses the tie),
 // and for rows in random order about K * (group size / rows seen) of them do.  After each
 // group one small kernel per query merges the survivors into the top-K and tightens the
-// threshold.  A query whose survivor list overflows its buffer is rescanned exactly by a
-// fallback kernel, so the result never depends on the data order.
+// threshold.  A query whose survivor list overflows its buffer is rescanned exactly inside
+// that kernel, so the result never depends on the data order.
 
 #include <cmath>
 #include <cstring>
@@ -24,7 +24,7 @@ using namespace xbq;
 thread_local int g_last_hip_error = 0;
 
 struct Options {
-    double growth = 2.0;
+    double growth = 4.0;
     int first = 1024;
     int qsplit = 0;
 } g_opt;
@@ -61,7 +61,7 @@ struct Plan {
     int first = 0;                       // rows of the dense group
     int cap = 0;                         // candidate slots per query
     int64_t batch = 0;                   // queries per batch
-    size_t off_thr = 0, off_cnt = 0, off_ovf = 0, off_topk = 0, off_cand = 0, off_dense = 0, off_q = 0;
+    size_t off_thr = 0, off_cnt = 0, off_topk = 0, off_cand = 0, off_dense = 0, off_q = 0;
     size_t total = 0;
 };
 
@@ -84,7 +84,6 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k)
     size_t off = 0;
     p.off_thr = off;   off = align_up(off + b * sizeof(uint32_t), 256);
     p.off_cnt = off;   off = align_up(off + b * sizeof(uint32_t), 256);
-    p.off_ovf = off;   off = align_up(off + b * sizeof(uint32_t), 256);
     p.off_topk = off;  off = align_up(off + b * k * sizeof(uint64_t), 256);
     p.off_cand = off;  off = align_up(off + b * p.cap * sizeof(uint64_t), 256);
     p.off_dense = off; off = align_up(off + b * static_cast<size_t>(p.first) * sizeof(uint32_t), 256);
@@ -237,7 +236,6 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
         sel.topk = reinterpret_cast<uint64_t*>(ws + p.off_topk);
         sel.thr = reinterpret_cast<uint32_t*>(ws + p.off_thr);
         sel.cnt = reinterpret_cast<uint32_t*>(ws + p.off_cnt);
-        sel.ovf = reinterpret_cast<uint32_t*>(ws + p.off_ovf);
         sel.cand = sa.cand;
         sel.cap = p.cap;
         sel.dense = sa.dense;
@@ -263,7 +261,11 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
         }
         // later groups: threshold scan, merge, exact rescan of overflowed queries
         while (seen < n) {
-            int64_t size = static_cast<int64_t>(std::ceil(static_cast<double>(seen) * (g_opt.growth - 1.0)));
+            // expected survivors per query in a group are about k * (growth - 1): keep them
+            // at a third of the list capacity at most
+            double growth = 1.0 + static_cast<double>(p.cap) / (3.0 * k);
+            if (growth > g_opt.growth) growth = g_opt.growth;
+            int64_t size = static_cast<int64_t>(std::ceil(static_cast<double>(seen) * (growth - 1.0)));
             size = (size + 511) / 512 * 512;
             int64_t end = seen + size;
             if (end > n || n - end < 512) end = n;
@@ -276,17 +278,15 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
             if (e != hipSuccess) return fail_hip(e);
             sel.row_begin = seen;
             sel.final_group = end >= n;
-            e = launch_select_merge(sel, s);
-            if (e != hipSuccess) return fail_hip(e);
-            RescanArgs ra{};
-            ra.db = db_codes;
-            ra.n = n;
-            ra.row_begin = seen;
-            ra.row_end = end;
-            ra.q_rows = q_rows;
-            ra.W = p.W;
-            ra.sel = sel;
-            e = launch_rescan(ra, s);
+            MergeArgs ma{};
+            ma.db = db_codes;
+            ma.n = n;
+            ma.row_begin = seen;
+            ma.row_end = end;
+            ma.q_rows = q_rows;
+            ma.W = p.W;
+            ma.sel = sel;
+            e = launch_select_merge(ma, s);
             if (e != hipSuccess) return fail_hip(e);
             seen = end;
         }

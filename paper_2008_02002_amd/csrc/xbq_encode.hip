@@ -74,22 +74,104 @@ __global__ __launch_bounds__(kBlock) void encode_bundle(const float* __restrict_
     const int wave = threadIdx.x >> 6;
     const int W = (d + 31) / 32;
     const int64_t bundle = blockIdx.x;
-    for (int rr = 0; rr < 16; ++rr) {
-        const int r = wave * 16 + rr;                    // row inside the bundle
-        const int64_t row = bundle * 64 + r;
-        const bool live = row < n;
-        const float* xr = X + (live ? row : 0) * d;
-        for (int c0 = 0; c0 < d; c0 += 64) {
-            const int c = c0 + lane;
-            const bool valid = live && c < d;
-            const uint32_t code = quantize<B>(valid ? xr[c] : 0.0f, scale);
-            const uint32_t word = plane_words<B>(code, valid, lane);
-            const int w = (c0 >> 5) + (lane & 1);
-            if (lane < 2 * B && w < W) tile[((lane >> 1) * W + w) * 64 + r] = word;
+    // 16 rows per wavefront, 64 coordinates per step; loads are issued eight steps ahead of
+    // their use so that each wavefront keeps 2 KB in flight.
+    const int steps = (d + 63) >> 6;
+    const int items = 16 * steps;
+    constexpr int U = 8;
+    for (int i0 = 0; i0 < items; i0 += U) {
+        float v[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u;
+            const int rr = i / steps, c = ((i - rr * steps) << 6) + lane;
+            const int64_t row = bundle * 64 + wave * 16 + rr;
+            ok[u] = i < items && row < n && c < d;
+            v[u] = ok[u] ? X[row * d + c] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u;
+            if (i < items) {
+                const int rr = i / steps, st = i - rr * steps;
+                const uint32_t word = plane_words<B>(quantize<B>(v[u], scale), ok[u], lane);
+                const int w = (st << 1) + (lane & 1);
+                if (lane < 2 * B && w < W) tile[((lane >> 1) * W + w) * 64 + wave * 16 + rr] = word;
+            }
         }
     }
     __syncthreads();
     const int words = B * W * 64;
+    uint32_t* out = codes + bundle * static_cast<int64_t>(words);
+    for (int t = threadIdx.x; t < words; t += blockDim.x) out[t] = tile[t];
+}
+
+// OR of a value over each aligned group of 8 lanes (every lane of the group gets the result):
+// neighbour swap, pair swap, then mirror within the half row.
+__device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
+{
+    v |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v |= static_cast<uint32_t>(__builtin_amdgcn_mov_dpp(static_cast<int>(v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    return v;
+}
+
+// XBQ_BUNDLE64 for d a multiple of 4: 16 bytes per lane.  Every row is seen as 8*W slots of
+// 4 coordinates (slots past d are padding), so an aligned group of 8 lanes always covers
+// exactly one plane word.  A lane quantizes its 4 coordinates; per plane it squeezes its 4
+// code bits into a nibble (mask, one 24-bit multiply that moves bits 0,4,8,12 to 12..15,
+// bit-field extract), shifts it to its place in the word, and a 3-step DPP OR over the 8
+// lanes completes the word.  Lane b of each group stores plane b's word into the LDS tile.
+template <int B>
+__global__ __launch_bounds__(kBlock) void encode_bundle_vec4(const float4* __restrict__ X4, int64_t n, int d,
+                                                             float scale, uint32_t recip, uint32_t* __restrict__ codes)
+{
+    extern __shared__ uint32_t tile[];                   // B * W * 64 words
+    const int W = (d + 31) >> 5;
+    const int slots = 8 * W;                             // float4 slots per row, padding included
+    const int f4_per_row = d >> 2;                       // real float4s per row
+    const int64_t bundle = blockIdx.x;
+    const int64_t row0 = bundle * 64;
+    const int live = n - row0 < 64 ? static_cast<int>(n - row0) : 64;
+    const int total = live * slots;                      // multiple of 8
+    const float4* src = X4 + row0 * f4_per_row;
+    const int words = B * W * 64;
+    if (live < 64) {                                     // rows past n must come out as zero words
+        for (int t = threadIdx.x; t < words; t += blockDim.x) tile[t] = 0;
+        __syncthreads();
+    }
+    const int sub = threadIdx.x & 7;                     // position inside the group of 8 lanes
+    constexpr int U = 4;
+    for (int i0 = threadIdx.x; i0 < total; i0 += kBlock * U) {
+        float4 v[U];
+        int r[U], slot[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * kBlock;
+            r[u] = static_cast<int>(__umulhi(static_cast<uint32_t>(i), recip));     // i / slots
+            slot[u] = i - r[u] * slots;
+            const bool real = i < total && slot[u] < f4_per_row;
+            v[u] = real ? src[r[u] * f4_per_row + slot[u]] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * kBlock;               // groups of 8 lanes are all in or all out
+            uint32_t packed = quantize<B>(v[u].x, scale) | (quantize<B>(v[u].y, scale) << 4) |
+                              (quantize<B>(v[u].z, scale) << 8) | (quantize<B>(v[u].w, scale) << 12);
+            if (slot[u] >= f4_per_row) packed = 0;       // padding coordinates store zero bits
+            uint32_t mine = 0;
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                const uint32_t spread = packed & (0x1111u << b);                    // bits b, b+4, b+8, b+12
+                const uint32_t nib = (__umul24(spread, 0x1248u >> b) >> 12) & 0xFu; // -> bits 0..3
+                const uint32_t word = or_reduce8(nib << (4 * sub));
+                if (sub == b) mine = word;
+            }
+            if (i < total && sub < B) tile[(sub * W + (slot[u] >> 3)) * 64 + r[u]] = mine;
+        }
+    }
+    __syncthreads();
     uint32_t* out = codes + bundle * static_cast<int64_t>(words);
     for (int t = threadIdx.x; t < words; t += blockDim.x) out[t] = tile[t];
 }
@@ -102,6 +184,14 @@ static hipError_t launch_encode_b(const float* X, int64_t n, int d, float scale,
     if (layout == XBQ_ROWS) {
         hipLaunchKernelGGL(encode_rows<B>, dim3(static_cast<unsigned>((n + 3) / 4)), dim3(kBlock), 0, s, X, n, d,
                            scale, codes);
+    } else if (d % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0) {
+        // recip = ceil(2^32 / slots), slots = 8 * W >= 8: mulhi(i, recip) == i / slots exactly
+        // for every i < 64 * slots <= 2^15 that the kernel uses
+        const uint32_t slots = 8u * static_cast<uint32_t>(W);
+        const uint32_t recip = static_cast<uint32_t>(((1ull << 32) + slots - 1) / slots);
+        const size_t lds = static_cast<size_t>(B) * W * 64 * sizeof(uint32_t);
+        hipLaunchKernelGGL(encode_bundle_vec4<B>, dim3(static_cast<unsigned>((n + 63) / 64)), dim3(kBlock), lds, s,
+                           reinterpret_cast<const float4*>(X), n, d, scale, recip, codes);
     } else {
         const size_t lds = static_cast<size_t>(B) * W * 64 * sizeof(uint32_t);
         hipLaunchKernelGGL(encode_bundle<B>, dim3(static_cast<unsigned>((n + 63) / 64)), dim3(kBlock), lds, s, X, n,

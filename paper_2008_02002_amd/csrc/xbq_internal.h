@@ -67,7 +67,6 @@ struct SelectArgs {
     uint64_t* topk;          // [m][k] best keys so far, ascending
     uint32_t* thr;           // [m] D of the k-th best key
     uint32_t* cnt;           // [m]
-    uint32_t* ovf;           // [m] 1 = candidate list overflowed for the current group
     const uint64_t* cand;    // [m][cap]
     int cap;
     const uint32_t* dense;   // [m][dense_stride]
@@ -79,18 +78,17 @@ struct SelectArgs {
     int32_t* score;          // [m][k]
 };
 
-hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s);
-hipError_t launch_select_merge(const SelectArgs& a, hipStream_t s);
-
-// Exact rescan of rows [row_begin, row_end) for the queries whose candidate list
-// overflowed (ovf[q] != 0); other workgroups exit at once.
-struct RescanArgs {
-    const uint32_t* db;
+// Merge of one scanned group [row_begin, row_end) into the top-K; carries what the exact
+// rescan of an overflowed query needs.
+struct MergeArgs {
+    const uint32_t* db;      // XBQ_BUNDLE64 codes
     int64_t n, row_begin, row_end;
-    const uint32_t* q_rows;  // XBQ_ROWS
+    const uint32_t* q_rows;  // XBQ_ROWS codes of this batch
     int W;
     SelectArgs sel;
 };
-hipError_t launch_rescan(const RescanArgs& a, hipStream_t s);
+
+hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s);
+hipError_t launch_select_merge(const MergeArgs& a, hipStream_t s);
 
 }  // namespace xbq

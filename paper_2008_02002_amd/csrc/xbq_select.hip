@@ -7,9 +7,10 @@
 // query is a short list that one workgroup sorts in LDS.
 //
 //   select_dense  : first group of rows, every distance stored -> top-K keys + threshold
-//   select_merge  : current top-K + candidates that beat the threshold -> new top-K
-//   rescan_exact  : for a query whose candidate list overflowed, re-score the group's rows
-//                   with a running threshold and bounded LDS buffer (always exact)
+//   select_merge  : current top-K + candidates that beat the threshold -> new top-K; for a
+//                   query whose candidate list overflowed it instead re-scores the group's
+//                   rows with a running threshold and a bounded LDS buffer (slow, always
+//                   exact, and only ever taken when the row order is adversarial)
 
 #include "xbq_internal.h"
 
@@ -58,7 +59,6 @@ __device__ __forceinline__ void write_topk(const SelectArgs& a, int q, const uin
     if (threadIdx.x == 0) {
         a.thr[q] = static_cast<uint32_t>(keys[a.k - 1] >> 32);
         a.cnt[q] = 0;
-        a.ovf[q] = 0;
     }
     if (a.final_group) write_result(a, q, keys);
 }
@@ -73,27 +73,6 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
         keys[t] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
     __syncthreads();
     bitonic_sort_lds(keys, P);
-    write_topk(a, q, keys);
-}
-
-__global__ __launch_bounds__(kBlock) void select_merge(const SelectArgs a)
-{
-    __shared__ uint64_t keys[kSortCap];
-    const int q = blockIdx.x;
-    const uint32_t c = a.cnt[q];
-    if (c > static_cast<uint32_t>(a.cap)) {          // overflow: leave top-K as it was, rescan decides
-        if (threadIdx.x == 0) { a.ovf[q] = 1; a.cnt[q] = 0; }
-        return;
-    }
-    if (c == 0 && !a.final_group) return;            // nothing beat the threshold
-    const int total = a.k + static_cast<int>(c);
-    const int P = next_pow2(total);
-    const uint64_t* best = a.topk + static_cast<size_t>(q) * a.k;
-    const uint64_t* cand = a.cand + static_cast<size_t>(q) * a.cap;
-    for (int t = threadIdx.x; t < P; t += blockDim.x)
-        keys[t] = t < a.k ? best[t] : (t < total ? cand[t - a.k] : kPadKey);
-    __syncthreads();
-    if (c != 0) bitonic_sort_lds(keys, P);
     write_topk(a, q, keys);
 }
 
@@ -114,41 +93,63 @@ __device__ uint32_t distance_generic(const uint32_t* db, int64_t row, const uint
     return D;
 }
 
-__global__ __launch_bounds__(kBlock) void rescan_exact(const RescanArgs r)
+// Exact re-score of rows [row_begin, row_end) for one query, starting from its current
+// top-K.  keys[] holds the best K so far plus survivors; it is compacted (sorted, cut to K,
+// threshold tightened) whenever another full workgroup of survivors might not fit.
+__device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill)
 {
-    __shared__ uint64_t keys[kSortCap];
-    __shared__ int fill;
     const SelectArgs& a = r.sel;
-    const int q = blockIdx.x;
-    if (a.ovf[q] == 0) return;                       // uniform across the workgroup
     const uint32_t* yq = r.q_rows + static_cast<size_t>(q) * a.bits * r.W;
     for (int t = threadIdx.x; t < a.k; t += blockDim.x) keys[t] = a.topk[static_cast<size_t>(q) * a.k + t];
-    if (threadIdx.x == 0) fill = a.k;
+    if (threadIdx.x == 0) *fill = a.k;
     __syncthreads();
     uint32_t thr = static_cast<uint32_t>(keys[a.k - 1] >> 32);
     for (int64_t base = r.row_begin; base < r.row_end; base += blockDim.x) {
         const int64_t row = base + threadIdx.x;
         if (row < r.row_end) {
             const uint32_t D = distance_generic(r.db, row, yq, a.bits, r.W);
-            if (D < thr) keys[atomicAdd(&fill, 1)] = make_key(D, static_cast<uint32_t>(row));
+            if (D < thr) keys[atomicAdd(fill, 1)] = make_key(D, static_cast<uint32_t>(row));
         }
         __syncthreads();
-        const int have = fill;                       // <= previous fill + blockDim.x <= kSortCap
+        const int have = *fill;                      // <= previous fill + blockDim.x <= kSortCap
         if (have > kSortCap - static_cast<int>(blockDim.x)) {
             const int P = next_pow2(have);
             for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
             __syncthreads();
             bitonic_sort_lds(keys, P);
             thr = static_cast<uint32_t>(keys[a.k - 1] >> 32);
-            if (threadIdx.x == 0) fill = a.k;
+            if (threadIdx.x == 0) *fill = a.k;
         }
         __syncthreads();
     }
-    const int have = fill;
+    const int have = *fill;
     const int P = next_pow2(have);
     for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
     __syncthreads();
     bitonic_sort_lds(keys, P);
+    write_topk(a, q, keys);
+}
+
+__global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r)
+{
+    __shared__ uint64_t keys[kSortCap];
+    __shared__ int fill;
+    const SelectArgs& a = r.sel;
+    const int q = blockIdx.x;
+    const uint32_t c = a.cnt[q];                     // same value in every lane: branches are uniform
+    if (c > static_cast<uint32_t>(a.cap)) {          // the list overflowed: nothing of it is used
+        rescan_rows(r, q, keys, &fill);
+        return;
+    }
+    if (c == 0 && !a.final_group) return;            // nothing beat the threshold
+    const int total = a.k + static_cast<int>(c);
+    const int P = next_pow2(total);
+    const uint64_t* best = a.topk + static_cast<size_t>(q) * a.k;
+    const uint64_t* cand = a.cand + static_cast<size_t>(q) * a.cap;
+    for (int t = threadIdx.x; t < P; t += blockDim.x)
+        keys[t] = t < a.k ? best[t] : (t < total ? cand[t - a.k] : kPadKey);
+    __syncthreads();
+    if (c != 0) bitonic_sort_lds(keys, P);
     write_topk(a, q, keys);
 }
 
@@ -160,18 +161,11 @@ hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_select_merge(const SelectArgs& a, hipStream_t s)
+hipError_t launch_select_merge(const MergeArgs& r, hipStream_t s)
 {
-    if (a.m <= 0) return hipSuccess;
-    if (a.k + a.cap > kSortCap) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(select_merge, dim3(a.m), dim3(kBlock), 0, s, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_rescan(const RescanArgs& r, hipStream_t s)
-{
-    if (r.sel.m <= 0 || r.row_end <= r.row_begin) return hipSuccess;
-    hipLaunchKernelGGL(rescan_exact, dim3(r.sel.m), dim3(kBlock), 0, s, r);
+    if (r.sel.m <= 0) return hipSuccess;
+    if (r.sel.k + r.sel.cap > kSortCap || r.row_end > r.n || r.row_begin < 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(select_merge, dim3(r.sel.m), dim3(kBlock), 0, s, r);
     return hipGetLastError();
 }
 

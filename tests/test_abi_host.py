@@ -109,7 +109,7 @@ def test_workspace_bytes(L):
 
 
 def test_options(L):
-    assert L.xbq_set_option(b"growth", 2.0) == xbq.OK
+    assert L.xbq_set_option(b"growth", 4.0) == xbq.OK
     assert L.xbq_set_option(b"growth", 1.0) == xbq.EINVAL
     assert L.xbq_set_option(b"nonsense", 1.0) == xbq.EINVAL
     assert L.xbq_set_option(None, 1.0) == xbq.EINVAL

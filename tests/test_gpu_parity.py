@@ -211,7 +211,7 @@ def test_options_do_not_change_results():
             xbq.xbq_set_option("qsplit", qsplit)
             gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 100, 2.0), want, f"growth={growth} first={first}")
     finally:
-        xbq.xbq_set_option("growth", 2.0)
+        xbq.xbq_set_option("growth", 4.0)
         xbq.xbq_set_option("first", 1024)
         xbq.xbq_set_option("qsplit", 0)
 
