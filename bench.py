@@ -22,7 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def cpu_baseline(w, bits, k, scale, budget_s=15.0):
+def cpu_baseline(w, bits, db_bits, k, scale, budget_s=15.0):
     """The oracle as it stands, on the host cores, on a bounded sample of the same
     workload: the whole database is encoded and the first q queries are searched, q
     sized from a short probe so the search takes about budget_s seconds."""
@@ -32,7 +32,7 @@ def cpu_baseline(w, bits, k, scale, budget_s=15.0):
 
     X = wl.database(w)
     t0 = time.perf_counter()
-    planes = oc.encode(X, bits, scale)
+    planes = oc.encode(X, db_bits, scale)
     t_enc = time.perf_counter() - t0
     del X
     Q = wl.queries(w)
@@ -76,6 +76,7 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--bits", type=int, default=0)
     ap.add_argument("--k", type=int, default=0)
+    ap.add_argument("--db-bits", type=int, default=0, help="narrower database codes (xbq_search_asym)")
     ap.add_argument("--queries", type=int, default=0, help="use only the first N queries")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-recall", action="store_true")
@@ -100,6 +101,7 @@ def main():
     if args.queries:
         w = wl.scaled_down(w, m=args.queries)
     bits = args.bits or w.bits[-1]
+    db_bits = args.db_bits or bits
     k = args.k or w.ks[-1]
     torch.cuda.set_device(0)
     xbq.lib()
@@ -114,16 +116,16 @@ def main():
     for lo in range(0, w.n, slab):
         hi = min(w.n, lo + slab)
         Xdb[lo:hi] = torch.from_numpy(wl.database(w, lo, hi)).cuda()
-    db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
+    db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, db_bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
     q = torch.empty(xbq.xbq_code_bytes(w.m, w.d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
     ws = torch.empty(xbq.xbq_search_workspace_bytes(w.n, w.m, w.d, bits, k), dtype=torch.uint8, device="cuda")
     idx = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
     score = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
 
     def step():
-        xbq.xbq_encode(Xdb, bits, scale, xbq.BUNDLE64, out=db)
+        xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)
         xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
-        xbq.xbq_search(db, w.n, q, w.m, w.d, bits, k, workspace=ws, idx=idx, score=score)
+        xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws, idx=idx, score=score)
 
     if args.calib_copy:
         src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device="cuda")      # 256 MiB
@@ -142,10 +144,10 @@ def main():
     e0.record()
     for i in range(args.steps):
         enc_ev[i][0].record()
-        xbq.xbq_encode(Xdb, bits, scale, xbq.BUNDLE64, out=db)
+        xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)
         enc_ev[i][1].record()
         xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
-        xbq.xbq_search(db, w.n, q, w.m, w.d, bits, k, workspace=ws, idx=idx, score=score)
+        xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws, idx=idx, score=score)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -155,7 +157,7 @@ def main():
     enc_ms = sum(a.elapsed_time(b) for a, b in enc_ev) / args.steps
     ms_per_step = max(wall_ms, gpu_ms) / args.steps
 
-    ops = cm.credited_lane_ops_per_pair(w.d, bits, bits) * pairs          # credited XOR + popcount lane-ops
+    ops = cm.credited_lane_ops_per_pair(w.d, bits, db_bits) * pairs          # credited XOR + popcount lane-ops
     achieved = ops / (scan_ms * 1e-3) / 1e12
     peak = cm.VALU_INT_LANE_OPS_PER_S / 1e12
     # HBM-side bytes per scan launch come from the committed rocprofv3 --pmc summary of this
@@ -180,7 +182,8 @@ def main():
         "vs_baseline": None,
         "dtype": "u32",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: n={w.n} d={w.d} m={w.m} bits={bits} K={k} ({w.kind}, seed {w.seed})",
+        "config": {"workload": f"{w.name}: n={w.n} d={w.d} m={w.m} bits={bits}" +
+                               (f"x{db_bits}" if db_bits != bits else "") + f" K={k} ({w.kind}, seed {w.seed})",
                    "scale": scale, "options": args.set},
         "roofline": {
             "bound": "alu",
@@ -193,11 +196,11 @@ def main():
             "scan_ms_per_step": scan_ms / args.steps,
             "launches_per_step": launches / args.steps,
             "avg_launch_ms": scan_ms / max(launches, 1),
-            "scan_code_GBps": w.n * cm.code_bytes_per_row(w.d, bits) / 1e9 / (scan_ms / args.steps * 1e-3),
+            "scan_code_GBps": w.n * cm.code_bytes_per_row(w.d, db_bits) / 1e9 / (scan_ms / args.steps * 1e-3),
         },
         "encode": {"db_ms": enc_ms,
-                   "GBps": w.n * cm.encode_bytes_per_row(w.d, bits) / 1e9 / (enc_ms * 1e-3),
-                   "hbm_frac": w.n * cm.encode_bytes_per_row(w.d, bits) / (enc_ms * 1e-3) / cm.HBM_BYTES_PER_S},
+                   "GBps": w.n * cm.encode_bytes_per_row(w.d, db_bits) / 1e9 / (enc_ms * 1e-3),
+                   "hbm_frac": w.n * cm.encode_bytes_per_row(w.d, db_bits) / (enc_ms * 1e-3) / cm.HBM_BYTES_PER_S},
     }
     if not args.no_recall:
         r, nq = recall_at_k(Xdb, Xq, idx, k)
@@ -205,7 +208,7 @@ def main():
     del Xdb
     torch.cuda.empty_cache()
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, bits, k, scale)
+        out["cpu_baseline"] = cpu_baseline(w, bits, db_bits, k, scale)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

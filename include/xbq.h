@@ -97,6 +97,18 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
                size_t workspace_bytes, void* stream);
 
 /*
+ * Same search with different code widths on the two sides (Section 3.6 and Section 5 use
+ * 4-bit queries against 3-bit documents: three quarters of the operations and of the
+ * database bytes of 4 x 4).  db_codes hold db_bits planes, q_codes q_bits planes;
+ * supported pairs: q_bits == db_bits or q_bits == db_bits + 1, both in 1..4, else
+ * XBQ_EUNSUPPORTED.  score = d*(2^q_bits-1)*(2^db_bits-1) - 2*D.  The workspace must be at
+ * least xbq_search_workspace_bytes(n, m, d, q_bits, k).  Everything else as xbq_search.
+ */
+int xbq_search_asym(const uint32_t* db_codes, int64_t n, int db_bits, const uint32_t* q_codes,
+                    int64_t m, int q_bits, int d, int k, int32_t* idx, int32_t* score,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid.  While tracing is on, xbq_search brackets every launch of the scan
  * kernel (the XOR + population-count loop) with HIP events on the caller's stream.
  * xbq_trace_read waits for those events, returns the summed kernel time, the number of

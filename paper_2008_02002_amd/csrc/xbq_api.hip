@@ -69,7 +69,7 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k)
 {
     Plan p;
     p.W = words32(d);
-    if (!scan_is_resident(bits, p.W)) {
+    if (!scan_is_resident(p.W)) {
         p.wc = scan_chunk_words(p.W);
         p.nchunks = (p.W + p.wc - 1) / p.wc;
     }
@@ -116,14 +116,14 @@ int choose_qsplit(int64_t bundles, int rows_per_lane, int m, int tile)
     return qs;
 }
 
-hipError_t traced_scan(int bits, const ScanArgs& a, bool dense, hipStream_t s)
+hipError_t traced_scan(const ScanArgs& a, bool dense, hipStream_t s)
 {
     const bool rec = g_trace.on && g_trace.used + 2 <= static_cast<int>(g_trace.ev.size());
     if (rec) {
         hipError_t e = hipEventRecord(g_trace.ev[g_trace.used], s);
         if (e != hipSuccess) return e;
     }
-    hipError_t e = launch_scan(bits, a, dense, s);
+    hipError_t e = launch_scan(a, dense, s);
     if (e != hipSuccess) return e;
     if (rec) {
         e = hipEventRecord(g_trace.ev[g_trace.used + 1], s);
@@ -185,8 +185,16 @@ size_t xbq_search_workspace_bytes(int64_t n, int64_t m, int d, int bits, int k)
 int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int64_t m, int d, int bits, int k,
                int32_t* idx, int32_t* score, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (d < 1 || bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
-    if (!valid_shape(d, bits)) return XBQ_EUNSUPPORTED;
+    return xbq_search_asym(db_codes, n, bits, q_codes, m, bits, d, k, idx, score, workspace, workspace_bytes, stream);
+}
+
+int xbq_search_asym(const uint32_t* db_codes, int64_t n, int db_bits, const uint32_t* q_codes, int64_t m, int q_bits,
+                    int d, int k, int32_t* idx, int32_t* score, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (d < 1 || db_bits < 1 || q_bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
+    if (!valid_shape(d, db_bits) || !valid_shape(d, q_bits) || !scan_supports_bits(q_bits, db_bits))
+        return XBQ_EUNSUPPORTED;
+    const int bits = q_bits;                             // the wider of the two: sizes the workspace
     if (!valid_search_sizes(n, m, d, bits, k)) return XBQ_EINVAL;
     if (n == 0 || m == 0) return XBQ_OK;
     if (!db_codes || !q_codes || !idx || !score || !workspace) return XBQ_EINVAL;
@@ -199,17 +207,19 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
-    const int rpl_max = (p.wc == 0 && bits * p.W <= 16) ? 2 : 1;
+    const int rpl_max = (p.wc == 0 && db_bits * p.W <= 16) ? 2 : 1;
     const int tile = p.wc ? kTileQ : 1;
 
     for (int64_t qb = 0; qb < m; qb += p.batch) {
         const int mb = static_cast<int>(m - qb < p.batch ? m - qb : p.batch);
-        const uint32_t* q_rows = q_codes + qb * (static_cast<int64_t>(bits) * p.W);
+        const uint32_t* q_rows = q_codes + qb * (static_cast<int64_t>(q_bits) * p.W);
 
         ScanArgs sa{};
         sa.db = db_codes;
         sa.n = n;
         sa.m = mb;
+        sa.q_bits = q_bits;
+        sa.db_bits = db_bits;
         sa.W = p.W;
         sa.wc = p.wc;
         sa.nchunks = p.nchunks;
@@ -221,7 +231,7 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
         sa.dense_stride = p.first;
         if (p.wc) {
             uint32_t* qc = reinterpret_cast<uint32_t*>(ws + p.off_q);
-            const hipError_t e = launch_repack_queries(q_rows, mb, bits, p.W, p.wc, p.nchunks, qc, s);
+            const hipError_t e = launch_repack_queries(q_rows, mb, q_bits, p.W, p.wc, p.nchunks, qc, s);
             if (e != hipSuccess) return fail_hip(e);
             sa.q = qc;
         } else {
@@ -232,7 +242,8 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
         sel.m = mb;
         sel.k = k;
         sel.d = d;
-        sel.bits = bits;
+        sel.q_bits = q_bits;
+        sel.db_bits = db_bits;
         sel.topk = reinterpret_cast<uint64_t*>(ws + p.off_topk);
         sel.thr = reinterpret_cast<uint32_t*>(ws + p.off_thr);
         sel.cnt = reinterpret_cast<uint32_t*>(ws + p.off_cnt);
@@ -251,7 +262,7 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
             const int64_t bundles = (seen + kLanes - 1) / kLanes;
             sa.rows_per_lane = 1;
             sa.qsplit = choose_qsplit(bundles, 1, mb, tile);
-            hipError_t e = traced_scan(bits, sa, true, s);
+            hipError_t e = traced_scan(sa, true, s);
             if (e != hipSuccess) return fail_hip(e);
             sel.row_begin = 0;
             sel.rows = p.first;
@@ -274,7 +285,7 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
             const int64_t bundles = (end - seen + kLanes - 1) / kLanes;
             sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
             sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, tile);
-            hipError_t e = traced_scan(bits, sa, false, s);
+            hipError_t e = traced_scan(sa, false, s);
             if (e != hipSuccess) return fail_hip(e);
             sel.row_begin = seen;
             sel.final_group = end >= n;

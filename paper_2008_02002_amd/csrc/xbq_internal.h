@@ -32,6 +32,7 @@ struct ScanArgs {
     const uint32_t* q;       // XBQ_ROWS codes (register-resident scan) or chunk-major
                              // padded codes [m][nchunks][B][WC] (word-chunked scan)
     int m;                   // queries in this batch
+    int q_bits, db_bits;     // bits per coordinate of the query codes and of the database codes
     int qsplit;              // queries per workgroup
     int qranges;             // ceil(m / qsplit)            (filled in by launch_scan)
     int row_blocks;          // row blocks of one workgroup (filled in by launch_scan)
@@ -49,12 +50,14 @@ struct ScanArgs {
     int dense_stride;
 };
 
-// True if (bits, W) is served by the register-resident scan.
-bool scan_is_resident(int bits, int W);
+// True if codes of W words per plane are served by the register-resident scan.
+bool scan_is_resident(int W);
+// True if the scan kernels are built for this pair of code widths.
+bool scan_supports_bits(int q_bits, int db_bits);
 // Chunk width the word-chunked scan uses for W words per plane.
 int scan_chunk_words(int W);
 
-hipError_t launch_scan(int bits, const ScanArgs& a, bool dense, hipStream_t s);
+hipError_t launch_scan(const ScanArgs& a, bool dense, hipStream_t s);
 
 hipError_t launch_repack_queries(const uint32_t* q_rows, int m, int bits, int W, int wc,
                                  int nchunks, uint32_t* q_chunked, hipStream_t s);
@@ -63,7 +66,8 @@ hipError_t launch_encode(const float* X, int64_t n, int d, int bits, float scale
                          uint32_t* codes, hipStream_t s);
 
 struct SelectArgs {
-    int m, k, d, bits;
+    int m, k, d;
+    int q_bits, db_bits;
     uint64_t* topk;          // [m][k] best keys so far, ascending
     uint32_t* thr;           // [m] D of the k-th best key
     uint32_t* cnt;           // [m]

@@ -69,18 +69,19 @@ __device__ __forceinline__ uint32_t popcount_add(uint32_t v, uint32_t acc)
     return r;
 }
 
-// Eq. 6 for one row held in x against the B*WC uniform words y (both plane-major).
-template <int B, int WC>
-__device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[B][WC], const uint32_t (&y)[B][WC])
+// Eq. 6 for one row held in x (BD planes) against the uniform query words y (BQ planes).
+template <int BQ, int BD, int WC>
+__device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[BD][WC], const uint32_t (&y)[BQ][WC])
 {
-    uint32_t acc[2 * B - 1];
+    constexpr int C = BQ + BD - 1;                       // weight classes i + j
+    uint32_t acc[C];
 #pragma unroll
-    for (int c = 0; c < 2 * B - 1; ++c) {
+    for (int c = 0; c < C; ++c) {
         bool first = true;
 #pragma unroll
-        for (int i = 0; i < B; ++i) {
+        for (int i = 0; i < BD; ++i) {
             const int j = c - i;
-            if (j < 0 || j >= B) continue;
+            if (j < 0 || j >= BQ) continue;
 #pragma unroll
             for (int w = 0; w < WC; ++w) {
                 const uint32_t v = x[i][w] ^ y[j][w];
@@ -89,16 +90,16 @@ __device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[B][WC], con
             }
         }
     }
-    uint32_t D = acc[2 * B - 2];
+    uint32_t D = acc[C - 1];
 #pragma unroll
-    for (int c = 2 * B - 3; c >= 0; --c) D = (D << 1) + acc[c];
+    for (int c = C - 2; c >= 0; --c) D = (D << 1) + acc[c];
     return D;
 }
 
 // ---------------------------------------------------------------------------------------
 // Register-resident scan.  One workgroup = 4*R bundles of rows x one query range.
 // ---------------------------------------------------------------------------------------
-template <int B, int W, int R, bool DENSE>
+template <int BQ, int BD, int W, int R, bool DENSE>
 __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
 {
     const int lane = lane_id();
@@ -109,15 +110,15 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
     if (bundle0 * kLanes >= a.row_end) return;
     const int64_t last_bundle = (a.n - 1) / kLanes;
 
-    uint32_t x[R][B][W];
+    uint32_t x[R][BD][W];
     uint32_t row[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int64_t bundle = bundle0 + r;
         const int64_t ld = bundle <= last_bundle ? bundle : last_bundle;   // stay inside the buffer
-        const uint32_t* p = a.db + ld * (B * W * kLanes) + lane;
+        const uint32_t* p = a.db + ld * (BD * W * kLanes) + lane;
 #pragma unroll
-        for (int b = 0; b < B; ++b)
+        for (int b = 0; b < BD; ++b)
 #pragma unroll
             for (int w = 0; w < W; ++w) x[r][b][w] = p[(b * W + w) * kLanes];
         row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
@@ -127,15 +128,15 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
     const int q1 = q0 + a.qsplit < a.m ? q0 + a.qsplit : a.m;
     __builtin_amdgcn_s_waitcnt(0);      // row words have landed: no per-load waits inside the loop
     for (int q = q0; q < q1; ++q) {
-        uniform_ptr yq = (uniform_ptr)(a.q + static_cast<size_t>(q) * (B * W));
-        uint32_t y[B][W];
+        uniform_ptr yq = (uniform_ptr)(a.q + static_cast<size_t>(q) * (BQ * W));
+        uint32_t y[BQ][W];
 #pragma unroll
-        for (int b = 0; b < B; ++b)
+        for (int b = 0; b < BQ; ++b)
 #pragma unroll
             for (int w = 0; w < W; ++w) y[b][w] = yq[b * W + w];
         uint32_t D[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) D[r] = xor_popcount<B, W>(x[r], y);
+        for (int r = 0; r < R; ++r) D[r] = xor_popcount<BQ, BD, W>(x[r], y);
 
         if (DENSE) {
 #pragma unroll
@@ -161,7 +162,7 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
 // so the B*WC words a (query, chunk) step needs are contiguous.  Words past W are zero on
 // both sides and add nothing to D.
 // ---------------------------------------------------------------------------------------
-template <int B, int WC, bool DENSE>
+template <int BQ, int BD, int WC, bool DENSE>
 __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
 {
     constexpr int TQ = kTileQ;
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
     const int64_t bundle = a.row_begin / kLanes + static_cast<int64_t>(row_block) * 4 + wave;
     if (bundle * kLanes >= a.row_end) return;
     const int W = a.W;
-    const uint32_t* xb = a.db + bundle * (static_cast<int64_t>(B) * W * kLanes) + lane;
+    const uint32_t* xb = a.db + bundle * (static_cast<int64_t>(BD) * W * kLanes) + lane;
     const uint32_t row = static_cast<uint32_t>(bundle * kLanes + lane);
     const bool valid = row < a.row_end;
 
@@ -183,9 +184,9 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
 #pragma unroll
         for (int t = 0; t < TQ; ++t) acc[t] = 0;
         for (int c = 0; c < a.nchunks; ++c) {
-            uint32_t x[B][WC];
+            uint32_t x[BD][WC];
 #pragma unroll
-            for (int b = 0; b < B; ++b)
+            for (int b = 0; b < BD; ++b)
 #pragma unroll
                 for (int w = 0; w < WC; ++w) {
                     const int ww = c * WC + w;
@@ -194,13 +195,13 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
                 const int q = qt + t < a.m ? qt + t : a.m - 1;     // clamp: tail tiles reread the last query
-                uniform_ptr yq = (uniform_ptr)(a.q + (static_cast<size_t>(q) * a.nchunks + c) * (B * WC));
-                uint32_t y[B][WC];
+                uniform_ptr yq = (uniform_ptr)(a.q + (static_cast<size_t>(q) * a.nchunks + c) * (BQ * WC));
+                uint32_t y[BQ][WC];
 #pragma unroll
-                for (int b = 0; b < B; ++b)
+                for (int b = 0; b < BQ; ++b)
 #pragma unroll
                     for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
-                acc[t] += xor_popcount<B, WC>(x, y);
+                acc[t] += xor_popcount<BQ, BD, WC>(x, y);
             }
         }
 #pragma unroll
@@ -239,7 +240,7 @@ __global__ void repack_queries(const uint32_t* __restrict__ src, int m, int B, i
 // ---------------------------------------------------------------------------------------
 // Dispatch
 // ---------------------------------------------------------------------------------------
-bool scan_is_resident(int bits, int W) { return bits >= 1 && bits <= XBQ_MAX_BITS && W >= 1 && W <= 8; }
+bool scan_is_resident(int W) { return W >= 1 && W <= 8; }
 
 int scan_chunk_words(int W)
 {
@@ -262,84 +263,90 @@ static bool tile_grid(ScanArgs& a, int64_t bundles, int bundles_per_block, dim3&
     return true;
 }
 
-template <int B, int W, int R>
+template <int BQ, int BD, int W, int R>
 static hipError_t launch_resident_brw(ScanArgs a, bool dense, int64_t bundles, hipStream_t s)
 {
     dim3 grid;
     if (!tile_grid(a, bundles, 4 * R, grid)) return hipErrorInvalidValue;
-    if (dense) hipLaunchKernelGGL((scan_resident<B, W, R, true>), grid, dim3(kBlock), 0, s, a);
-    else       hipLaunchKernelGGL((scan_resident<B, W, R, false>), grid, dim3(kBlock), 0, s, a);
+    if (dense) hipLaunchKernelGGL((scan_resident<BQ, BD, W, R, true>), grid, dim3(kBlock), 0, s, a);
+    else       hipLaunchKernelGGL((scan_resident<BQ, BD, W, R, false>), grid, dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
-template <int B, int W>
+template <int BQ, int BD, int W>
 static hipError_t launch_resident_bw(const ScanArgs& a, bool dense, int64_t bundles, hipStream_t s)
 {
-    if constexpr (B * W <= 16) {
-        if (a.rows_per_lane == 2) return launch_resident_brw<B, W, 2>(a, dense, bundles, s);
+    if constexpr (BD * W <= 16) {
+        if (a.rows_per_lane == 2) return launch_resident_brw<BQ, BD, W, 2>(a, dense, bundles, s);
     }
-    return launch_resident_brw<B, W, 1>(a, dense, bundles, s);
+    return launch_resident_brw<BQ, BD, W, 1>(a, dense, bundles, s);
 }
 
-template <int B>
+template <int BQ, int BD>
 static hipError_t launch_resident_b(const ScanArgs& a, bool dense, int64_t bundles, hipStream_t s)
 {
     switch (a.W) {
-    case 1: return launch_resident_bw<B, 1>(a, dense, bundles, s);
-    case 2: return launch_resident_bw<B, 2>(a, dense, bundles, s);
-    case 3: return launch_resident_bw<B, 3>(a, dense, bundles, s);
-    case 4: return launch_resident_bw<B, 4>(a, dense, bundles, s);
-    case 5: return launch_resident_bw<B, 5>(a, dense, bundles, s);
-    case 6: return launch_resident_bw<B, 6>(a, dense, bundles, s);
-    case 7: return launch_resident_bw<B, 7>(a, dense, bundles, s);
-    case 8: return launch_resident_bw<B, 8>(a, dense, bundles, s);
+    case 1: return launch_resident_bw<BQ, BD, 1>(a, dense, bundles, s);
+    case 2: return launch_resident_bw<BQ, BD, 2>(a, dense, bundles, s);
+    case 3: return launch_resident_bw<BQ, BD, 3>(a, dense, bundles, s);
+    case 4: return launch_resident_bw<BQ, BD, 4>(a, dense, bundles, s);
+    case 5: return launch_resident_bw<BQ, BD, 5>(a, dense, bundles, s);
+    case 6: return launch_resident_bw<BQ, BD, 6>(a, dense, bundles, s);
+    case 7: return launch_resident_bw<BQ, BD, 7>(a, dense, bundles, s);
+    case 8: return launch_resident_bw<BQ, BD, 8>(a, dense, bundles, s);
     default: return hipErrorInvalidValue;
     }
 }
 
-template <int B, int WC>
+template <int BQ, int BD, int WC>
 static hipError_t launch_chunked_bw(ScanArgs a, bool dense, int64_t bundles, hipStream_t s)
 {
     dim3 grid;
     if (!tile_grid(a, bundles, 4, grid)) return hipErrorInvalidValue;
-    if (dense) hipLaunchKernelGGL((scan_chunked<B, WC, true>), grid, dim3(kBlock), 0, s, a);
-    else       hipLaunchKernelGGL((scan_chunked<B, WC, false>), grid, dim3(kBlock), 0, s, a);
+    if (dense) hipLaunchKernelGGL((scan_chunked<BQ, BD, WC, true>), grid, dim3(kBlock), 0, s, a);
+    else       hipLaunchKernelGGL((scan_chunked<BQ, BD, WC, false>), grid, dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
-template <int B>
+template <int BQ, int BD>
 static hipError_t launch_chunked_b(const ScanArgs& a, bool dense, int64_t bundles, hipStream_t s)
 {
     switch (a.wc) {
-    case 5: return launch_chunked_bw<B, 5>(a, dense, bundles, s);
-    case 6: return launch_chunked_bw<B, 6>(a, dense, bundles, s);
-    case 7: return launch_chunked_bw<B, 7>(a, dense, bundles, s);
-    case 8: return launch_chunked_bw<B, 8>(a, dense, bundles, s);
+    case 5: return launch_chunked_bw<BQ, BD, 5>(a, dense, bundles, s);
+    case 6: return launch_chunked_bw<BQ, BD, 6>(a, dense, bundles, s);
+    case 7: return launch_chunked_bw<BQ, BD, 7>(a, dense, bundles, s);
+    case 8: return launch_chunked_bw<BQ, BD, 8>(a, dense, bundles, s);
     default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_scan(int bits, const ScanArgs& args, bool dense, hipStream_t s)
+template <int BQ, int BD>
+static hipError_t launch_scan_b(const ScanArgs& a, bool dense, int64_t bundles, hipStream_t s)
+{
+    return a.wc == 0 ? launch_resident_b<BQ, BD>(a, dense, bundles, s) : launch_chunked_b<BQ, BD>(a, dense, bundles, s);
+}
+
+bool scan_supports_bits(int q_bits, int db_bits)
+{
+    return db_bits >= 1 && db_bits <= XBQ_MAX_BITS && (q_bits == db_bits || q_bits == db_bits + 1) &&
+           q_bits <= XBQ_MAX_BITS;
+}
+
+hipError_t launch_scan(const ScanArgs& args, bool dense, hipStream_t s)
 {
     ScanArgs a = args;
     if (a.row_end <= a.row_begin || a.m <= 0) return hipSuccess;
     if (a.row_begin % kLanes != 0 || a.qsplit < 1 || a.row_end > a.n) return hipErrorInvalidValue;
     const int64_t bundles = (a.row_end - a.row_begin + kLanes - 1) / kLanes;
     a.qranges = (a.m + a.qsplit - 1) / a.qsplit;
-    if (a.wc == 0) {
-        switch (bits) {
-        case 1: return launch_resident_b<1>(a, dense, bundles, s);
-        case 2: return launch_resident_b<2>(a, dense, bundles, s);
-        case 3: return launch_resident_b<3>(a, dense, bundles, s);
-        case 4: return launch_resident_b<4>(a, dense, bundles, s);
-        default: return hipErrorInvalidValue;
-        }
-    }
-    switch (bits) {
-    case 1: return launch_chunked_b<1>(a, dense, bundles, s);
-    case 2: return launch_chunked_b<2>(a, dense, bundles, s);
-    case 3: return launch_chunked_b<3>(a, dense, bundles, s);
-    case 4: return launch_chunked_b<4>(a, dense, bundles, s);
+    switch (a.q_bits * 10 + a.db_bits) {
+    case 11: return launch_scan_b<1, 1>(a, dense, bundles, s);
+    case 22: return launch_scan_b<2, 2>(a, dense, bundles, s);
+    case 33: return launch_scan_b<3, 3>(a, dense, bundles, s);
+    case 44: return launch_scan_b<4, 4>(a, dense, bundles, s);
+    case 21: return launch_scan_b<2, 1>(a, dense, bundles, s);
+    case 32: return launch_scan_b<3, 2>(a, dense, bundles, s);
+    case 43: return launch_scan_b<4, 3>(a, dense, bundles, s);
     default: return hipErrorInvalidValue;
     }
 }

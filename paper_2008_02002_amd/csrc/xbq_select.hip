@@ -45,7 +45,7 @@ __device__ void bitonic_sort_lds(uint64_t* keys, int P)
 
 __device__ __forceinline__ void write_result(const SelectArgs& a, int q, const uint64_t* keys)
 {
-    const int32_t full = a.d * ((1 << a.bits) - 1) * ((1 << a.bits) - 1);
+    const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
     for (int t = threadIdx.x; t < a.k; t += blockDim.x) {
         const uint64_t key = keys[t];
         a.idx[static_cast<size_t>(q) * a.k + t] = static_cast<int32_t>(key & 0xffffffffu);
@@ -77,18 +77,16 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
 }
 
 // Eq. 6 for one (row, query) with run-time sizes; slow path used only by the rescan.
-__device__ uint32_t distance_generic(const uint32_t* db, int64_t row, const uint32_t* yq, int B, int W)
+__device__ uint32_t distance_generic(const uint32_t* db, int64_t row, const uint32_t* yq, int BQ, int BD, int W)
 {
-    const uint32_t* xb = db + (row / kLanes) * (static_cast<int64_t>(B) * W * kLanes) + (row % kLanes);
+    const uint32_t* xb = db + (row / kLanes) * (static_cast<int64_t>(BD) * W * kLanes) + (row % kLanes);
     uint32_t D = 0;
     for (int w = 0; w < W; ++w) {
         uint32_t x[XBQ_MAX_BITS], y[XBQ_MAX_BITS];
-        for (int b = 0; b < B; ++b) {
-            x[b] = xb[(b * W + w) * kLanes];
-            y[b] = yq[b * W + w];
-        }
-        for (int i = 0; i < B; ++i)
-            for (int j = 0; j < B; ++j) D += static_cast<uint32_t>(__builtin_popcount(x[i] ^ y[j])) << (i + j);
+        for (int b = 0; b < BD; ++b) x[b] = xb[(b * W + w) * kLanes];
+        for (int b = 0; b < BQ; ++b) y[b] = yq[b * W + w];
+        for (int i = 0; i < BD; ++i)
+            for (int j = 0; j < BQ; ++j) D += static_cast<uint32_t>(__builtin_popcount(x[i] ^ y[j])) << (i + j);
     }
     return D;
 }
@@ -99,7 +97,7 @@ __device__ uint32_t distance_generic(const uint32_t* db, int64_t row, const uint
 __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill)
 {
     const SelectArgs& a = r.sel;
-    const uint32_t* yq = r.q_rows + static_cast<size_t>(q) * a.bits * r.W;
+    const uint32_t* yq = r.q_rows + static_cast<size_t>(q) * a.q_bits * r.W;
     for (int t = threadIdx.x; t < a.k; t += blockDim.x) keys[t] = a.topk[static_cast<size_t>(q) * a.k + t];
     if (threadIdx.x == 0) *fill = a.k;
     __syncthreads();
@@ -107,7 +105,7 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill
     for (int64_t base = r.row_begin; base < r.row_end; base += blockDim.x) {
         const int64_t row = base + threadIdx.x;
         if (row < r.row_end) {
-            const uint32_t D = distance_generic(r.db, row, yq, a.bits, r.W);
+            const uint32_t D = distance_generic(r.db, row, yq, a.q_bits, a.db_bits, r.W);
             if (D < thr) keys[atomicAdd(fill, 1)] = make_key(D, static_cast<uint32_t>(row));
         }
         __syncthreads();

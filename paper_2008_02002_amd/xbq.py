@@ -18,7 +18,7 @@ MAX_BITS, MAX_DIM, MAX_K = 4, 2048, 1024
 
 EXPORTS = (
     "xbq_version", "xbq_strerror", "xbq_last_hip_error", "xbq_code_bytes", "xbq_encode",
-    "xbq_search_workspace_bytes", "xbq_search", "xbq_trace_enable", "xbq_trace_read",
+    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_trace_enable", "xbq_trace_read",
     "xbq_set_option",
 )
 
@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
         L.xbq_search_workspace_bytes.restype = sz
         L.xbq_search.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp, sz, vp]
         L.xbq_search.restype = i32
+        L.xbq_search_asym.argtypes = [vp, i64, i32, vp, i64, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.xbq_search_asym.restype = i32
         L.xbq_trace_enable.argtypes = [i32]
         L.xbq_trace_enable.restype = i32
         L.xbq_trace_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64),
@@ -132,6 +134,28 @@ def xbq_search(db_codes, n: int, q_codes, m: int, d: int, bits: int, k: int, wor
                           ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                           _stream())
     _check(rc, "xbq_search")
+    return idx, score
+
+
+def xbq_search_asym(db_codes, n: int, db_bits: int, q_codes, m: int, q_bits: int, d: int, k: int,
+                    workspace=None, idx=None, score=None):
+    """Search with q_bits-plane query codes against db_bits-plane database codes."""
+    import torch
+    dev = db_codes.device
+    need = xbq_search_workspace_bytes(n, m, d, q_bits, k)
+    if need == 0:
+        raise XbqError(EINVAL, "xbq_search_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    if idx is None:
+        idx = torch.empty((m, k), dtype=torch.int32, device=dev)
+    if score is None:
+        score = torch.empty((m, k), dtype=torch.int32, device=dev)
+    rc = lib().xbq_search_asym(ctypes.c_void_p(db_codes.data_ptr()), n, db_bits, ctypes.c_void_p(q_codes.data_ptr()),
+                               m, q_bits, d, k, ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(score.data_ptr()),
+                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                               _stream())
+    _check(rc, "xbq_search_asym")
     return idx, score
 
 

@@ -70,3 +70,19 @@ def check_order_properties(idx: np.ndarray, score: np.ndarray, n: int):
     assert (ds <= 0).all(), "scores not descending"
     di = np.diff(idx.astype(np.int64), axis=1)
     assert (di[ds == 0] > 0).all(), "tie not broken by lower index"
+
+
+def gpu_search_asym(Xdb, Xq, db_bits: int, q_bits: int, k: int, scale: float):
+    import torch
+    n, d = Xdb.shape
+    m = Xq.shape[0]
+    db = xbq.xbq_encode(to_dev(Xdb), db_bits, scale, xbq.BUNDLE64)
+    q = xbq.xbq_encode(to_dev(Xq), q_bits, scale, xbq.ROWS)
+    idx, score = xbq.xbq_search_asym(db, n, db_bits, q, m, q_bits, d, k)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), score.cpu().numpy()
+
+
+def oracle_search_asym(Xdb, Xq, db_bits: int, q_bits: int, k: int, scale: float):
+    d = Xdb.shape[1]
+    return oc.search(oc.encode(Xdb, db_bits, scale), oc.encode(Xq, q_bits, scale), d, k)

@@ -96,6 +96,24 @@ def test_search_argument_errors(L):
     assert s(n=0) == xbq.OK and s(m=0) == xbq.OK                # empty inputs are no-ops
 
 
+def test_search_asym_argument_errors(L):
+    fake = ctypes.c_void_p(0x1000)
+    null = ctypes.c_void_p(0)
+
+    def s(db_bits=3, q_bits=4, n=1000, m=10, d=128, k=10, db=fake, ws=fake, wsb=1 << 40):
+        return L.xbq_search_asym(db, n, db_bits, fake, m, q_bits, d, k, fake, fake, ws, wsb, null)
+
+    assert s(db_bits=4, q_bits=3) == xbq.EUNSUPPORTED       # queries may not be narrower
+    assert s(db_bits=2, q_bits=4) == xbq.EUNSUPPORTED
+    assert s(db_bits=4, q_bits=5) == xbq.EUNSUPPORTED
+    assert s(db_bits=0) == xbq.EINVAL
+    assert s(db=null) == xbq.EINVAL
+    assert s(k=0) == xbq.EINVAL
+    need = L.xbq_search_workspace_bytes(1000, 10, 128, 4, 10)
+    assert s(wsb=need - 1) == xbq.EWORKSPACE
+    assert s(n=0) == xbq.OK
+
+
 def test_workspace_bytes(L):
     f = L.xbq_search_workspace_bytes
     assert f(1000, 10, 128, 4, 0) == 0

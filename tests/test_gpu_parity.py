@@ -145,6 +145,46 @@ def test_configs_scaled_down(name, n, m):
             gu.check_order_properties(got[0], got[1], n)
 
 
+ASYM = [
+    # n, d, m, q_bits, db_bits, k
+    (5000, 128, 40, 4, 3, 10),
+    (5000, 200, 40, 4, 3, 100),
+    (20000, 96, 64, 4, 3, 100),
+    (9000, 64, 30, 3, 2, 50),
+    (9000, 40, 30, 2, 1, 20),
+    (3000, 960, 24, 4, 3, 10),
+    (2500, 300, 17, 3, 2, 7),
+    (300, 256, 5, 4, 3, 300),
+]
+
+
+@pytest.mark.parametrize("n,d,m,qb,db,k", ASYM)
+def test_search_asymmetric_bits(n, d, m, qb, db, k):
+    # 4-bit queries against 3-bit documents is the setting of Sections 3.6 and 5
+    _say(f"asym n={n} d={d} m={m} q_bits={qb} db_bits={db} k={k}")
+    Xdb = _rand(n, d, seed=n + d + qb)
+    Xq = _rand(m, d, seed=n + d + qb + 1)
+    gu.assert_same(gu.gpu_search_asym(Xdb, Xq, db, qb, k, 2.2), gu.oracle_search_asym(Xdb, Xq, db, qb, k, 2.2),
+                   f"asym {qb}x{db}")
+
+
+def test_asymmetric_on_word_embedding_stand_in():
+    w = wl.scaled_down(wl.WORKLOADS["C4"], n=150_000, m=100)
+    Xdb, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
+    got = gu.gpu_search_asym(Xdb, Xq, 3, 4, 100, scale)
+    gu.assert_same(got, gu.oracle_search_asym(Xdb, Xq, 3, 4, 100, scale), "C4 4x3")
+    gu.check_order_properties(got[0], got[1], w.n)
+
+
+def test_asymmetric_unsupported_pairs_are_refused():
+    import torch
+    t = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
+    for qb, db in ((3, 4), (4, 2), (4, 1), (1, 2)):
+        with pytest.raises(xbq.XbqError) as e:
+            xbq.xbq_search_asym(t, 64, db, t, 4, qb, 32, 1)
+        assert e.value.code == xbq.EUNSUPPORTED
+
+
 def test_all_scores_tied():
     # non-negative data at scale 1: every coordinate falls in the same cell, all scores equal
     w = wl.scaled_down(wl.WORKLOADS["C3"], n=30_000, m=16)
