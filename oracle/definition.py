@@ -249,6 +249,59 @@ def search(X_db, X_q, B: int, K: int, scale: float = 1.0):
 
 
 # --------------------------------------------------------------------------
+# Section 4, Algorithm 1 (K-Select): histogram of the integer distances, boundary at
+# the K-th smallest distance plus an extra distance (Section 3.6), candidates, exact
+# refine, sort.
+# --------------------------------------------------------------------------
+
+
+def kth_distance_by_histogram(dist_row: np.ndarray, K: int) -> int:
+    """Algorithm 1, histogram steps: h_v = number of rows at distance v; the boundary is
+    the smallest j with sum_{i <= j} h_i >= K."""
+    h = np.bincount(np.asarray(dist_row, dtype=np.int64))
+    cum = np.cumsum(h)
+    return int(np.argmax(cum >= K))
+
+
+def k_select_candidates(dist_row: np.ndarray, K: int, extra: int, limit: int | None = None) -> np.ndarray:
+    """Algorithm 1, candidate list L: every row with d <= maxDistance, where
+    maxDistance = (K-th smallest distance) + extraDistance.  Returned in (distance, row)
+    order; if ``limit`` is given only the first ``limit`` of that order are kept (a bound
+    on the list the implementation under test documents)."""
+    dist_row = np.asarray(dist_row, dtype=np.int64)
+    max_distance = kth_distance_by_histogram(dist_row, K) + extra
+    rows = np.nonzero(dist_row <= max_distance)[0]
+    order = np.lexsort((rows, dist_row[rows]))
+    rows = rows[order]
+    return rows if limit is None else rows[:limit]
+
+
+def k_select(dist: np.ndarray, X_db: np.ndarray, X_q: np.ndarray, K: int, extra: int, limit: int | None = None):
+    """Algorithm 1 from the distances on: candidates, refine by the exact inner product of
+    the original vectors (accumulated in float64), sort by similarity (descending, ties to
+    the lower row), first K.  Returns (idx [m, K], similarity float64 [m, K], |L| [m])."""
+    m = dist.shape[0]
+    idx = np.empty((m, K), dtype=np.int64)
+    sim = np.empty((m, K), dtype=np.float64)
+    count = np.empty(m, dtype=np.int64)
+    Xd = np.asarray(X_db, dtype=np.float64)
+    Xq = np.asarray(X_q, dtype=np.float64)
+    for q in range(m):
+        L = k_select_candidates(dist[q], K, extra, limit)
+        count[q] = len(L)
+        s = Xd[L] @ Xq[q]
+        order = np.lexsort((L, -s))[:K]
+        idx[q] = L[order]
+        sim[q] = s[order]
+    return idx, sim, count
+
+
+def distance_from_score(S, d: int, Bq: int, Bd: int):
+    """Inverse of :func:`score_from_distance`."""
+    return (d * ((1 << Bq) - 1) * ((1 << Bd) - 1) - np.asarray(S, dtype=np.int64)) // 2
+
+
+# --------------------------------------------------------------------------
 # Section 5: Precision@K (same number as recall@K for equal-size sets)
 # --------------------------------------------------------------------------
 

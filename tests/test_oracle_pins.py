@@ -310,3 +310,65 @@ def test_precision_at_k():
     idx, sim = od.exact_cosine_topk(X, X[:5], 3)
     assert idx[:, 0].tolist() == [0, 1, 2, 3, 4]                             # self is the nearest
     assert np.allclose(sim[:, 0], 1.0, atol=1e-6)
+
+
+# ------------------------------------------------------------- Algorithm 1 (K-Select)
+def _kselect_case(seed, n=400, d=24, m=5, Bq=4, Bd=3):
+    rng = np.random.default_rng(seed)
+    Xd = rng.standard_normal((n, d)).astype(np.float32)
+    Xd /= np.linalg.norm(Xd, axis=1, keepdims=True)
+    Xq = rng.standard_normal((m, d)).astype(np.float32)
+    Xq /= np.linalg.norm(Xq, axis=1, keepdims=True)
+    D = od.distance_matrix(od.pack_planes(od.encode(Xq, Bq, 2.0), Bq), od.pack_planes(od.encode(Xd, Bd, 2.0), Bd))
+    return Xd, Xq, D
+
+
+def test_histogram_boundary_is_kth_smallest_distance():
+    _, _, D = _kselect_case(31)
+    for q in range(D.shape[0]):
+        for K in (1, 2, 17, 399, 400):
+            assert od.kth_distance_by_histogram(D[q], K) == sorted(D[q].tolist())[K - 1]
+
+
+def test_candidates_are_exactly_rows_within_the_bound():
+    _, _, D = _kselect_case(32)
+    for extra in (0, 3, 40):
+        for K in (1, 10):
+            L = od.k_select_candidates(D[0], K, extra)
+            bound = sorted(D[0].tolist())[K - 1] + extra
+            assert sorted(L.tolist()) == [i for i in range(D.shape[1]) if D[0, i] <= bound]
+            keys = [(int(D[0, i]), int(i)) for i in L]
+            assert keys == sorted(keys) and len(L) >= K
+            assert od.k_select_candidates(D[0], K, extra, limit=K).tolist() == L[:K].tolist()
+
+
+def test_k_select_with_unbounded_extra_is_exact_search():
+    # once every row is a candidate the refine stage is plain exact search
+    Xd, Xq, D = _kselect_case(33)
+    idx, sim, count = od.k_select(D, Xd, Xq, 10, extra=int(D.max()))
+    ridx, rsim = od.exact_cosine_topk(Xd, Xq, 10)
+    assert (count == Xd.shape[0]).all()
+    assert np.array_equal(idx, ridx) and np.allclose(sim, rsim, atol=0)
+
+
+def test_k_select_refines_within_candidates_and_precision_grows_with_extra():
+    Xd, Xq, D = _kselect_case(34, n=3000, m=8)
+    real, _ = od.exact_cosine_topk(Xd, Xq, 10)
+    prev = -1.0
+    for extra in (0, 2, 5, 10, 20, 50, 100, 100000):
+        idx, sim, count = od.k_select(D, Xd, Xq, 10, extra)
+        for q in range(Xq.shape[0]):
+            L = set(od.k_select_candidates(D[q], 10, extra).tolist())
+            assert set(idx[q].tolist()) <= L                                   # only candidates are returned
+            assert (np.diff(sim[q]) <= 0).all()                                # sorted by similarity
+            want = sorted(L, key=lambda r: (-float(Xd[r].astype(np.float64) @ Xq[q].astype(np.float64)), r))[:10]
+            assert idx[q].tolist() == want                                     # brute-force re-ranking of L
+        p = od.precision_at_k(idx, real)
+        assert p >= prev - 1e-12                                               # nested candidate sets
+        prev = p
+    assert prev == 1.0
+
+
+def test_distance_from_score_roundtrip():
+    D = np.array([[0, 5, 77], [1, 2, 3]])
+    assert np.array_equal(od.distance_from_score(od.score_from_distance(D, 50, 4, 3), 50, 4, 3), D)
