@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--queries", type=int, default=0, help="use only the first N queries")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-recall", action="store_true")
+    ap.add_argument("--refine", type=int, default=-1, metavar="EXTRA",
+                    help="time the candidate search + fp32 refine (xbq_search_refine) with this extra distance")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (reference for HBM byte counters)")
     ap.add_argument("--set", action="append", default=[], metavar="NAME=VALUE",
@@ -118,14 +120,27 @@ def main():
         Xdb[lo:hi] = torch.from_numpy(wl.database(w, lo, hi)).cuda()
     db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, db_bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
     q = torch.empty(xbq.xbq_code_bytes(w.m, w.d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
-    ws = torch.empty(xbq.xbq_search_workspace_bytes(w.n, w.m, w.d, bits, k), dtype=torch.uint8, device="cuda")
+    if args.refine >= 0:
+        wsb = xbq.lib().xbq_search_refine_workspace_bytes(w.n, w.m, w.d, bits, k)
+        sim = torch.empty((w.m, k), dtype=torch.float32, device="cuda")
+        ncand = torch.empty((w.m,), dtype=torch.int32, device="cuda")
+    else:
+        wsb = xbq.xbq_search_workspace_bytes(w.n, w.m, w.d, bits, k)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
     idx = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
     score = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
+
+    def search():
+        if args.refine >= 0:
+            xbq.xbq_search_refine(Xdb, db, db_bits, Xq, q, bits, k, args.refine, workspace=ws, idx=idx, sim=sim,
+                                  cand=ncand)
+        else:
+            xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws, idx=idx, score=score)
 
     def step():
         xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)
         xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
-        xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws, idx=idx, score=score)
+        search()
 
     if args.calib_copy:
         src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device="cuda")      # 256 MiB
@@ -147,7 +162,7 @@ def main():
         xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)
         enc_ev[i][1].record()
         xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
-        xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws, idx=idx, score=score)
+        search()
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -184,7 +199,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: n={w.n} d={w.d} m={w.m} bits={bits}" +
                                (f"x{db_bits}" if db_bits != bits else "") + f" K={k} ({w.kind}, seed {w.seed})",
-                   "scale": scale, "options": args.set},
+                   "scale": scale, "options": args.set,
+                   "path": "xbq_search_refine extra=%d" % args.refine if args.refine >= 0 else "xbq_search"},
         "roofline": {
             "bound": "alu",
             "kernel": "scan (XOR + population count), all launches of one step",
@@ -205,6 +221,8 @@ def main():
     if not args.no_recall:
         r, nq = recall_at_k(Xdb, Xq, idx, k)
         out["recall_at_k"] = {"value": r, "queries": nq, "against": "exact fp32 cosine (torch matmul + topk)"}
+        if args.refine >= 0:
+            out["recall_at_k"]["mean_candidates"] = float(ncand.float().mean())
     del Xdb
     torch.cuda.empty_cache()
     if not args.no_cpu:

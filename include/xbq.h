@@ -109,6 +109,29 @@ int xbq_search_asym(const uint32_t* db_codes, int64_t n, int db_bits, const uint
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Search with the extra-distance candidate list and the exact refine of Algorithm 1
+ * (Section 3.6 "extra distance"; Section 4.1 "Histogram and Select" and "Refine").
+ * Per query: D_K = the K-th smallest distance over all n rows; the candidate list L holds
+ * every row with D <= D_K + extra_distance (ties included), in (D, row) order, cut to the
+ * first XBQ_REFINE_MAX_CANDIDATES if longer; each candidate's similarity is the fp32 inner
+ * product of its original row with the original query (lane-strided fused multiply-adds
+ * and a butterfly sum, so within a few ulp of the exact value); the K best by (similarity
+ * descending, row ascending) are returned.
+ *   X_db [n][d], X_q [m][d]  the fp32 vectors the codes were made from (device)
+ *   extra_distance           >= 0, in units of the integer distance D
+ *   idx [m][k] int32, similarity [m][k] fp32
+ *   candidates               [m] int32 = |L| per query, or NULL
+ *   workspace                at least xbq_search_refine_workspace_bytes(n, m, d, q_bits, k)
+ * Code widths as for xbq_search_asym (pass the same value twice for symmetric codes).
+ */
+#define XBQ_REFINE_MAX_CANDIDATES 2048
+size_t xbq_search_refine_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int k);
+int xbq_search_refine(const float* X_db, const uint32_t* db_codes, int64_t n, int db_bits,
+                      const float* X_q, const uint32_t* q_codes, int64_t m, int q_bits, int d, int k,
+                      int extra_distance, int32_t* idx, float* similarity, int32_t* candidates,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid.  While tracing is on, xbq_search brackets every launch of the scan
  * kernel (the XOR + population-count loop) with HIP events on the caller's stream.
  * xbq_trace_read waits for those events, returns the summed kernel time, the number of

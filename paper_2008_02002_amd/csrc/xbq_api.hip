@@ -61,11 +61,16 @@ struct Plan {
     int first = 0;                       // rows of the dense group
     int cap = 0;                         // candidate slots per query
     int64_t batch = 0;                   // queries per batch
+    int keep_max = 0;                    // keys kept per query (k, or the candidate bound when refining)
+    size_t off_len = 0;
     size_t off_thr = 0, off_cnt = 0, off_topk = 0, off_cand = 0, off_dense = 0, off_q = 0;
     size_t total = 0;
 };
 
-Plan make_plan(int64_t n, int64_t m, int d, int bits, int k)
+constexpr int kRefineKeep = 2048;    // candidate bound of the refine path
+constexpr int kRefineCap = 2048;     // survivor list of the refine path (keep + cap <= kSortCap)
+
+Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false)
 {
     Plan p;
     p.W = words32(d);
@@ -78,13 +83,16 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k)
     if (first > kSortCap) first = kSortCap;
     first = first / kLanes * kLanes;
     p.first = static_cast<int>(n < first ? n : first);
-    p.cap = 3 * kpad > 1024 ? 3 * kpad : 1024;
-    p.batch = m < kQueryBatch ? m : kQueryBatch;
+    p.cap = refine ? kRefineCap : (3 * kpad > 1024 ? 3 * kpad : 1024);
+    p.keep_max = refine ? kRefineKeep : k;
+    const int64_t max_batch = refine ? kQueryBatch / 2 : kQueryBatch;
+    p.batch = m < max_batch ? m : max_batch;
     const size_t b = static_cast<size_t>(p.batch);
     size_t off = 0;
     p.off_thr = off;   off = align_up(off + b * sizeof(uint32_t), 256);
     p.off_cnt = off;   off = align_up(off + b * sizeof(uint32_t), 256);
-    p.off_topk = off;  off = align_up(off + b * k * sizeof(uint64_t), 256);
+    p.off_len = off;   off = align_up(off + b * sizeof(uint32_t), 256);
+    p.off_topk = off;  off = align_up(off + b * p.keep_max * sizeof(uint64_t), 256);
     p.off_cand = off;  off = align_up(off + b * p.cap * sizeof(uint64_t), 256);
     p.off_dense = off; off = align_up(off + b * static_cast<size_t>(p.first) * sizeof(uint32_t), 256);
     p.off_q = off;
@@ -132,6 +140,145 @@ hipError_t traced_scan(const ScanArgs& a, bool dense, hipStream_t s)
         g_trace.pairs += static_cast<double>(a.row_end - a.row_begin) * a.m;
     }
     return hipSuccess;
+}
+
+// What one search call has to do; extra < 0 is the plain exact top-K, extra >= 0 the
+// candidate search of Algorithm 1 followed by the fp32 refine.
+struct SearchJob {
+    const uint32_t* db_codes; int64_t n; int db_bits;
+    const uint32_t* q_codes;  int64_t m; int q_bits;
+    int d, k, extra;
+    int32_t* idx;
+    int32_t* score;            // plain mode
+    const float* X_db;         // refine mode
+    const float* X_q;
+    float* similarity;
+    int32_t* candidates;
+};
+
+int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
+{
+    const uint32_t* db_codes = job.db_codes;
+    const uint32_t* q_codes = job.q_codes;
+    const int64_t n = job.n, m = job.m;
+    const int db_bits = job.db_bits, q_bits = job.q_bits, d = job.d, k = job.k;
+    const bool refine = job.extra >= 0;
+    const int rpl_max = (p.wc == 0 && db_bits * p.W <= 16) ? 2 : 1;
+    const int tile = p.wc ? kTileQ : 1;
+
+    for (int64_t qb = 0; qb < m; qb += p.batch) {
+        const int mb = static_cast<int>(m - qb < p.batch ? m - qb : p.batch);
+        const uint32_t* q_rows = q_codes + qb * (static_cast<int64_t>(q_bits) * p.W);
+
+        ScanArgs sa{};
+        sa.db = db_codes;
+        sa.n = n;
+        sa.m = mb;
+        sa.q_bits = q_bits;
+        sa.db_bits = db_bits;
+        sa.W = p.W;
+        sa.wc = p.wc;
+        sa.nchunks = p.nchunks;
+        sa.thr = reinterpret_cast<uint32_t*>(ws + p.off_thr);
+        sa.cnt = reinterpret_cast<uint32_t*>(ws + p.off_cnt);
+        sa.cand = reinterpret_cast<uint64_t*>(ws + p.off_cand);
+        sa.cap = p.cap;
+        sa.dense = reinterpret_cast<uint32_t*>(ws + p.off_dense);
+        sa.dense_stride = p.first;
+        if (p.wc) {
+            uint32_t* qc = reinterpret_cast<uint32_t*>(ws + p.off_q);
+            const hipError_t e = launch_repack_queries(q_rows, mb, q_bits, p.W, p.wc, p.nchunks, qc, s);
+            if (e != hipSuccess) return fail_hip(e);
+            sa.q = qc;
+        } else {
+            sa.q = q_rows;
+        }
+
+        SelectArgs sel{};
+        sel.m = mb;
+        sel.k = k;
+        sel.d = d;
+        sel.q_bits = q_bits;
+        sel.db_bits = db_bits;
+        sel.topk = reinterpret_cast<uint64_t*>(ws + p.off_topk);
+        sel.thr = reinterpret_cast<uint32_t*>(ws + p.off_thr);
+        sel.cnt = reinterpret_cast<uint32_t*>(ws + p.off_cnt);
+        sel.cand = sa.cand;
+        sel.cap = p.cap;
+        sel.dense = sa.dense;
+        sel.dense_stride = p.first;
+        sel.len = reinterpret_cast<uint32_t*>(ws + p.off_len);
+        sel.keep_max = p.keep_max;
+        sel.extra = job.extra;
+        sel.idx = job.idx + qb * k;
+        sel.score = refine ? nullptr : job.score + qb * k;
+
+        // group 0: dense
+        int64_t seen = p.first;
+        {
+            sa.row_begin = 0;
+            sa.row_end = seen;
+            const int64_t bundles = (seen + kLanes - 1) / kLanes;
+            sa.rows_per_lane = 1;
+            sa.qsplit = choose_qsplit(bundles, 1, mb, tile);
+            hipError_t e = traced_scan(sa, true, s);
+            if (e != hipSuccess) return fail_hip(e);
+            sel.row_begin = 0;
+            sel.rows = p.first;
+            sel.final_group = seen >= n;
+            e = launch_select_dense(sel, s);
+            if (e != hipSuccess) return fail_hip(e);
+        }
+        // later groups: threshold scan, merge, exact rescan of overflowed queries
+        while (seen < n) {
+            // expected survivors per query in a group are about k * (growth - 1): keep them
+            // at a third of the list capacity at most
+            double growth = 1.0 + static_cast<double>(p.cap) / (3.0 * k);
+            if (growth > g_opt.growth) growth = g_opt.growth;
+            if (refine && growth > 1.5) growth = 1.5;     // the kept list may be as long as the survivor list
+            int64_t size = static_cast<int64_t>(std::ceil(static_cast<double>(seen) * (growth - 1.0)));
+            size = (size + 511) / 512 * 512;
+            int64_t end = seen + size;
+            if (end > n || n - end < 512) end = n;
+            sa.row_begin = seen;
+            sa.row_end = end;
+            const int64_t bundles = (end - seen + kLanes - 1) / kLanes;
+            sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
+            sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, tile);
+            hipError_t e = traced_scan(sa, false, s);
+            if (e != hipSuccess) return fail_hip(e);
+            sel.row_begin = seen;
+            sel.final_group = end >= n;
+            MergeArgs ma{};
+            ma.db = db_codes;
+            ma.n = n;
+            ma.row_begin = seen;
+            ma.row_end = end;
+            ma.q_rows = q_rows;
+            ma.W = p.W;
+            ma.sel = sel;
+            e = launch_select_merge(ma, s);
+            if (e != hipSuccess) return fail_hip(e);
+            seen = end;
+        }
+        if (refine) {
+            RefineArgs ra{};
+            ra.X_db = job.X_db;
+            ra.X_q = job.X_q + qb * d;
+            ra.m = mb;
+            ra.k = k;
+            ra.d = d;
+            ra.topk = sel.topk;
+            ra.len = sel.len;
+            ra.keep_max = p.keep_max;
+            ra.idx = job.idx + qb * k;
+            ra.sim = job.similarity + qb * k;
+            ra.count = job.candidates ? job.candidates + qb : nullptr;
+            const hipError_t e = launch_refine(ra, s);
+            if (e != hipSuccess) return fail_hip(e);
+        }
+    }
+    return XBQ_OK;
 }
 
 }  // namespace
@@ -194,115 +341,54 @@ int xbq_search_asym(const uint32_t* db_codes, int64_t n, int db_bits, const uint
     if (d < 1 || db_bits < 1 || q_bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
     if (!valid_shape(d, db_bits) || !valid_shape(d, q_bits) || !scan_supports_bits(q_bits, db_bits))
         return XBQ_EUNSUPPORTED;
-    const int bits = q_bits;                             // the wider of the two: sizes the workspace
-    if (!valid_search_sizes(n, m, d, bits, k)) return XBQ_EINVAL;
+    if (!valid_search_sizes(n, m, d, q_bits, k)) return XBQ_EINVAL;
     if (n == 0 || m == 0) return XBQ_OK;
     if (!db_codes || !q_codes || !idx || !score || !workspace) return XBQ_EINVAL;
     if (reinterpret_cast<uintptr_t>(db_codes) % 4 || reinterpret_cast<uintptr_t>(q_codes) % 4 ||
         reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(score) % 4 ||
         reinterpret_cast<uintptr_t>(workspace) % 256)
         return XBQ_EINVAL;
-    const Plan p = make_plan(n, m, d, bits, k);
+    const Plan p = make_plan(n, m, d, q_bits, k, false);
     if (workspace_bytes < p.total) return XBQ_EWORKSPACE;
+    SearchJob job{};
+    job.db_codes = db_codes; job.n = n; job.db_bits = db_bits;
+    job.q_codes = q_codes; job.m = m; job.q_bits = q_bits;
+    job.d = d; job.k = k; job.extra = -1;
+    job.idx = idx; job.score = score;
+    return run_search(job, p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
 
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    char* ws = static_cast<char*>(workspace);
-    const int rpl_max = (p.wc == 0 && db_bits * p.W <= 16) ? 2 : 1;
-    const int tile = p.wc ? kTileQ : 1;
+size_t xbq_search_refine_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int k)
+{
+    if (!valid_search_sizes(n, m, d, q_bits, k)) return 0;
+    if (n == 0 || m == 0) return 256;
+    return make_plan(n, m, d, q_bits, k, true).total;
+}
 
-    for (int64_t qb = 0; qb < m; qb += p.batch) {
-        const int mb = static_cast<int>(m - qb < p.batch ? m - qb : p.batch);
-        const uint32_t* q_rows = q_codes + qb * (static_cast<int64_t>(q_bits) * p.W);
-
-        ScanArgs sa{};
-        sa.db = db_codes;
-        sa.n = n;
-        sa.m = mb;
-        sa.q_bits = q_bits;
-        sa.db_bits = db_bits;
-        sa.W = p.W;
-        sa.wc = p.wc;
-        sa.nchunks = p.nchunks;
-        sa.thr = reinterpret_cast<uint32_t*>(ws + p.off_thr);
-        sa.cnt = reinterpret_cast<uint32_t*>(ws + p.off_cnt);
-        sa.cand = reinterpret_cast<uint64_t*>(ws + p.off_cand);
-        sa.cap = p.cap;
-        sa.dense = reinterpret_cast<uint32_t*>(ws + p.off_dense);
-        sa.dense_stride = p.first;
-        if (p.wc) {
-            uint32_t* qc = reinterpret_cast<uint32_t*>(ws + p.off_q);
-            const hipError_t e = launch_repack_queries(q_rows, mb, q_bits, p.W, p.wc, p.nchunks, qc, s);
-            if (e != hipSuccess) return fail_hip(e);
-            sa.q = qc;
-        } else {
-            sa.q = q_rows;
-        }
-
-        SelectArgs sel{};
-        sel.m = mb;
-        sel.k = k;
-        sel.d = d;
-        sel.q_bits = q_bits;
-        sel.db_bits = db_bits;
-        sel.topk = reinterpret_cast<uint64_t*>(ws + p.off_topk);
-        sel.thr = reinterpret_cast<uint32_t*>(ws + p.off_thr);
-        sel.cnt = reinterpret_cast<uint32_t*>(ws + p.off_cnt);
-        sel.cand = sa.cand;
-        sel.cap = p.cap;
-        sel.dense = sa.dense;
-        sel.dense_stride = p.first;
-        sel.idx = idx + qb * k;
-        sel.score = score + qb * k;
-
-        // group 0: dense
-        int64_t seen = p.first;
-        {
-            sa.row_begin = 0;
-            sa.row_end = seen;
-            const int64_t bundles = (seen + kLanes - 1) / kLanes;
-            sa.rows_per_lane = 1;
-            sa.qsplit = choose_qsplit(bundles, 1, mb, tile);
-            hipError_t e = traced_scan(sa, true, s);
-            if (e != hipSuccess) return fail_hip(e);
-            sel.row_begin = 0;
-            sel.rows = p.first;
-            sel.final_group = seen >= n;
-            e = launch_select_dense(sel, s);
-            if (e != hipSuccess) return fail_hip(e);
-        }
-        // later groups: threshold scan, merge, exact rescan of overflowed queries
-        while (seen < n) {
-            // expected survivors per query in a group are about k * (growth - 1): keep them
-            // at a third of the list capacity at most
-            double growth = 1.0 + static_cast<double>(p.cap) / (3.0 * k);
-            if (growth > g_opt.growth) growth = g_opt.growth;
-            int64_t size = static_cast<int64_t>(std::ceil(static_cast<double>(seen) * (growth - 1.0)));
-            size = (size + 511) / 512 * 512;
-            int64_t end = seen + size;
-            if (end > n || n - end < 512) end = n;
-            sa.row_begin = seen;
-            sa.row_end = end;
-            const int64_t bundles = (end - seen + kLanes - 1) / kLanes;
-            sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
-            sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, tile);
-            hipError_t e = traced_scan(sa, false, s);
-            if (e != hipSuccess) return fail_hip(e);
-            sel.row_begin = seen;
-            sel.final_group = end >= n;
-            MergeArgs ma{};
-            ma.db = db_codes;
-            ma.n = n;
-            ma.row_begin = seen;
-            ma.row_end = end;
-            ma.q_rows = q_rows;
-            ma.W = p.W;
-            ma.sel = sel;
-            e = launch_select_merge(ma, s);
-            if (e != hipSuccess) return fail_hip(e);
-            seen = end;
-        }
-    }
-    return XBQ_OK;
+int xbq_search_refine(const float* X_db, const uint32_t* db_codes, int64_t n, int db_bits, const float* X_q,
+                      const uint32_t* q_codes, int64_t m, int q_bits, int d, int k, int extra_distance, int32_t* idx,
+                      float* similarity, int32_t* candidates, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (d < 1 || db_bits < 1 || q_bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
+    if (!valid_shape(d, db_bits) || !valid_shape(d, q_bits) || !scan_supports_bits(q_bits, db_bits))
+        return XBQ_EUNSUPPORTED;
+    if (!valid_search_sizes(n, m, d, q_bits, k)) return XBQ_EINVAL;
+    if (extra_distance < 0 || extra_distance > (1 << 30)) return XBQ_EINVAL;
+    if (n == 0 || m == 0) return XBQ_OK;
+    if (!X_db || !X_q || !db_codes || !q_codes || !idx || !similarity || !workspace) return XBQ_EINVAL;
+    if (reinterpret_cast<uintptr_t>(db_codes) % 4 || reinterpret_cast<uintptr_t>(q_codes) % 4 ||
+        reinterpret_cast<uintptr_t>(X_db) % 4 || reinterpret_cast<uintptr_t>(X_q) % 4 ||
+        reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(similarity) % 4 ||
+        reinterpret_cast<uintptr_t>(candidates) % 4 || reinterpret_cast<uintptr_t>(workspace) % 256)
+        return XBQ_EINVAL;
+    const Plan p = make_plan(n, m, d, q_bits, k, true);
+    if (workspace_bytes < p.total) return XBQ_EWORKSPACE;
+    SearchJob job{};
+    job.db_codes = db_codes; job.n = n; job.db_bits = db_bits;
+    job.q_codes = q_codes; job.m = m; job.q_bits = q_bits;
+    job.d = d; job.k = k; job.extra = extra_distance;
+    job.idx = idx; job.X_db = X_db; job.X_q = X_q; job.similarity = similarity; job.candidates = candidates;
+    return run_search(job, p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 int xbq_trace_enable(int on)

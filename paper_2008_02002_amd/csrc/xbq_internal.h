@@ -68,16 +68,20 @@ hipError_t launch_encode(const float* X, int64_t n, int d, int bits, float scale
 struct SelectArgs {
     int m, k, d;
     int q_bits, db_bits;
-    uint64_t* topk;          // [m][k] best keys so far, ascending
-    uint32_t* thr;           // [m] D of the k-th best key
-    uint32_t* cnt;           // [m]
+    uint64_t* topk;          // [m][keep_max] best keys so far, ascending
+    uint32_t* len;           // [m] keys held in topk[q]; unused (always k) when extra < 0
+    int keep_max;            // row stride of topk: k for plain top-K, the candidate bound otherwise
+    int extra;               // < 0: plain top-K.  >= 0: keep every key with D <= D_k + extra
+                             // (Algorithm 1's candidate list), at most keep_max of them
+    uint32_t* thr;           // [m] a later row is of interest when its D < thr[q]
+    uint32_t* cnt;           // [m] survivors appended by the scan
     const uint64_t* cand;    // [m][cap]
     int cap;
     const uint32_t* dense;   // [m][dense_stride]
     int dense_stride;
     int64_t row_begin;       // first row of the group just scanned
     int rows;                // rows in the dense group
-    int final_group;         // 1 = also write idx / score
+    int final_group;         // 1 = last group: plain mode also writes idx / score
     int32_t* idx;            // [m][k]
     int32_t* score;          // [m][k]
 };
@@ -94,5 +98,20 @@ struct MergeArgs {
 
 hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s);
 hipError_t launch_select_merge(const MergeArgs& a, hipStream_t s);
+
+// Refine stage of Algorithm 1: exact fp32 inner products of the kept candidates with the
+// query, sorted by similarity (descending, ties to the lower row); first k are written.
+struct RefineArgs {
+    const float* X_db;       // [n][d]
+    const float* X_q;        // [m][d] (this batch)
+    int m, k, d;
+    const uint64_t* topk;    // [m][keep_max] candidate keys
+    const uint32_t* len;     // [m]
+    int keep_max;
+    int32_t* idx;            // [m][k]
+    float* sim;              // [m][k]
+    int32_t* count;          // [m] candidates refined per query, or nullptr
+};
+hipError_t launch_refine(const RefineArgs& a, hipStream_t s);
 
 }  // namespace xbq

@@ -53,19 +53,45 @@ __device__ __forceinline__ void write_result(const SelectArgs& a, int q, const u
     }
 }
 
-__device__ __forceinline__ void write_topk(const SelectArgs& a, int q, const uint64_t* keys)
+// Store the head of the sorted keys as the query's new list and derive its threshold.
+// Plain top-K: the first k keys; later rows matter only if D < D_k (an equal D loses the tie
+// to the rows already held, which all have lower numbers).  Candidate mode (extra >= 0):
+// every key with D <= D_k + extra, at most keep_max (the best by key); later rows matter if
+// D <= D_k + extra and, once the list is cut, only if they beat its last key.
+// `have` sorted keys are in LDS; all threads call this, with a barrier before it.
+__device__ void write_topk(const SelectArgs& a, int q, const uint64_t* keys, int have, int* scratch)
 {
-    for (int t = threadIdx.x; t < a.k; t += blockDim.x) a.topk[static_cast<size_t>(q) * a.k + t] = keys[t];
-    if (threadIdx.x == 0) {
-        a.thr[q] = static_cast<uint32_t>(keys[a.k - 1] >> 32);
+    const uint32_t dk = static_cast<uint32_t>(keys[a.k - 1] >> 32);
+    int keep = a.k;
+    if (a.extra >= 0) {
+        const uint32_t bound = dk + static_cast<uint32_t>(a.extra);
+        if (threadIdx.x == 0) *scratch = have;                       // all keys within the bound
+        __syncthreads();
+        for (int t = threadIdx.x; t + 1 < have; t += blockDim.x)     // sorted: find the single step
+            if (static_cast<uint32_t>(keys[t] >> 32) <= bound && static_cast<uint32_t>(keys[t + 1] >> 32) > bound)
+                *scratch = t + 1;
+        __syncthreads();
+        const bool cut = *scratch > a.keep_max;                      // more candidates than may be kept
+        keep = cut ? a.keep_max : *scratch;
+        if (threadIdx.x == 0) {
+            a.len[q] = static_cast<uint32_t>(keep);
+            // a cut list holds the keep_max best keys: a later row gets in only with a smaller
+            // D than the last one kept (an equal D has a higher row number and stays out)
+            a.thr[q] = cut ? static_cast<uint32_t>(keys[keep - 1] >> 32) : bound + 1;
+            a.cnt[q] = 0;
+        }
+    } else if (threadIdx.x == 0) {
+        a.thr[q] = dk;
         a.cnt[q] = 0;
     }
-    if (a.final_group) write_result(a, q, keys);
+    for (int t = threadIdx.x; t < keep; t += blockDim.x) a.topk[static_cast<size_t>(q) * a.keep_max + t] = keys[t];
+    if (a.final_group && a.extra < 0) write_result(a, q, keys);
 }
 
 __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
 {
     __shared__ uint64_t keys[kSortCap];
+    __shared__ int scratch;
     const int q = blockIdx.x;
     const int P = next_pow2(a.rows);
     const uint32_t* src = a.dense + static_cast<size_t>(q) * a.dense_stride;
@@ -73,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
         keys[t] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
     __syncthreads();
     bitonic_sort_lds(keys, P);
-    write_topk(a, q, keys);
+    write_topk(a, q, keys, a.rows, &scratch);
 }
 
 // Eq. 6 for one (row, query) with run-time sizes; slow path used only by the rescan.
@@ -98,10 +124,11 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill
 {
     const SelectArgs& a = r.sel;
     const uint32_t* yq = r.q_rows + static_cast<size_t>(q) * a.q_bits * r.W;
-    for (int t = threadIdx.x; t < a.k; t += blockDim.x) keys[t] = a.topk[static_cast<size_t>(q) * a.k + t];
-    if (threadIdx.x == 0) *fill = a.k;
+    const int held = a.extra >= 0 ? static_cast<int>(a.len[q]) : a.k;
+    for (int t = threadIdx.x; t < held; t += blockDim.x) keys[t] = a.topk[static_cast<size_t>(q) * a.keep_max + t];
+    if (threadIdx.x == 0) *fill = held;
     __syncthreads();
-    uint32_t thr = static_cast<uint32_t>(keys[a.k - 1] >> 32);
+    uint32_t thr = a.thr[q];
     for (int64_t base = r.row_begin; base < r.row_end; base += blockDim.x) {
         const int64_t row = base + threadIdx.x;
         if (row < r.row_end) {
@@ -115,8 +142,27 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill
             for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
             __syncthreads();
             bitonic_sort_lds(keys, P);
-            thr = static_cast<uint32_t>(keys[a.k - 1] >> 32);
-            if (threadIdx.x == 0) *fill = a.k;
+            // cut back to what is still of interest; the threshold can only tighten
+            const uint32_t dk = static_cast<uint32_t>(keys[a.k - 1] >> 32);
+            const uint32_t now = a.extra >= 0 ? dk + static_cast<uint32_t>(a.extra) + 1 : dk;
+            thr = now < thr ? now : thr;
+            int keep = a.k;
+            if (a.extra >= 0) {
+                __syncthreads();
+                if (threadIdx.x == 0) *fill = have;
+                __syncthreads();
+                for (int t = threadIdx.x; t + 1 < have; t += blockDim.x)
+                    if (static_cast<uint32_t>(keys[t] >> 32) < thr && static_cast<uint32_t>(keys[t + 1] >> 32) >= thr)
+                        *fill = t + 1;
+                __syncthreads();
+                keep = *fill < a.keep_max ? *fill : a.keep_max;
+                if (*fill > a.keep_max) {
+                    const uint32_t last = static_cast<uint32_t>(keys[keep - 1] >> 32);
+                    thr = last < thr ? last : thr;
+                }
+                __syncthreads();
+            }
+            if (threadIdx.x == 0) *fill = keep;
         }
         __syncthreads();
     }
@@ -125,7 +171,7 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill
     for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
     __syncthreads();
     bitonic_sort_lds(keys, P);
-    write_topk(a, q, keys);
+    write_topk(a, q, keys, have, fill);
 }
 
 __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r)
@@ -139,16 +185,70 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r)
         rescan_rows(r, q, keys, &fill);
         return;
     }
-    if (c == 0 && !a.final_group) return;            // nothing beat the threshold
-    const int total = a.k + static_cast<int>(c);
+    if (c == 0 && !(a.final_group && a.extra < 0)) return;       // nothing new: list and threshold stand
+    const int held = a.extra >= 0 ? static_cast<int>(a.len[q]) : a.k;
+    const int total = held + static_cast<int>(c);
     const int P = next_pow2(total);
-    const uint64_t* best = a.topk + static_cast<size_t>(q) * a.k;
+    const uint64_t* best = a.topk + static_cast<size_t>(q) * a.keep_max;
     const uint64_t* cand = a.cand + static_cast<size_t>(q) * a.cap;
     for (int t = threadIdx.x; t < P; t += blockDim.x)
-        keys[t] = t < a.k ? best[t] : (t < total ? cand[t - a.k] : kPadKey);
+        keys[t] = t < held ? best[t] : (t < total ? cand[t - held] : kPadKey);
     __syncthreads();
     if (c != 0) bitonic_sort_lds(keys, P);
-    write_topk(a, q, keys);
+    write_topk(a, q, keys, total, &fill);
+}
+
+// ---------------------------------------------------------------------------------------
+// Refine (Algorithm 1, last loop; Section 4.1 "Refine").  One workgroup per query: the query
+// vector sits in LDS, each wavefront takes candidates in turn, reads the candidate's fp32 row
+// with coalesced loads and reduces the products across its lanes; the similarities are then
+// sorted (descending, ties to the lower row) as 64-bit keys.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t descending_bits(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);     // ascending order of floats as unsigned
+    return ~u;                                           // reversed: larger float = smaller key
+}
+
+__device__ __forceinline__ float bits_to_float_descending(uint32_t k)
+{
+    uint32_t u = ~k;
+    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+    return __uint_as_float(u);
+}
+
+__global__ __launch_bounds__(kBlock) void refine_topk(const RefineArgs a)
+{
+    extern __shared__ uint64_t lds64[];
+    uint64_t* keys = lds64;                              // kSortCap keys
+    float* qv = reinterpret_cast<float*>(lds64 + kSortCap);   // d floats
+    const int q = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int have = static_cast<int>(a.len[q]);
+    const float* xq = a.X_q + static_cast<size_t>(q) * a.d;
+    for (int c = threadIdx.x; c < a.d; c += blockDim.x) qv[c] = xq[c];
+    __syncthreads();
+    const uint64_t* list = a.topk + static_cast<size_t>(q) * a.keep_max;
+    for (int t = wave; t < have; t += 4) {
+        const uint32_t row = static_cast<uint32_t>(list[t] & 0xffffffffu);
+        const float* xr = a.X_db + static_cast<size_t>(row) * a.d;
+        float s = 0.0f;
+        for (int c = lane; c < a.d; c += 64) s = fmaf(xr[c], qv[c], s);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+        if (lane == 0) keys[t] = (static_cast<uint64_t>(descending_bits(s)) << 32) | row;
+    }
+    const int P = next_pow2(have);
+    for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
+    __syncthreads();
+    bitonic_sort_lds(keys, P);
+    for (int t = threadIdx.x; t < a.k; t += blockDim.x) {
+        const uint64_t key = keys[t];
+        a.idx[static_cast<size_t>(q) * a.k + t] = static_cast<int32_t>(key & 0xffffffffu);
+        a.sim[static_cast<size_t>(q) * a.k + t] = bits_to_float_descending(static_cast<uint32_t>(key >> 32));
+    }
+    if (a.count != nullptr && threadIdx.x == 0) a.count[q] = have;
 }
 
 hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s)
@@ -159,10 +259,19 @@ hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s)
     return hipGetLastError();
 }
 
+hipError_t launch_refine(const RefineArgs& a, hipStream_t s)
+{
+    if (a.m <= 0) return hipSuccess;
+    if (a.keep_max > kSortCap || a.k > a.keep_max) return hipErrorInvalidValue;
+    const size_t lds = kSortCap * sizeof(uint64_t) + static_cast<size_t>(a.d) * sizeof(float);
+    hipLaunchKernelGGL(refine_topk, dim3(a.m), dim3(kBlock), lds, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_select_merge(const MergeArgs& r, hipStream_t s)
 {
     if (r.sel.m <= 0) return hipSuccess;
-    if (r.sel.k + r.sel.cap > kSortCap || r.row_end > r.n || r.row_begin < 0) return hipErrorInvalidValue;
+    if (r.sel.keep_max + r.sel.cap > kSortCap || r.row_end > r.n || r.row_begin < 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(select_merge, dim3(r.sel.m), dim3(kBlock), 0, s, r);
     return hipGetLastError();
 }

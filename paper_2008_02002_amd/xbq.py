@@ -15,10 +15,11 @@ LIB_PATH = os.path.join(_HERE, "libxbq.so")
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 ROWS, BUNDLE64 = 0, 1
 MAX_BITS, MAX_DIM, MAX_K = 4, 2048, 1024
+REFINE_MAX_CANDIDATES = 2048
 
 EXPORTS = (
     "xbq_version", "xbq_strerror", "xbq_last_hip_error", "xbq_code_bytes", "xbq_encode",
-    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_trace_enable", "xbq_trace_read",
+    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_trace_enable", "xbq_trace_read",
     "xbq_set_option",
 )
 
@@ -58,6 +59,10 @@ def lib() -> ctypes.CDLL:
         L.xbq_search.restype = i32
         L.xbq_search_asym.argtypes = [vp, i64, i32, vp, i64, i32, i32, i32, vp, vp, vp, sz, vp]
         L.xbq_search_asym.restype = i32
+        L.xbq_search_refine_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
+        L.xbq_search_refine_workspace_bytes.restype = sz
+        L.xbq_search_refine.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+        L.xbq_search_refine.restype = i32
         L.xbq_trace_enable.argtypes = [i32]
         L.xbq_trace_enable.restype = i32
         L.xbq_trace_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64),
@@ -157,6 +162,35 @@ def xbq_search_asym(db_codes, n: int, db_bits: int, q_codes, m: int, q_bits: int
                                _stream())
     _check(rc, "xbq_search_asym")
     return idx, score
+
+
+def xbq_search_refine(X_db, db_codes, db_bits: int, X_q, q_codes, q_bits: int, k: int, extra_distance: int,
+                      workspace=None, idx=None, sim=None, cand=None):
+    """Candidate search + fp32 refine.  Returns (idx int32 [m, k], similarity fp32 [m, k],
+    candidates int32 [m]) CUDA tensors."""
+    import torch
+    n, d = X_db.shape
+    m = X_q.shape[0]
+    for t in (X_db, X_q):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+            raise ValueError("X_db and X_q must be contiguous fp32 CUDA tensors")
+    need = lib().xbq_search_refine_workspace_bytes(n, m, d, q_bits, k)
+    if need == 0:
+        raise XbqError(EINVAL, "xbq_search_refine_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X_db.device)
+    if idx is None:
+        idx = torch.empty((m, k), dtype=torch.int32, device=X_db.device)
+    if sim is None:
+        sim = torch.empty((m, k), dtype=torch.float32, device=X_db.device)
+    if cand is None:
+        cand = torch.empty((m,), dtype=torch.int32, device=X_db.device)
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    rc = lib().xbq_search_refine(p(X_db), p(db_codes), n, db_bits, p(X_q), p(q_codes), m, q_bits, d, k,
+                                 int(extra_distance), p(idx), p(sim), p(cand), p(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "xbq_search_refine")
+    return idx, sim, cand
 
 
 def xbq_trace_enable(on: bool):

@@ -114,6 +114,27 @@ def test_search_asym_argument_errors(L):
     assert s(n=0) == xbq.OK
 
 
+def test_search_refine_argument_errors(L):
+    fake = ctypes.c_void_p(0x1000)
+    null = ctypes.c_void_p(0)
+
+    def s(xdb=fake, xq=fake, n=1000, m=10, d=128, k=10, extra=5, db_bits=3, q_bits=4, sim=fake, wsb=1 << 40):
+        return L.xbq_search_refine(xdb, fake, n, db_bits, xq, fake, m, q_bits, d, k, extra, fake, sim, null,
+                                   fake, wsb, null)
+
+    assert s(xdb=null) == xbq.EINVAL
+    assert s(xq=null) == xbq.EINVAL
+    assert s(sim=null) == xbq.EINVAL
+    assert s(extra=-1) == xbq.EINVAL
+    assert s(k=0) == xbq.EINVAL
+    assert s(db_bits=4, q_bits=3) == xbq.EUNSUPPORTED
+    need = L.xbq_search_refine_workspace_bytes(1000, 10, 128, 4, 10)
+    assert need > L.xbq_search_workspace_bytes(1000, 10, 128, 4, 10)
+    assert s(wsb=need - 1) == xbq.EWORKSPACE
+    assert s(m=0) == xbq.OK
+    assert L.xbq_search_refine_workspace_bytes(1000, 10, 128, 4, 0) == 0
+
+
 def test_workspace_bytes(L):
     f = L.xbq_search_workspace_bytes
     assert f(1000, 10, 128, 4, 0) == 0

@@ -84,3 +84,27 @@ def test_c4_full_size():
 
 def test_c5_full_size():
     _run("C5", 4, (100,), 300)
+
+
+def test_c2_full_size_refine_4x3():
+    """Algorithm 1 end to end at full size: 4-bit queries, 3-bit rows, extra distance, fp32
+    refine.  The oracle runs a subset of queries over the whole database."""
+    import torch
+    from oracle import definition as od
+    w = wl.WORKLOADS["C2"]
+    k, extra, qb, db_bits = 100, 100, 4, 3
+    X, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
+    xd, xq = torch.from_numpy(X).cuda(), torch.from_numpy(Xq).cuda()
+    db = xbq.xbq_encode(xd, db_bits, scale, xbq.BUNDLE64)
+    q = xbq.xbq_encode(xq, qb, scale, xbq.ROWS)
+    idx, sim, cand = xbq.xbq_search_refine(xd, db, db_bits, xq, q, qb, k, extra)
+    torch.cuda.synchronize()
+    idx, sim, cand = idx.cpu().numpy(), sim.cpu().numpy(), cand.cpu().numpy()
+    _say("C2 refine: searched on the GPU")
+    sub = np.concatenate([np.arange(40), w.m - 1 - np.arange(40)])
+    S = oc.scores(oc.encode(X, db_bits, scale), oc.encode(Xq[sub], qb, scale), w.d)
+    D = od.distance_from_score(S, w.d, qb, db_bits)
+    _say("C2 refine: oracle distances done")
+    gu.assert_refined_matches((idx[sub], sim[sub], cand[sub]), X, Xq[sub], D, k, extra, xbq.REFINE_MAX_CANDIDATES)
+    real, _ = od.exact_cosine_topk(X, Xq[sub[:16]], k)
+    assert od.precision_at_k(idx[sub[:16]], real) > 0.9

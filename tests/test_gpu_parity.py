@@ -185,6 +185,50 @@ def test_asymmetric_unsupported_pairs_are_refused():
         assert e.value.code == xbq.EUNSUPPORTED
 
 
+REFINE = [
+    # n, d, m, q_bits, db_bits, k, extra
+    (6000, 128, 20, 4, 4, 10, 0),
+    (6000, 128, 20, 4, 3, 10, 20),
+    (30000, 128, 40, 4, 3, 100, 40),
+    (30000, 96, 40, 4, 4, 100, 200),
+    (20000, 200, 30, 4, 3, 10, 64),
+    (4000, 960, 12, 4, 3, 10, 300),
+    (3000, 64, 10, 3, 3, 1024, 10),
+    (2000, 32, 16, 2, 2, 5, 3),
+    (900, 128, 7, 4, 3, 10, 100000),       # every row is a candidate
+]
+
+
+@pytest.mark.parametrize("n,d,m,qb,db,k,extra", REFINE)
+def test_search_refine_matches_algorithm_1(n, d, m, qb, db, k, extra):
+    _say(f"refine n={n} d={d} m={m} {qb}x{db} k={k} extra={extra}")
+    rng = np.random.default_rng(n + d + extra)
+    Xdb = rng.standard_normal((n, d)).astype(np.float32)
+    Xdb /= np.linalg.norm(Xdb, axis=1, keepdims=True)
+    Xq = rng.standard_normal((m, d)).astype(np.float32)
+    Xq /= np.linalg.norm(Xq, axis=1, keepdims=True)
+    scale = wl.choose_scale(Xdb)
+    got = gu.gpu_search_refine(Xdb, Xq, db, qb, k, extra, scale)
+    D = gu.oracle_distances(Xdb, Xq, db, qb, scale)
+    gu.assert_refined_matches(got, Xdb, Xq, D, k, extra, xbq.REFINE_MAX_CANDIDATES)
+
+
+def test_refine_on_clustered_rows_and_sorted_rows():
+    w = wl.scaled_down(wl.WORKLOADS["C4"], n=120_000, m=48)
+    Xdb, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
+    for extra in (0, 30, 120):
+        _say(f"refine C4 stand-in extra={extra}")
+        got = gu.gpu_search_refine(Xdb, Xq, 3, 4, 10, extra, scale)
+        D = gu.oracle_distances(Xdb, Xq, 3, 4, scale)
+        gu.assert_refined_matches(got, Xdb, Xq, D, 10, extra, xbq.REFINE_MAX_CANDIDATES)
+    # adversarial order: rows ever closer to the query overflow the survivor lists
+    order = np.argsort(Xdb @ Xq[0])
+    Xs = np.ascontiguousarray(Xdb[order][:40_000])
+    got = gu.gpu_search_refine(Xs, Xq[:4], 3, 4, 10, 50, scale)
+    D = gu.oracle_distances(Xs, Xq[:4], 3, 4, scale)
+    gu.assert_refined_matches(got, Xs, Xq[:4], D, 10, 50, xbq.REFINE_MAX_CANDIDATES)
+
+
 def test_all_scores_tied():
     # non-negative data at scale 1: every coordinate falls in the same cell, all scores equal
     w = wl.scaled_down(wl.WORKLOADS["C3"], n=30_000, m=16)
