@@ -147,6 +147,9 @@ int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
  *             automatically for large k so the survivor lists stay short)
  *   "first"   rows scored densely before any threshold exists (default 1024)
  *   "qsplit"  queries per workgroup (0 = automatic)
+ *   "selector"          0 = automatic, 1 = threshold filter with growing row groups (many
+ *                       queries), 2 = histogram selection (few queries; Section 4.1)
+ *   "hist_max_queries"  automatic choice: histogram selection up to this many queries
  * Returns XBQ_EINVAL for an unknown name or a value out of range.
  */
 int xbq_set_option(const char* name, double value);

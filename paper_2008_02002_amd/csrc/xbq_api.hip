@@ -27,6 +27,8 @@ struct Options {
     double growth = 4.0;
     int first = 1024;
     int qsplit = 0;
+    int selector = 0;                // 0 automatic, 1 threshold filter, 2 histogram
+    int hist_max_queries = 16;       // automatic choice: histogram selection up to this many queries
 } g_opt;
 
 struct Trace {
@@ -64,8 +66,15 @@ struct Plan {
     int keep_max = 0;                    // keys kept per query (k, or the candidate bound when refining)
     size_t off_len = 0;
     size_t off_thr = 0, off_cnt = 0, off_topk = 0, off_cand = 0, off_dense = 0, off_q = 0;
+    // histogram selection (aliases the regions above: one call runs one of the two paths)
+    bool hist = false;
+    int hist_wc = 0, hist_nchunks = 0, hist_shift = 0;
+    size_t hoff_q = 0, hoff_zero = 0, hoff_dist = 0, hoff_cand = 0;
+    size_t zero_words = 0;               // hist + cand_cnt, cleared in one go
     size_t total = 0;
 };
+
+constexpr int64_t kHistMaxDistBytes = int64_t(1) << 30;   // stored distances of one pass
 
 constexpr int kRefineKeep = 2048;    // candidate bound of the refine path
 constexpr int kRefineCap = 2048;     // survivor list of the refine path (keep + cap <= kSortCap)
@@ -98,6 +107,26 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false
     p.off_q = off;
     if (p.wc) off = align_up(off + b * p.nchunks * bits * p.wc * sizeof(uint32_t), 256);
     p.total = off;
+
+    // histogram selection: eligible for plain top-K when the stored distances stay moderate
+    const bool want = g_opt.selector == 2 || (g_opt.selector == 0 && m <= g_opt.hist_max_queries);
+    const int hq = static_cast<int>(m < kHistMaxQueries ? m : kHistMaxQueries);
+    if (!refine && want && m <= p.batch && n * int64_t(4) * hq <= kHistMaxDistBytes) {
+        p.hist = true;
+        p.hist_wc = p.wc ? p.wc : p.W;
+        p.hist_nchunks = p.wc ? p.nchunks : 1;
+        const int64_t dmax = static_cast<int64_t>(d) * ((1 << bits) - 1) * ((1 << bits) - 1);
+        while ((dmax >> p.hist_shift) >= kHistBins) ++p.hist_shift;
+        size_t h = 0;
+        p.hoff_q = h;
+        if (p.wc) h = align_up(h + b * p.nchunks * bits * p.wc * sizeof(uint32_t), 256);
+        p.hoff_zero = h;
+        p.zero_words = static_cast<size_t>(hq) * (kHistBins + 1);
+        h = align_up(h + p.zero_words * sizeof(uint32_t), 256);
+        p.hoff_cand = h;  h = align_up(h + static_cast<size_t>(hq) * kSortCap * sizeof(uint64_t), 256);
+        p.hoff_dist = h;  h = align_up(h + static_cast<size_t>(hq) * n * sizeof(uint32_t), 256);
+        if (h > p.total) p.total = h;
+    }
     return p;
 }
 
@@ -156,6 +185,72 @@ struct SearchJob {
     int32_t* candidates;
 };
 
+// Histogram selection: queries in passes of kHistMaxQueries, three launches per pass.
+int run_hist_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
+{
+    const int64_t n = job.n, m = job.m;
+    const uint32_t* q_all = job.q_codes;
+    if (p.wc) {                                          // long codes: chunk-major padded query copy
+        uint32_t* qc = reinterpret_cast<uint32_t*>(ws + p.hoff_q);
+        for (int64_t qb = 0; qb < m; qb += p.batch) {    // p.batch >= m here (m is small)
+            const int mb = static_cast<int>(m - qb < p.batch ? m - qb : p.batch);
+            const hipError_t e = launch_repack_queries(job.q_codes + qb * (static_cast<int64_t>(job.q_bits) * p.W), mb,
+                                                       job.q_bits, p.W, p.wc, p.nchunks,
+                                                       qc + qb * (static_cast<int64_t>(p.nchunks) * job.q_bits * p.wc), s);
+            if (e != hipSuccess) return fail_hip(e);
+        }
+        q_all = qc;
+    }
+    const int64_t q_stride = static_cast<int64_t>(p.hist_nchunks) * job.q_bits * p.hist_wc;
+    uint32_t* zero = reinterpret_cast<uint32_t*>(ws + p.hoff_zero);
+    for (int64_t qb = 0; qb < m; qb += kHistMaxQueries) {
+        const int mb = static_cast<int>(m - qb < kHistMaxQueries ? m - qb : kHistMaxQueries);
+        hipError_t e = launch_clear(zero, static_cast<int64_t>(p.zero_words), s);
+        if (e != hipSuccess) return fail_hip(e);
+        HistArgs ha{};
+        ha.db = job.db_codes;
+        ha.n = n;
+        ha.q = q_all + qb * q_stride;
+        ha.m = mb;
+        ha.q_bits = job.q_bits;
+        ha.db_bits = job.db_bits;
+        ha.W = p.W;
+        ha.wc = p.hist_wc;
+        ha.nchunks = p.hist_nchunks;
+        ha.dist = reinterpret_cast<uint32_t*>(ws + p.hoff_dist);
+        ha.hist = zero;
+        ha.shift = p.hist_shift;
+        const bool rec = g_trace.on && g_trace.used + 2 <= static_cast<int>(g_trace.ev.size());
+        if (rec && (e = hipEventRecord(g_trace.ev[g_trace.used], s)) != hipSuccess) return fail_hip(e);
+        e = launch_scan_hist(ha, s);
+        if (e != hipSuccess) return fail_hip(e);
+        if (rec) {
+            if ((e = hipEventRecord(g_trace.ev[g_trace.used + 1], s)) != hipSuccess) return fail_hip(e);
+            g_trace.used += 2;
+            g_trace.pairs += static_cast<double>(n) * mb;
+        }
+        CollectArgs ca{};
+        ca.dist = ha.dist;
+        ca.hist = zero;
+        ca.n = n;
+        ca.m = mb;
+        ca.k = job.k;
+        ca.d = job.d;
+        ca.q_bits = job.q_bits;
+        ca.db_bits = job.db_bits;
+        ca.shift = p.hist_shift;
+        ca.rows_per_block = 16 * 16 * kBlock;         // 65536 rows per workgroup
+        ca.blocks_per_query = static_cast<int>((n + ca.rows_per_block - 1) / ca.rows_per_block);
+        ca.cand = reinterpret_cast<uint64_t*>(ws + p.hoff_cand);
+        ca.cand_cnt = zero + static_cast<size_t>(kHistMaxQueries < m ? kHistMaxQueries : m) * kHistBins;
+        ca.idx = job.idx + qb * job.k;
+        ca.score = job.score + qb * job.k;
+        e = launch_hist_collect(ca, s);
+        if (e != hipSuccess) return fail_hip(e);
+    }
+    return XBQ_OK;
+}
+
 int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
 {
     const uint32_t* db_codes = job.db_codes;
@@ -165,6 +260,8 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
     const bool refine = job.extra >= 0;
     const int rpl_max = (p.wc == 0 && db_bits * p.W <= 16) ? 2 : 1;
     const int tile = p.wc ? kTileQ : 1;
+
+    if (p.hist && !refine) return run_hist_search(job, p, ws, s);
 
     for (int64_t qb = 0; qb < m; qb += p.batch) {
         const int mb = static_cast<int>(m - qb < p.batch ? m - qb : p.batch);
@@ -437,6 +534,16 @@ int xbq_set_option(const char* name, double value)
     if (!std::strcmp(name, "first")) {
         if (!(value >= 64 && value <= kSortCap)) return XBQ_EINVAL;
         g_opt.first = static_cast<int>(value);
+        return XBQ_OK;
+    }
+    if (!std::strcmp(name, "selector")) {
+        if (!(value == 0 || value == 1 || value == 2)) return XBQ_EINVAL;
+        g_opt.selector = static_cast<int>(value);
+        return XBQ_OK;
+    }
+    if (!std::strcmp(name, "hist_max_queries")) {
+        if (!(value >= 0 && value <= (1 << 20))) return XBQ_EINVAL;
+        g_opt.hist_max_queries = static_cast<int>(value);
         return XBQ_OK;
     }
     if (!std::strcmp(name, "qsplit")) {

@@ -13,6 +13,8 @@ constexpr int kLanes = 64;        // wavefront width on gfx950
 constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts, one per SIMD)
 constexpr int kSortCap = 4096;    // most 64-bit keys one workgroup sorts in LDS
 constexpr int kTileQ = 16;        // queries per register tile of the word-chunked scan
+constexpr int kHistBins = 1024;   // histogram bins per query (histogram selection)
+constexpr int kHistMaxQueries = 8;  // queries per pass of the histogram selection
 
 // A candidate is ordered by the 64-bit key (D << 32) | row: smaller key = better
 // (smaller distance D, then lower row number).  D is the Eq. 6 distance.
@@ -113,5 +115,35 @@ struct RefineArgs {
     int32_t* count;          // [m] candidates refined per query, or nullptr
 };
 hipError_t launch_refine(const RefineArgs& a, hipStream_t s);
+
+// Histogram selection (few queries): see xbq_hist.hip.
+struct HistArgs {
+    const uint32_t* db;      // XBQ_BUNDLE64 codes
+    int64_t n;
+    const uint32_t* q;       // [m][nchunks][q_bits][wc]
+    int m;                   // 1..kHistMaxQueries
+    int q_bits, db_bits;
+    int W, wc, nchunks;
+    uint32_t* dist;          // [m][n] distances, written
+    uint32_t* hist;          // [m][kHistBins], zero on entry
+    int shift;               // bin = D >> shift  (< kHistBins for every possible D)
+};
+
+struct CollectArgs {
+    const uint32_t* dist;    // [m][n]
+    const uint32_t* hist;    // [m][kHistBins]
+    int64_t n;
+    int m, k, d, q_bits, db_bits, shift;
+    int rows_per_block;      // rows of dist one workgroup filters
+    int blocks_per_query;    // ceil(n / rows_per_block)
+    uint64_t* cand;          // [m][kSortCap]
+    uint32_t* cand_cnt;      // [m], zero on entry
+    int32_t* idx;            // [m][k]
+    int32_t* score;          // [m][k]
+};
+
+hipError_t launch_clear(uint32_t* p, int64_t count, hipStream_t s);
+hipError_t launch_scan_hist(const HistArgs& a, hipStream_t s);
+hipError_t launch_hist_collect(const CollectArgs& a, hipStream_t s);
 
 }  // namespace xbq

@@ -145,6 +145,7 @@ def test_workspace_bytes(L):
     assert a == b and 0 < a < (1 << 30)             # independent of n once n is large
     assert f(1_000_000, 1_000_000, 128, 4, 100) < (1 << 30)      # bounded in m (internal batches)
     assert f(1_000_000, 1000, 960, 4, 10) > f(1_000_000, 1000, 128, 4, 10)   # repacked queries
+    assert f(1_000_000, 4, 128, 4, 10) >= 4 * 1_000_000 * 4                     # stored distances, few queries
 
 
 def test_options(L):
@@ -154,6 +155,10 @@ def test_options(L):
     assert L.xbq_set_option(None, 1.0) == xbq.EINVAL
     assert L.xbq_set_option(b"first", 1024) == xbq.OK
     assert L.xbq_set_option(b"qsplit", 0) == xbq.OK
+    assert L.xbq_set_option(b"selector", 3) == xbq.EINVAL
+    for sel in (1, 2, 0):
+        assert L.xbq_set_option(b"selector", sel) == xbq.OK
+    assert L.xbq_set_option(b"hist_max_queries", 16) == xbq.OK
 
 
 def test_missing_library_is_loud(monkeypatch):

@@ -66,6 +66,42 @@ def _run(name, bits, ks, oracle_queries):
         gu.assert_same((idx[sub], score[sub]), (ridx, rscore), f"{name} bits={bits} k={k}")
 
 
+def _run_few_queries(name, bits, k, m):
+    """The few-query (histogram selection) path at full database size, every query checked."""
+    import torch
+    w = wl.WORKLOADS[name]
+    scale = wl.workload_scale(w)
+    Xq = wl.queries(w, 0, m)
+    W = (w.d + 31) // 32
+    db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
+    planes = np.empty((w.n, bits, (w.d + 63) // 64), dtype=np.uint64)
+    slab = 1 << 20
+    for lo in range(0, w.n, slab):
+        hi = min(w.n, lo + slab)
+        X = wl.database(w, lo, hi)
+        xbq.xbq_encode(torch.from_numpy(X).cuda(), bits, scale, xbq.BUNDLE64, out=db[lo // 64 * 64 * bits * W:])
+        planes[lo:hi] = oc.encode(X, bits, scale)
+    q = xbq.xbq_encode(torch.from_numpy(Xq).cuda(), bits, scale, xbq.ROWS)
+    idx, score = xbq.xbq_search(db, w.n, q, m, w.d, bits, k)
+    torch.cuda.synchronize()
+    _say(f"{name}: {m} queries searched on the GPU")
+    gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), oc.search(planes, oc.encode(Xq, bits, scale), w.d, k),
+                   f"{name} few queries")
+
+
+def test_c2_full_size_single_query_mode():
+    _run_few_queries("C2", 4, 100, 1)
+    _run_few_queries("C2", 4, 100, 8)
+
+
+def test_c5_full_size_few_queries():
+    _run_few_queries("C5", 4, 100, 5)
+
+
+def test_c3_full_size_few_queries_long_codes():
+    _run_few_queries("C3", 3, 10, 3)
+
+
 def test_c2_full_size():
     _run("C2", 4, (100,), 1000)
 

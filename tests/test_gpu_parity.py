@@ -29,6 +29,14 @@ def _gpu():
     yield
 
 
+@pytest.fixture(params=[1, 2], ids=["threshold", "histogram"])
+def selector(request):
+    """Run a test once with each top-K selector forced."""
+    xbq.xbq_set_option("selector", request.param)
+    yield request.param
+    xbq.xbq_set_option("selector", 0)
+
+
 def _rand(n, d, seed, lo=-0.5, hi=0.5):
     return np.random.default_rng(seed).uniform(lo, hi, size=(n, d)).astype(np.float32)
 
@@ -112,7 +120,7 @@ SMALL = [
 
 
 @pytest.mark.parametrize("n,d,m,bits,k", SMALL)
-def test_search_matches_oracle_small(n, d, m, bits, k):
+def test_search_matches_oracle_small(n, d, m, bits, k, selector):
     _say(f"search n={n} d={d} m={m} bits={bits} k={k}")
     Xdb = _rand(n, d, seed=n + d)
     Xq = _rand(m, d, seed=n + d + 1)
@@ -121,7 +129,7 @@ def test_search_matches_oracle_small(n, d, m, bits, k):
                    f"n={n} d={d} bits={bits} k={k}")
 
 
-def test_config_c1_full():
+def test_config_c1_full(selector):
     w = wl.WORKLOADS["C1"]
     _say("C1 full")
     Xdb, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
@@ -134,7 +142,7 @@ def test_config_c1_full():
 
 @pytest.mark.parametrize("name,n,m", [("C2", 150_000, 200), ("C3", 40_000, 64), ("C4", 200_000, 150),
                                       ("C5", 300_000, 150)])
-def test_configs_scaled_down(name, n, m):
+def test_configs_scaled_down(name, n, m, selector):
     w = wl.scaled_down(wl.WORKLOADS[name], n=n, m=m)
     Xdb, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
     for bits in w.bits:
@@ -159,7 +167,7 @@ ASYM = [
 
 
 @pytest.mark.parametrize("n,d,m,qb,db,k", ASYM)
-def test_search_asymmetric_bits(n, d, m, qb, db, k):
+def test_search_asymmetric_bits(n, d, m, qb, db, k, selector):
     # 4-bit queries against 3-bit documents is the setting of Sections 3.6 and 5
     _say(f"asym n={n} d={d} m={m} q_bits={qb} db_bits={db} k={k}")
     Xdb = _rand(n, d, seed=n + d + qb)
@@ -229,7 +237,7 @@ def test_refine_on_clustered_rows_and_sorted_rows():
     gu.assert_refined_matches(got, Xs, Xq[:4], D, 10, 50, xbq.REFINE_MAX_CANDIDATES)
 
 
-def test_all_scores_tied():
+def test_all_scores_tied(selector):
     # non-negative data at scale 1: every coordinate falls in the same cell, all scores equal
     w = wl.scaled_down(wl.WORKLOADS["C3"], n=30_000, m=16)
     Xdb, Xq = wl.database(w), wl.queries(w)
@@ -238,7 +246,7 @@ def test_all_scores_tied():
     assert (idx == np.arange(10)[None, :]).all()
 
 
-def test_duplicated_rows_and_few_distinct_scores():
+def test_duplicated_rows_and_few_distinct_scores(selector):
     base = _rand(500, 24, seed=5)
     Xdb = np.tile(base, (40, 1))                        # every row occurs 40 times
     Xq = _rand(12, 24, seed=6)
@@ -246,7 +254,7 @@ def test_duplicated_rows_and_few_distinct_scores():
         gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 1.5), gu.oracle_search(Xdb, Xq, bits, k, 1.5), "dups")
 
 
-def test_rows_sorted_by_similarity_forces_exact_rescan():
+def test_rows_sorted_by_similarity_forces_exact_rescan(selector):
     # later rows are ever closer to the queries: every group floods the candidate lists,
     # which must overflow and take the exact rescan path
     rng = np.random.default_rng(17)
@@ -263,6 +271,27 @@ def test_rows_sorted_by_similarity_forces_exact_rescan():
     for bits, k in ((4, 10), (3, 100), (4, 1024)):
         _say(f"sorted rows bits={bits} k={k}")
         gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 3.0), gu.oracle_search(Xdb, Xq, bits, k, 3.0), "sorted")
+
+
+def test_massive_ties_take_the_streaming_path_of_the_histogram_selector():
+    # one bit, low dimension: a handful of distinct distances over 300k rows, so the boundary
+    # bin holds far more rows than the sort buffer
+    Xdb = _rand(300_000, 8, seed=41)
+    Xq = _rand(5, 8, seed=42)
+    xbq.xbq_set_option("selector", 2)
+    try:
+        for bits, k in ((1, 100), (2, 1000)):
+            gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 1.5), gu.oracle_search(Xdb, Xq, bits, k, 1.5), "ties")
+    finally:
+        xbq.xbq_set_option("selector", 0)
+
+
+def test_automatic_selector_switches_with_query_count():
+    Xdb = _rand(40_000, 128, seed=43)
+    want_few = gu.oracle_search(Xdb, _rand(9, 128, seed=44), 4, 10, 2.0)
+    gu.assert_same(gu.gpu_search(Xdb, _rand(9, 128, seed=44), 4, 10, 2.0), want_few, "auto, 9 queries")
+    Xq = _rand(700, 128, seed=45)
+    gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 10, 2.0), gu.oracle_search(Xdb, Xq, 4, 10, 2.0), "auto, 700 queries")
 
 
 def test_many_queries_cross_the_internal_batch():
@@ -288,6 +317,7 @@ def test_options_do_not_change_results():
     Xdb = _rand(30_000, 128, seed=3)
     Xq = _rand(64, 128, seed=4)
     want = gu.oracle_search(Xdb, Xq, 4, 100, 2.0)
+    xbq.xbq_set_option("selector", 1)
     try:
         for growth, first, qsplit in ((1.5, 1024, 0), (4.0, 512, 16), (8.0, 4096, 1000), (2.0, 64, 7)):
             xbq.xbq_set_option("growth", growth)
@@ -298,11 +328,12 @@ def test_options_do_not_change_results():
         xbq.xbq_set_option("growth", 4.0)
         xbq.xbq_set_option("first", 1024)
         xbq.xbq_set_option("qsplit", 0)
+        xbq.xbq_set_option("selector", 0)
 
 
 def test_trace_reports_scan_time():
     Xdb = _rand(50_000, 128, seed=8)
-    Xq = _rand(256, 128, seed=9)
+    Xq = _rand(300, 128, seed=9)
     xbq.xbq_trace_enable(True)
     try:
         gu.gpu_search(Xdb, Xq, 4, 10, 2.0)
@@ -310,4 +341,4 @@ def test_trace_reports_scan_time():
     finally:
         xbq.xbq_trace_enable(False)
     assert launches >= 2 and ms > 0
-    assert pairs == 50_000 * 256
+    assert pairs == 50_000 * 300
