@@ -218,6 +218,37 @@ def main():
                    "GBps": w.n * cm.encode_bytes_per_row(w.d, db_bits) / 1e9 / (enc_ms * 1e-3),
                    "hbm_frac": w.n * cm.encode_bytes_per_row(w.d, db_bits) / (enc_ms * 1e-3) / cm.HBM_BYTES_PER_S},
     }
+    # the regime the paper measured (Section 5: single-query requests): one query against the
+    # resident codes, bound by the HBM stream of the database codes
+    if args.refine < 0:
+        for mq in (1, 8):
+            if mq > w.m:
+                continue
+            idx1 = torch.empty((mq, k), dtype=torch.int32, device="cuda")
+            sc1 = torch.empty((mq, k), dtype=torch.int32, device="cuda")
+            ws1 = torch.empty(xbq.xbq_search_workspace_bytes(w.n, mq, w.d, bits, k), dtype=torch.uint8, device="cuda")
+            reps = 30
+            for _ in range(3):
+                xbq.xbq_search_asym(db, w.n, db_bits, q, mq, bits, w.d, k, workspace=ws1, idx=idx1, score=sc1)
+            torch.cuda.synchronize()
+            xbq.xbq_trace_enable(True)
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for _ in range(reps):
+                xbq.xbq_search_asym(db, w.n, db_bits, q, mq, bits, w.d, k, workspace=ws1, idx=idx1, score=sc1)
+            a1.record()
+            torch.cuda.synchronize()
+            sms, sl, _ = xbq.xbq_trace_read()
+            xbq.xbq_trace_enable(False)
+            lat_ms = a0.elapsed_time(a1) / reps
+            stream_bytes = w.n * (cm.code_bytes_per_row(w.d, db_bits) + 4 * mq)     # codes in, distances out
+            out.setdefault("few_queries", []).append({
+                "queries": mq, "search_ms": lat_ms, "queries_per_s": mq / (lat_ms * 1e-3),
+                "scan_kernel_ms": sms / reps, "scan_launches": sl / reps,
+                "scan_GBps": stream_bytes / 1e9 / (sms / reps * 1e-3),
+                "scan_hbm_frac": stream_bytes / (sms / reps * 1e-3) / cm.HBM_BYTES_PER_S,
+                "note": "codes resident, encode not included; scan bytes = database codes + stored distances"})
+            del idx1, sc1, ws1
     if not args.no_recall:
         r, nq = recall_at_k(Xdb, Xq, idx, k)
         out["recall_at_k"] = {"value": r, "queries": nq, "against": "exact fp32 cosine (torch matmul + topk)"}
