@@ -150,6 +150,10 @@ int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
  *   "selector"          0 = automatic, 1 = threshold filter with growing row groups (many
  *                       queries), 2 = histogram selection (few queries; Section 4.1)
  *   "hist_max_queries"  automatic choice: histogram selection up to this many queries
+ *   "kernel"            0 = XOR + population count (the method of the paper, default);
+ *                       1 = cross-check scan that gets the same integer distances from packed
+ *                       4-bit dot products (d <= 256, threshold selector only; needs
+ *                       n * ceil(d/32) * 16 more workspace bytes)
  * Returns XBQ_EINVAL for an unknown name or a value out of range.
  */
 int xbq_set_option(const char* name, double value);

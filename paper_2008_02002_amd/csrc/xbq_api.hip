@@ -29,6 +29,7 @@ struct Options {
     int qsplit = 0;
     int selector = 0;                // 0 automatic, 1 threshold filter, 2 histogram
     int hist_max_queries = 16;       // automatic choice: histogram selection up to this many queries
+    int kernel = 0;                  // 0 XOR + population count, 1 packed 4-bit dot products (cross-check)
 } g_opt;
 
 struct Trace {
@@ -66,6 +67,8 @@ struct Plan {
     int keep_max = 0;                    // keys kept per query (k, or the candidate bound when refining)
     size_t off_len = 0;
     size_t off_thr = 0, off_cnt = 0, off_topk = 0, off_cand = 0, off_dense = 0, off_q = 0;
+    bool dot = false;                    // cross-check scan: nibble copies of database and queries
+    size_t off_dbn = 0, off_qn = 0, off_qsum = 0;
     // histogram selection (aliases the regions above: one call runs one of the two paths)
     bool hist = false;
     int hist_wc = 0, hist_nchunks = 0, hist_shift = 0;
@@ -106,12 +109,19 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false
     p.off_dense = off; off = align_up(off + b * static_cast<size_t>(p.first) * sizeof(uint32_t), 256);
     p.off_q = off;
     if (p.wc) off = align_up(off + b * p.nchunks * bits * p.wc * sizeof(uint32_t), 256);
+    if (g_opt.kernel == 1 && p.wc == 0) {
+        p.dot = true;
+        const size_t wd = 4u * p.W;
+        p.off_qn = off;   off = align_up(off + b * wd * sizeof(uint32_t), 256);
+        p.off_qsum = off; off = align_up(off + b * sizeof(int32_t), 256);
+        p.off_dbn = off;  off = align_up(off + static_cast<size_t>((n + kLanes - 1) / kLanes) * kLanes * wd * sizeof(uint32_t), 256);
+    }
     p.total = off;
 
     // histogram selection: eligible for plain top-K when the stored distances stay moderate
     const bool want = g_opt.selector == 2 || (g_opt.selector == 0 && m <= g_opt.hist_max_queries);
     const int hq = static_cast<int>(m < kHistMaxQueries ? m : kHistMaxQueries);
-    if (!refine && want && m <= p.batch && n * int64_t(4) * hq <= kHistMaxDistBytes) {
+    if (!refine && !p.dot && want && m <= p.batch && n * int64_t(4) * hq <= kHistMaxDistBytes) {
         p.hist = true;
         p.hist_wc = p.wc ? p.wc : p.W;
         p.hist_nchunks = p.wc ? p.nchunks : 1;
@@ -165,6 +175,21 @@ hipError_t traced_scan(const ScanArgs& a, bool dense, hipStream_t s)
     if (rec) {
         e = hipEventRecord(g_trace.ev[g_trace.used + 1], s);
         if (e != hipSuccess) return e;
+        g_trace.used += 2;
+        g_trace.pairs += static_cast<double>(a.row_end - a.row_begin) * a.m;
+    }
+    return hipSuccess;
+}
+
+hipError_t traced_scan_dot(const DotArgs& a, bool dense, hipStream_t s)
+{
+    const bool rec = g_trace.on && g_trace.used + 2 <= static_cast<int>(g_trace.ev.size());
+    hipError_t e;
+    if (rec && (e = hipEventRecord(g_trace.ev[g_trace.used], s)) != hipSuccess) return e;
+    e = launch_scan_dot(a, dense, s);
+    if (e != hipSuccess) return e;
+    if (rec) {
+        if ((e = hipEventRecord(g_trace.ev[g_trace.used + 1], s)) != hipSuccess) return e;
         g_trace.used += 2;
         g_trace.pairs += static_cast<double>(a.row_end - a.row_begin) * a.m;
     }
@@ -262,6 +287,10 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
     const int tile = p.wc ? kTileQ : 1;
 
     if (p.hist && !refine) return run_hist_search(job, p, ws, s);
+    if (p.dot) {
+        const hipError_t e = launch_nibbles_db(db_codes, n, d, db_bits, reinterpret_cast<uint32_t*>(ws + p.off_dbn), s);
+        if (e != hipSuccess) return fail_hip(e);
+    }
 
     for (int64_t qb = 0; qb < m; qb += p.batch) {
         const int mb = static_cast<int>(m - qb < p.batch ? m - qb : p.batch);
@@ -291,6 +320,27 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             sa.q = q_rows;
         }
 
+        DotArgs da{};
+        if (p.dot) {
+            uint32_t* qn = reinterpret_cast<uint32_t*>(ws + p.off_qn);
+            int32_t* qsum = reinterpret_cast<int32_t*>(ws + p.off_qsum);
+            const hipError_t e = launch_nibbles_q(q_rows, mb, d, q_bits, qn, qsum, s);
+            if (e != hipSuccess) return fail_hip(e);
+            da.dbn = reinterpret_cast<const uint32_t*>(ws + p.off_dbn);
+            da.n = n;
+            da.qn = qn;
+            da.qsum = qsum;
+            da.m = mb;
+            da.WD = 4 * p.W;
+            da.half_full_minus_d = (d * ((1 << q_bits) - 1) * ((1 << db_bits) - 1) - d) / 2;
+            da.thr = sa.thr;
+            da.cnt = sa.cnt;
+            da.cand = sa.cand;
+            da.cap = sa.cap;
+            da.dense = sa.dense;
+            da.dense_stride = sa.dense_stride;
+        }
+
         SelectArgs sel{};
         sel.m = mb;
         sel.k = k;
@@ -318,7 +368,8 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             const int64_t bundles = (seen + kLanes - 1) / kLanes;
             sa.rows_per_lane = 1;
             sa.qsplit = choose_qsplit(bundles, 1, mb, tile);
-            hipError_t e = traced_scan(sa, true, s);
+            da.row_begin = sa.row_begin; da.row_end = sa.row_end; da.rows_per_lane = 1; da.qsplit = sa.qsplit;
+            hipError_t e = p.dot ? traced_scan_dot(da, true, s) : traced_scan(sa, true, s);
             if (e != hipSuccess) return fail_hip(e);
             sel.row_begin = 0;
             sel.rows = p.first;
@@ -342,7 +393,8 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             const int64_t bundles = (end - seen + kLanes - 1) / kLanes;
             sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
             sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, tile);
-            hipError_t e = traced_scan(sa, false, s);
+            da.row_begin = seen; da.row_end = end; da.rows_per_lane = sa.rows_per_lane; da.qsplit = sa.qsplit;
+            hipError_t e = p.dot ? traced_scan_dot(da, false, s) : traced_scan(sa, false, s);
             if (e != hipSuccess) return fail_hip(e);
             sel.row_begin = seen;
             sel.final_group = end >= n;
@@ -534,6 +586,11 @@ int xbq_set_option(const char* name, double value)
     if (!std::strcmp(name, "first")) {
         if (!(value >= 64 && value <= kSortCap)) return XBQ_EINVAL;
         g_opt.first = static_cast<int>(value);
+        return XBQ_OK;
+    }
+    if (!std::strcmp(name, "kernel")) {
+        if (!(value == 0 || value == 1)) return XBQ_EINVAL;
+        g_opt.kernel = static_cast<int>(value);
         return XBQ_OK;
     }
     if (!std::strcmp(name, "selector")) {

@@ -116,6 +116,23 @@ struct RefineArgs {
 };
 hipError_t launch_refine(const RefineArgs& a, hipStream_t s);
 
+// Cross-check scan with packed 4-bit dot products: see xbq_dot.hip.
+struct DotArgs {
+    const uint32_t* dbn;     // nibbles of the database rows, [bundles][WD][64]
+    int64_t n, row_begin, row_end;
+    const uint32_t* qn;      // nibbles of the queries, [m][WD]
+    const int32_t* qsum;     // [m] sum of the query's nibble values
+    int m, qsplit, qranges, row_blocks;
+    int WD;                  // dwords of nibbles per row = 4 * W
+    int rows_per_lane;
+    int half_full_minus_d;   // (d (2^Bq - 1)(2^Bd - 1) - d) / 2
+    const uint32_t* thr; uint32_t* cnt; uint64_t* cand; int cap;
+    uint32_t* dense; int dense_stride;
+};
+hipError_t launch_scan_dot(const DotArgs& a, bool dense, hipStream_t s);
+hipError_t launch_nibbles_db(const uint32_t* codes, int64_t n, int d, int bits, uint32_t* out, hipStream_t s);
+hipError_t launch_nibbles_q(const uint32_t* codes, int m, int d, int bits, uint32_t* out, int32_t* vsum, hipStream_t s);
+
 // Histogram selection (few queries): see xbq_hist.hip.
 struct HistArgs {
     const uint32_t* db;      // XBQ_BUNDLE64 codes

@@ -237,6 +237,35 @@ def test_refine_on_clustered_rows_and_sorted_rows():
     gu.assert_refined_matches(got, Xs, Xq[:4], D, 10, 50, xbq.REFINE_MAX_CANDIDATES)
 
 
+DOT = [
+    # n, d, m, q_bits, db_bits, k   (the cross-check scan serves d <= 256)
+    (5000, 128, 300, 4, 4, 10),
+    (20000, 128, 300, 4, 3, 100),
+    (9000, 200, 280, 3, 3, 50),
+    (9000, 96, 300, 4, 4, 100),
+    (7000, 250, 290, 3, 2, 10),
+    (6000, 33, 300, 2, 2, 5),
+    (6000, 256, 270, 1, 1, 20),
+    (4097, 8, 260, 2, 1, 64),
+]
+
+
+@pytest.mark.parametrize("n,d,m,qb,db,k", DOT)
+def test_dot_product_cross_check_scan_gives_the_same_result(n, d, m, qb, db, k):
+    _say(f"dot cross-check n={n} d={d} m={m} {qb}x{db} k={k}")
+    Xdb = _rand(n, d, seed=n + d + 7)
+    Xq = _rand(m, d, seed=n + d + 8)
+    want = gu.oracle_search_asym(Xdb, Xq, db, qb, k, 2.1)
+    xbq.xbq_set_option("kernel", 1)
+    xbq.xbq_set_option("selector", 1)
+    try:
+        gu.assert_same(gu.gpu_search_asym(Xdb, Xq, db, qb, k, 2.1), want, "dot cross-check")
+    finally:
+        xbq.xbq_set_option("kernel", 0)
+        xbq.xbq_set_option("selector", 0)
+    gu.assert_same(gu.gpu_search_asym(Xdb, Xq, db, qb, k, 2.1), want, "xor path")
+
+
 def test_all_scores_tied(selector):
     # non-negative data at scale 1: every coordinate falls in the same cell, all scores equal
     w = wl.scaled_down(wl.WORKLOADS["C3"], n=30_000, m=16)
