@@ -74,9 +74,11 @@ size_t xbq_code_bytes(int64_t n, int d, int bits, int layout);
 int xbq_encode(const float* X, int64_t n, int d, int bits, float scale, int layout,
                uint32_t* codes, void* stream);
 
-/* Bytes of scratch xbq_search needs for these sizes; 0 if arguments are invalid.
- * Depends on n only through min(n, small constant) and on m only up to an internal
- * query batch, so it stays below ~1 GiB. */
+/* Bytes of scratch xbq_search needs for these sizes; 0 if arguments are invalid.  Depends on
+ * the options in force (xbq_set_option).  With more than a handful of queries it depends on
+ * n only through min(n, small constant) and on m only up to an internal query batch (below
+ * ~0.3 GiB); with few queries (histogram selection) it holds 4 bytes per (query, row) for up
+ * to 8 queries, at most 1 GiB; the cross-check kernel adds a copy of the database codes. */
 size_t xbq_search_workspace_bytes(int64_t n, int64_t m, int d, int bits, int k);
 
 /*

@@ -1,0 +1,116 @@
+// Device functions shared by the kernels of libxbq.so (included by the .hip files only).
+#pragma once
+
+#include "xbq_internal.h"
+
+namespace xbq {
+
+// Uniform (wavefront-invariant) data is read through the constant address space so that the
+// compiler uses scalar loads and the values arrive in SGPRs.
+typedef const uint32_t __attribute__((address_space(4))) * uniform_ptr;
+typedef const int32_t __attribute__((address_space(4))) * uniform_iptr;
+
+constexpr uint64_t kPadKey = ~0ull;                      // sorts after every real key
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
+
+__device__ __forceinline__ int next_pow2(int v)
+{
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+// acc + POPCNT(v) in one instruction.  Written as an instruction so the compiler keeps one
+// running sum per weight class; left to itself it re-associates the sums into trees of
+// three-input adds, which costs a fifth more vector instructions.
+__device__ __forceinline__ uint32_t popcount_add(uint32_t v, uint32_t acc)
+{
+    uint32_t r;
+    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(v), "v"(acc));
+    return r;
+}
+
+// Eq. 6 of Section 3.3 for one row held in x (BD planes) against the uniform query words y
+// (BQ planes), WC words per plane: sum_i sum_j POPCNT(x_i ^ y_j) << (i + j), with one running
+// sum per weight class i + j and a Horner combination at the end.
+template <int BQ, int BD, int WC>
+__device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[BD][WC], const uint32_t (&y)[BQ][WC])
+{
+    constexpr int C = BQ + BD - 1;
+    uint32_t acc[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        bool first = true;
+#pragma unroll
+        for (int i = 0; i < BD; ++i) {
+            const int j = c - i;
+            if (j < 0 || j >= BQ) continue;
+#pragma unroll
+            for (int w = 0; w < WC; ++w) {
+                const uint32_t v = x[i][w] ^ y[j][w];
+                acc[c] = first ? static_cast<uint32_t>(__builtin_popcount(v)) : popcount_add(v, acc[c]);
+                first = false;
+            }
+        }
+    }
+    uint32_t D = acc[C - 1];
+#pragma unroll
+    for (int c = C - 2; c >= 0; --c) D = (D << 1) + acc[c];
+    return D;
+}
+
+// Append the keys of the lanes with `pass` set to list[0 .. cap): one atomic per wavefront on
+// *counter reserves the slots, v_mbcnt ranks the lanes.  Keys past cap are dropped; the
+// counter still counts them, which is how an overflow is seen later.
+__device__ __forceinline__ void append_keys(bool pass, uint32_t D, uint32_t row, uint32_t* counter, uint64_t* list,
+                                            uint32_t cap)
+{
+    const uint64_t mask = __ballot(pass);
+    if (mask == 0) return;
+    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
+    uint32_t base = 0;
+    if (lane_id() == leader) base = atomicAdd(counter, static_cast<uint32_t>(__popcll(mask)));
+    base = __shfl(base, leader);
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+    const uint32_t pos = base + rank;
+    if (pass && pos < cap) list[pos] = make_key(D, row);
+}
+
+// Workgroup -> (row block, query range) of the scan kernels.  The grid is one-dimensional.
+// Hardware hands consecutive workgroup ids to the 8 XCDs in turn, each XCD with its own L2,
+// so the id is split as (id % 8, id / 8): XCD c works through row blocks c, c + 8, c + 16, ...
+// and for each of them through all query ranges back to back.  A row block is then fetched
+// from HBM by one XCD only and stays in that L2 while its query ranges run; the (small) query
+// array is what every XCD shares.  If the hardware assigned ids differently the result would
+// be the same, only the locality would be lost.
+constexpr int kXcds = 8;
+__device__ __forceinline__ bool decode_tile(int row_blocks, int qranges, int& row_block, int& qrange)
+{
+    const unsigned id = blockIdx.x;
+    const unsigned xcd = id % kXcds, j = id / kXcds;
+    row_block = static_cast<int>((j / qranges) * kXcds + xcd);
+    qrange = static_cast<int>(j % qranges);
+    return row_block < row_blocks;
+}
+
+// Ascending bitonic sort of P (power of two) 64-bit keys in LDS by the whole workgroup.
+// The caller has synchronised after filling `keys`; the routine ends with a barrier.
+__device__ inline void bitonic_sort_lds(uint64_t* keys, int P)
+{
+    for (int k = 2; k <= P; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (P >> 1); t += blockDim.x) {
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int l = i | j;
+                const bool up = (i & k) == 0;
+                const uint64_t a = keys[i], b = keys[l];
+                if ((a > b) == up) { keys[i] = b; keys[l] = a; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+}  // namespace xbq

@@ -11,12 +11,9 @@
 // method of the paper, which replaces multiplies by XOR.  It produces the same D for every
 // pair, so everything downstream (threshold filter, candidate lists, selection) is shared.
 
-#include "xbq_internal.h"
+#include "xbq_device.h"
 
 namespace xbq {
-
-typedef const uint32_t __attribute__((address_space(4))) * uniform_ptr;
-typedef const int32_t __attribute__((address_space(4))) * uniform_iptr;
 
 // 8 bits -> the least significant bit of each of 8 nibbles.
 __device__ __forceinline__ uint32_t spread8(uint32_t byte)
@@ -91,33 +88,14 @@ __global__ void nibbles_from_rows(const uint32_t* __restrict__ codes, int m, int
     vsum[q] = sum;
 }
 
-__device__ __forceinline__ void emit_dot(bool pass, uint32_t D, uint32_t row, int q, uint32_t* cnt, uint64_t* cand,
-                                         int cap)
-{
-    const uint64_t mask = __ballot(pass);
-    if (mask == 0) return;
-    const int lane = threadIdx.x & 63;
-    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
-    uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(&cnt[q], static_cast<uint32_t>(__popcll(mask)));
-    base = __shfl(base, leader);
-    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
-                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
-    const uint32_t pos = base + rank;
-    if (pass && pos < static_cast<uint32_t>(cap)) cand[static_cast<size_t>(q) * cap + pos] = make_key(D, row);
-}
-
 // Same tiling and workgroup order as scan_resident; WD = 4 * W dwords of nibbles per row.
 template <int WD, int R, bool DENSE>
 __global__ __launch_bounds__(kBlock) void scan_dot8(const DotArgs a)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const unsigned id = blockIdx.x;
-    const unsigned xcd = id % 8, j = id / 8;
-    const int row_block = static_cast<int>((j / a.qranges) * 8 + xcd);
-    const int qrange = static_cast<int>(j % a.qranges);
-    if (row_block >= a.row_blocks) return;
+    int row_block, qrange;
+    if (!decode_tile(a.row_blocks, a.qranges, row_block, qrange)) return;
     const int64_t bundle0 = a.row_begin / kLanes + (static_cast<int64_t>(row_block) * 4 + wave) * R;
     if (bundle0 * kLanes >= a.row_end) return;
     const int64_t last_bundle = (a.n - 1) / kLanes;
@@ -171,7 +149,8 @@ __global__ __launch_bounds__(kBlock) void scan_dot8(const DotArgs a)
             if (__builtin_expect(__ballot(any) != 0, 0)) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    emit_dot(D[r] < t && row[r] < a.row_end, D[r], row[r], q, a.cnt, a.cand, a.cap);
+                    append_keys(D[r] < t && row[r] < a.row_end, D[r], row[r], &a.cnt[q], a.cand + static_cast<size_t>(q) * a.cap,
+                                static_cast<uint32_t>(a.cap));
             }
         }
     }

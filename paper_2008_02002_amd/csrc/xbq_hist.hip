@@ -19,52 +19,15 @@
 // stage; here bins are 2^shift wide (at most 1024 per query) and the final sort makes the
 // result the exact top-K with ties to the lower row.
 
-#include "xbq_internal.h"
+#include "xbq_device.h"
 
 namespace xbq {
-
-typedef const uint32_t __attribute__((address_space(4))) * uniform_ptr;
-
-constexpr uint64_t kPadKeyH = ~0ull;
 
 __global__ void clear_u32(uint32_t* p, int64_t count)
 {
     for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < count;
          i += static_cast<int64_t>(gridDim.x) * blockDim.x)
         p[i] = 0;
-}
-
-__device__ __forceinline__ uint32_t popcount_add_h(uint32_t v, uint32_t acc)
-{
-    uint32_t r;
-    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(v), "v"(acc));
-    return r;
-}
-
-template <int BQ, int BD, int WC>
-__device__ __forceinline__ uint32_t xor_popcount_h(const uint32_t (&x)[BD][WC], const uint32_t (&y)[BQ][WC])
-{
-    constexpr int C = BQ + BD - 1;
-    uint32_t acc[C];
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-        bool first = true;
-#pragma unroll
-        for (int i = 0; i < BD; ++i) {
-            const int j = c - i;
-            if (j < 0 || j >= BQ) continue;
-#pragma unroll
-            for (int w = 0; w < WC; ++w) {
-                const uint32_t v = x[i][w] ^ y[j][w];
-                acc[c] = first ? static_cast<uint32_t>(__builtin_popcount(v)) : popcount_add_h(v, acc[c]);
-                first = false;
-            }
-        }
-    }
-    uint32_t D = acc[C - 1];
-#pragma unroll
-    for (int c = C - 2; c >= 0; --c) D = (D << 1) + acc[c];
-    return D;
 }
 
 // One wavefront per bundle of 64 rows (grid-stride); queries come from the chunk-major layout
@@ -109,7 +72,7 @@ __global__ __launch_bounds__(kHistBlock) void scan_hist(const HistArgs a)
                     for (int b = 0; b < BQ; ++b)
 #pragma unroll
                         for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
-                    acc[t] += xor_popcount_h<BQ, BD, WC>(x, y);
+                    acc[t] += xor_popcount<BQ, BD, WC>(x, y);
                 }
             }
         }
@@ -129,30 +92,6 @@ __global__ __launch_bounds__(kHistBlock) void scan_hist(const HistArgs a)
         const uint32_t v = lh[t];
         if (v) atomicAdd(&a.hist[t], v);
     }
-}
-
-// Ascending bitonic sort of P keys in LDS (same routine as in the selection kernels).
-__device__ void bitonic_sort_h(uint64_t* keys, int P)
-{
-    for (int k = 2; k <= P; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = threadIdx.x; t < (P >> 1); t += blockDim.x) {
-                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                const int l = i | j;
-                const bool up = (i & k) == 0;
-                const uint64_t x = keys[i], y = keys[l];
-                if ((x > y) == up) { keys[i] = y; keys[l] = x; }
-            }
-            __syncthreads();
-        }
-    }
-}
-
-__device__ __forceinline__ int next_pow2_h(int v)
-{
-    int p = 1;
-    while (p < v) p <<= 1;
-    return p;
 }
 
 __device__ void write_result_h(const CollectArgs& a, int q, const uint64_t* keys)
@@ -182,20 +121,20 @@ __device__ void stream_select(const CollectArgs& a, int q, uint64_t* keys, int* 
         __syncthreads();
         const int have = *fill;
         if (have > kSortCap - static_cast<int>(blockDim.x)) {
-            const int P = next_pow2_h(have);
-            for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKeyH;
+            const int P = next_pow2(have);
+            for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
             __syncthreads();
-            bitonic_sort_h(keys, P);
+            bitonic_sort_lds(keys, P);
             thr = static_cast<uint32_t>(keys[a.k - 1] >> 32);   // have >= K here: K <= 1024 < have
             if (threadIdx.x == 0) *fill = a.k;
         }
         __syncthreads();
     }
     const int have = *fill;
-    const int P = next_pow2_h(have);
-    for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKeyH;
+    const int P = next_pow2(have);
+    for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
     __syncthreads();
-    bitonic_sort_h(keys, P);
+    bitonic_sort_lds(keys, P);
     write_result_h(a, q, keys);
 }
 
@@ -245,7 +184,6 @@ __global__ __launch_bounds__(kBlock) void hist_collect(const CollectArgs a)
     __shared__ int s_bin, s_total;
     const int q = blockIdx.x / a.blocks_per_query;
     const int chunk = blockIdx.x - q * a.blocks_per_query;
-    const int lane = threadIdx.x & 63;
     uint32_t bin;
     int total;
     boundary_bin(a.hist + static_cast<size_t>(q) * kHistBins, a.k, wave_sum, &s_bin, &s_total, bin, total);
@@ -275,17 +213,7 @@ __global__ __launch_bounds__(kBlock) void hist_collect(const CollectArgs a)
             for (int e = 0; e < 4; ++e) {
                 const int64_t row = r0 + (static_cast<int64_t>(u) * kBlock + threadIdx.x) * 4 + e;
                 const bool pass = row < r_end && (D[u][e] >> a.shift) <= bin;
-                const uint64_t mask = __ballot(pass);
-                if (mask) {
-                    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
-                    uint32_t base_pos = 0;
-                    if (lane == leader) base_pos = atomicAdd(&a.cand_cnt[q], static_cast<uint32_t>(__popcll(mask)));
-                    base_pos = __shfl(base_pos, leader);
-                    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
-                                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
-                    if (pass && base_pos + rank < static_cast<uint32_t>(kSortCap))
-                        list[base_pos + rank] = make_key(D[u][e], static_cast<uint32_t>(row));
-                }
+                append_keys(pass, D[u][e], static_cast<uint32_t>(row), &a.cand_cnt[q], list, static_cast<uint32_t>(kSortCap));
             }
         }
     }
@@ -306,10 +234,10 @@ __global__ __launch_bounds__(kBlock) void hist_finish(const CollectArgs a)
         return;
     }
     const uint64_t* list = a.cand + static_cast<size_t>(q) * kSortCap;
-    const int P = next_pow2_h(total);
-    for (int t = threadIdx.x; t < P; t += blockDim.x) keys[t] = t < total ? list[t] : kPadKeyH;
+    const int P = next_pow2(total);
+    for (int t = threadIdx.x; t < P; t += blockDim.x) keys[t] = t < total ? list[t] : kPadKey;
     __syncthreads();
-    bitonic_sort_h(keys, P);
+    bitonic_sort_lds(keys, P);
     write_result_h(a, q, keys);
 }
 

@@ -17,84 +17,9 @@
 //                    plane against a register tile of kTileQ queries, partial distances
 //                    accumulated per query; the database chunk comes from L2.
 
-#include "xbq_internal.h"
+#include "xbq_device.h"
 
 namespace xbq {
-
-typedef const uint32_t __attribute__((address_space(4))) * uniform_ptr;  // scalar-load path
-
-__device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
-
-// Append the keys of the lanes with `pass` set to cand[q]; one atomic per wavefront.
-__device__ __forceinline__ void emit(bool pass, uint32_t D, uint32_t row, int q, uint32_t* cnt,
-                                     uint64_t* cand, int cap)
-{
-    const uint64_t mask = __ballot(pass);
-    if (mask == 0) return;
-    const int lane = lane_id();
-    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
-    uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(&cnt[q], static_cast<uint32_t>(__popcll(mask)));
-    base = __shfl(base, leader);
-    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
-                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
-    const uint32_t pos = base + rank;
-    if (pass && pos < static_cast<uint32_t>(cap)) cand[static_cast<size_t>(q) * cap + pos] = make_key(D, row);
-}
-
-// Workgroup -> (row block, query range).  The grid is one-dimensional.  Hardware hands
-// consecutive workgroup ids to the 8 XCDs in turn, each XCD with its own L2, so the id is
-// split as (id % 8, id / 8): XCD c works through row blocks c, c + 8, c + 16, ... and for each
-// of them through all query ranges back to back.  A row block is then fetched from HBM by
-// one XCD only and stays in that L2 while its query ranges run; the (small) query array is
-// what every XCD shares.  If the hardware assigned ids differently the result would be the
-// same, only the locality would be lost.
-constexpr int kXcds = 8;
-__device__ __forceinline__ bool decode_tile(int row_blocks, int qranges, int& row_block, int& qrange)
-{
-    const unsigned id = blockIdx.x;
-    const unsigned xcd = id % kXcds, j = id / kXcds;
-    row_block = static_cast<int>((j / qranges) * kXcds + xcd);
-    qrange = static_cast<int>(j % qranges);
-    return row_block < row_blocks;
-}
-
-// acc + POPCNT(v) in one instruction.  Written as an instruction so the compiler keeps one
-// running sum per weight class; left to itself it re-associates the sums into trees of
-// three-input adds, which costs a fifth more vector instructions.
-__device__ __forceinline__ uint32_t popcount_add(uint32_t v, uint32_t acc)
-{
-    uint32_t r;
-    asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(r) : "v"(v), "v"(acc));
-    return r;
-}
-
-// Eq. 6 for one row held in x (BD planes) against the uniform query words y (BQ planes).
-template <int BQ, int BD, int WC>
-__device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[BD][WC], const uint32_t (&y)[BQ][WC])
-{
-    constexpr int C = BQ + BD - 1;                       // weight classes i + j
-    uint32_t acc[C];
-#pragma unroll
-    for (int c = 0; c < C; ++c) {
-        bool first = true;
-#pragma unroll
-        for (int i = 0; i < BD; ++i) {
-            const int j = c - i;
-            if (j < 0 || j >= BQ) continue;
-#pragma unroll
-            for (int w = 0; w < WC; ++w) {
-                const uint32_t v = x[i][w] ^ y[j][w];
-                acc[c] = first ? static_cast<uint32_t>(__builtin_popcount(v)) : popcount_add(v, acc[c]);
-                first = false;
-            }
-        }
-    }
-    uint32_t D = acc[C - 1];
-#pragma unroll
-    for (int c = C - 2; c >= 0; --c) D = (D << 1) + acc[c];
-    return D;
-}
 
 // ---------------------------------------------------------------------------------------
 // Register-resident scan.  One workgroup = 4*R bundles of rows x one query range.
@@ -151,7 +76,8 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
             if (__builtin_expect(__ballot(any) != 0, 0)) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    emit(D[r] < t && row[r] < a.row_end, D[r], row[r], q, a.cnt, a.cand, a.cap);
+                    append_keys(D[r] < t && row[r] < a.row_end, D[r], row[r], &a.cnt[q], a.cand + static_cast<size_t>(q) * a.cap,
+                                static_cast<uint32_t>(a.cap));
             }
         }
     }
@@ -212,7 +138,8 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
                     if (valid) a.dense[static_cast<size_t>(q) * a.dense_stride + (row - a.row_begin)] = acc[t];
                 } else {
                     const uint32_t thr = ((uniform_ptr)a.thr)[q];
-                    emit(acc[t] < thr && valid, acc[t], row, q, a.cnt, a.cand, a.cap);
+                    append_keys(acc[t] < thr && valid, acc[t], row, &a.cnt[q], a.cand + static_cast<size_t>(q) * a.cap,
+                                static_cast<uint32_t>(a.cap));
                 }
             }
         }

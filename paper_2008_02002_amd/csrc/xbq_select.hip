@@ -12,36 +12,9 @@
 //                   rows with a running threshold and a bounded LDS buffer (slow, always
 //                   exact, and only ever taken when the row order is adversarial)
 
-#include "xbq_internal.h"
+#include "xbq_device.h"
 
 namespace xbq {
-
-constexpr uint64_t kPadKey = ~0ull;
-
-__device__ __forceinline__ int next_pow2(int v)
-{
-    int p = 1;
-    while (p < v) p <<= 1;
-    return p;
-}
-
-// Ascending bitonic sort of P (power of two) keys in LDS by the whole workgroup.
-// The caller has already synchronised after filling `keys`.
-__device__ void bitonic_sort_lds(uint64_t* keys, int P)
-{
-    for (int k = 2; k <= P; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = threadIdx.x; t < (P >> 1); t += blockDim.x) {
-                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                const int l = i | j;
-                const bool up = (i & k) == 0;
-                const uint64_t a = keys[i], b = keys[l];
-                if ((a > b) == up) { keys[i] = b; keys[l] = a; }
-            }
-            __syncthreads();
-        }
-    }
-}
 
 __device__ __forceinline__ void write_result(const SelectArgs& a, int q, const uint64_t* keys)
 {
