@@ -264,7 +264,7 @@ int run_hist_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s
         ca.q_bits = job.q_bits;
         ca.db_bits = job.db_bits;
         ca.shift = p.hist_shift;
-        ca.rows_per_block = 16 * 16 * kBlock;         // 65536 rows per workgroup
+        ca.rows_per_block = 4 * 16 * kBlock;          // 16384 rows per workgroup: four rounds of loads
         ca.blocks_per_query = static_cast<int>((n + ca.rows_per_block - 1) / ca.rows_per_block);
         ca.cand = reinterpret_cast<uint64_t*>(ws + p.hoff_cand);
         ca.cand_cnt = zero + static_cast<size_t>(kHistMaxQueries < m ? kHistMaxQueries : m) * kHistBins;
