@@ -241,9 +241,24 @@ def main():
             sms, sl, _ = xbq.xbq_trace_read()
             xbq.xbq_trace_enable(False)
             lat_ms = a0.elapsed_time(a1) / reps
+            # the same search captured once in a HIP graph and replayed (no launch gaps from the host)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                xbq.xbq_search_asym(db, w.n, db_bits, q, mq, bits, w.d, k, workspace=ws1, idx=idx1, score=sc1)
+            graph.replay()
+            torch.cuda.synchronize()
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record()
+            for _ in range(reps):
+                graph.replay()
+            g1.record()
+            torch.cuda.synchronize()
+            graph_ms = g0.elapsed_time(g1) / reps
+            del graph
             stream_bytes = w.n * (cm.code_bytes_per_row(w.d, db_bits) + 4 * mq)     # codes in, distances out
             out.setdefault("few_queries", []).append({
                 "queries": mq, "search_ms": lat_ms, "queries_per_s": mq / (lat_ms * 1e-3),
+                "graph_replay_ms": graph_ms, "graph_queries_per_s": mq / (graph_ms * 1e-3),
                 "scan_kernel_ms": sms / reps, "scan_launches": sl / reps,
                 "scan_GBps": stream_bytes / 1e9 / (sms / reps * 1e-3),
                 "scan_hbm_frac": stream_bytes / (sms / reps * 1e-3) / cm.HBM_BYTES_PER_S,

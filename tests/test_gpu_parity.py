@@ -371,3 +371,41 @@ def test_trace_reports_scan_time():
         xbq.xbq_trace_enable(False)
     assert launches >= 2 and ms > 0
     assert pairs == 50_000 * 300
+
+
+def test_search_can_be_captured_in_a_hip_graph_and_replayed():
+    """The library allocates nothing, clears with kernels and never synchronises, so a search
+    can be captured once and replayed on new queries written into the same buffers."""
+    import torch
+    n, d, bits, k = 60_000, 128, 4, 10
+    Xdb = _rand(n, d, seed=51)
+    db = xbq.xbq_encode(gu.to_dev(Xdb), bits, 2.0, xbq.BUNDLE64)
+    planes = oc.encode(Xdb, bits, 2.0)
+    for m in (1, 300):                                   # histogram selector, threshold selector
+        xq = torch.zeros((m, d), dtype=torch.float32, device="cuda")
+        q = torch.zeros(xbq.xbq_code_bytes(m, d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
+        ws = torch.empty(xbq.xbq_search_workspace_bytes(n, m, d, bits, k), dtype=torch.uint8, device="cuda")
+        idx = torch.empty((m, k), dtype=torch.int32, device="cuda")
+        score = torch.empty((m, k), dtype=torch.int32, device="cuda")
+
+        def run():
+            xbq.xbq_encode(xq, bits, 2.0, xbq.ROWS, out=q)
+            xbq.xbq_search(db, n, q, m, d, bits, k, workspace=ws, idx=idx, score=score)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run()                                         # warm-up outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        for rep in range(4):
+            Xq = _rand(m, d, seed=60 + rep)
+            xq.copy_(torch.from_numpy(Xq))                # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            want = oc.search(planes, oc.encode(Xq, bits, 2.0), d, k)
+            gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), want, f"graph replay {rep}, m={m}")
