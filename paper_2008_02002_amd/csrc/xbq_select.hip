@@ -203,14 +203,31 @@ __global__ __launch_bounds__(kBlock) void refine_topk(const RefineArgs a)
     for (int c = threadIdx.x; c < a.d; c += blockDim.x) qv[c] = xq[c];
     __syncthreads();
     const uint64_t* list = a.topk + static_cast<size_t>(q) * a.keep_max;
-    for (int t = wave; t < have; t += 4) {
-        const uint32_t row = static_cast<uint32_t>(list[t] & 0xffffffffu);
-        const float* xr = a.X_db + static_cast<size_t>(row) * a.d;
-        float s = 0.0f;
-        for (int c = lane; c < a.d; c += 64) s = fmaf(xr[c], qv[c], s);
+    // each wavefront takes four candidates per round so that their row loads overlap
+    constexpr int U = 4;
+    for (int t0 = wave * U; t0 < have; t0 += 4 * U) {
+        uint32_t row[U];
+        float s[U];
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-        if (lane == 0) keys[t] = (static_cast<uint64_t>(descending_bits(s)) << 32) | row;
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u < have ? t0 + u : have - 1;         // the tail repeats the last candidate
+            row[u] = static_cast<uint32_t>(list[t] & 0xffffffffu);
+            s[u] = 0.0f;
+        }
+        for (int c = lane; c < a.d; c += 64) {
+            float xv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) xv[u] = a.X_db[static_cast<size_t>(row[u]) * a.d + c];
+            const float qc = qv[c];
+#pragma unroll
+            for (int u = 0; u < U; ++u) s[u] = fmaf(xv[u], qc, s[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) s[u] += __shfl_xor(s[u], off);
+            if (lane == 0 && t0 + u < have) keys[t0 + u] = (static_cast<uint64_t>(descending_bits(s[u])) << 32) | row[u];
+        }
     }
     const int P = next_pow2(have);
     for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
