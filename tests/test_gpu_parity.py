@@ -409,3 +409,29 @@ def test_search_can_be_captured_in_a_hip_graph_and_replayed():
             torch.cuda.synchronize()
             want = oc.search(planes, oc.encode(Xq, bits, 2.0), d, k)
             gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), want, f"graph replay {rep}, m={m}")
+
+
+def test_random_shapes_against_the_oracle():
+    """Seeded sweep over valid shapes: dimensions around word and chunk boundaries, row counts
+    around bundle and group boundaries, every supported pair of code widths, both selectors."""
+    rng = np.random.default_rng(2024)
+    dims = [1, 7, 31, 32, 33, 63, 64, 65, 95, 96, 127, 128, 129, 200, 255, 256, 257, 288, 511, 700, 1023, 1500]
+    rows = [1, 2, 63, 64, 65, 127, 128, 1000, 1023, 1024, 1025, 1535, 1536, 1537, 4095, 4096, 4097, 5121, 9999]
+    pairs = [(1, 1), (2, 2), (3, 3), (4, 4), (2, 1), (3, 2), (4, 3)]
+    try:
+        for trial in range(36):
+            d = int(rng.choice(dims))
+            n = int(rng.choice(rows))
+            qb, db = pairs[int(rng.integers(len(pairs)))]
+            m = int(rng.choice([1, 3, 8, 9, 17, 40, 130]))
+            k = int(min(n, rng.choice([1, 2, 10, 64, 100, 513, 1024])))
+            sel = int(rng.choice([1, 2]))
+            scale = float(rng.choice([1.0, 1.7, 3.3]))
+            _say(f"trial {trial}: n={n} d={d} m={m} {qb}x{db} k={k} selector={sel} scale={scale}")
+            Xdb = _rand(n, d, seed=1000 + trial)
+            Xq = _rand(m, d, seed=2000 + trial)
+            xbq.xbq_set_option("selector", sel)
+            gu.assert_same(gu.gpu_search_asym(Xdb, Xq, db, qb, k, scale), gu.oracle_search_asym(Xdb, Xq, db, qb, k, scale),
+                           f"trial {trial}")
+    finally:
+        xbq.xbq_set_option("selector", 0)
