@@ -154,8 +154,9 @@ int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
  *   "hist_max_queries"  automatic choice: histogram selection up to this many queries
  *   "kernel"            0 = XOR + population count (the method of the paper, default);
  *                       1 = cross-check scan that gets the same integer distances from packed
- *                       4-bit dot products (d <= 256, threshold selector only; needs
- *                       n * ceil(d/32) * 16 more workspace bytes)
+ *                       4-bit dot products, 2 = from an int8 matrix product on the matrix
+ *                       cores (both: d <= 256, threshold selector only, and a decoded copy of
+ *                       the database codes in the workspace: n*ceil(d/32)*16 resp. *32 bytes)
  * Returns XBQ_EINVAL for an unknown name or a value out of range.
  */
 int xbq_set_option(const char* name, double value);

@@ -29,7 +29,7 @@ struct Options {
     int qsplit = 0;
     int selector = 0;                // 0 automatic, 1 threshold filter, 2 histogram
     int hist_max_queries = 16;       // automatic choice: histogram selection up to this many queries
-    int kernel = 0;                  // 0 XOR + population count, 1 packed 4-bit dot products (cross-check)
+    int kernel = 0;                  // 0 XOR + population count; cross-checks: 1 packed 4-bit dots, 2 int8 MFMA
 } g_opt;
 
 struct Trace {
@@ -69,6 +69,8 @@ struct Plan {
     size_t off_thr = 0, off_cnt = 0, off_topk = 0, off_cand = 0, off_dense = 0, off_q = 0;
     bool dot = false;                    // cross-check scan: nibble copies of database and queries
     size_t off_dbn = 0, off_qn = 0, off_qsum = 0;
+    bool mfma = false;                   // cross-check scan: int8 copies of database and queries
+    size_t off_dbb = 0, off_qb = 0;
     // histogram selection (aliases the regions above: one call runs one of the two paths)
     bool hist = false;
     int hist_wc = 0, hist_nchunks = 0, hist_shift = 0;
@@ -116,12 +118,18 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false
         p.off_qsum = off; off = align_up(off + b * sizeof(int32_t), 256);
         p.off_dbn = off;  off = align_up(off + static_cast<size_t>((n + kLanes - 1) / kLanes) * kLanes * wd * sizeof(uint32_t), 256);
     }
+    if (g_opt.kernel == 2 && p.wc == 0) {
+        p.mfma = true;
+        const size_t row_bytes = 32u * p.W;
+        p.off_qb = off;  off = align_up(off + (b + 31) / 32 * 32 * row_bytes, 256);
+        p.off_dbb = off; off = align_up(off + static_cast<size_t>((n + kLanes - 1) / kLanes) * kLanes * row_bytes, 256);
+    }
     p.total = off;
 
     // histogram selection: eligible for plain top-K when the stored distances stay moderate
     const bool want = g_opt.selector == 2 || (g_opt.selector == 0 && m <= g_opt.hist_max_queries);
     const int hq = static_cast<int>(m < kHistMaxQueries ? m : kHistMaxQueries);
-    if (!refine && !p.dot && want && m <= p.batch && n * int64_t(4) * hq <= kHistMaxDistBytes) {
+    if (!refine && !p.dot && !p.mfma && want && m <= p.batch && n * int64_t(4) * hq <= kHistMaxDistBytes) {
         p.hist = true;
         p.hist_wc = p.wc ? p.wc : p.W;
         p.hist_nchunks = p.wc ? p.nchunks : 1;
@@ -187,6 +195,21 @@ hipError_t traced_scan_dot(const DotArgs& a, bool dense, hipStream_t s)
     hipError_t e;
     if (rec && (e = hipEventRecord(g_trace.ev[g_trace.used], s)) != hipSuccess) return e;
     e = launch_scan_dot(a, dense, s);
+    if (e != hipSuccess) return e;
+    if (rec) {
+        if ((e = hipEventRecord(g_trace.ev[g_trace.used + 1], s)) != hipSuccess) return e;
+        g_trace.used += 2;
+        g_trace.pairs += static_cast<double>(a.row_end - a.row_begin) * a.m;
+    }
+    return hipSuccess;
+}
+
+hipError_t traced_scan_mfma(const MfmaArgs& a, bool dense, hipStream_t s)
+{
+    const bool rec = g_trace.on && g_trace.used + 2 <= static_cast<int>(g_trace.ev.size());
+    hipError_t e;
+    if (rec && (e = hipEventRecord(g_trace.ev[g_trace.used], s)) != hipSuccess) return e;
+    e = launch_scan_mfma(a, dense, s);
     if (e != hipSuccess) return e;
     if (rec) {
         if ((e = hipEventRecord(g_trace.ev[g_trace.used + 1], s)) != hipSuccess) return e;
@@ -291,6 +314,10 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
         const hipError_t e = launch_nibbles_db(db_codes, n, d, db_bits, reinterpret_cast<uint32_t*>(ws + p.off_dbn), s);
         if (e != hipSuccess) return fail_hip(e);
     }
+    if (p.mfma) {
+        const hipError_t e = launch_bytes_db(db_codes, n, d, db_bits, reinterpret_cast<uint32_t*>(ws + p.off_dbb), s);
+        if (e != hipSuccess) return fail_hip(e);
+    }
 
     for (int64_t qb = 0; qb < m; qb += p.batch) {
         const int mb = static_cast<int>(m - qb < p.batch ? m - qb : p.batch);
@@ -341,6 +368,28 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             da.dense_stride = sa.dense_stride;
         }
 
+        MfmaArgs fa{};
+        if (p.mfma) {
+            const int mpad = (mb + 31) / 32 * 32;
+            uint32_t* qb8 = reinterpret_cast<uint32_t*>(ws + p.off_qb);
+            const hipError_t e = launch_bytes_q(q_rows, mb, mpad, d, q_bits, qb8, s);
+            if (e != hipSuccess) return fail_hip(e);
+            fa.dbb = reinterpret_cast<const uint8_t*>(ws + p.off_dbb);
+            fa.rows_padded = (n + kLanes - 1) / kLanes * kLanes;
+            fa.qb = reinterpret_cast<const uint8_t*>(qb8);
+            fa.m = mb;
+            fa.m_padded = mpad;
+            fa.W = p.W;
+            fa.full = d * ((1 << q_bits) - 1) * ((1 << db_bits) - 1);
+            fa.thr = sa.thr;
+            fa.cnt = sa.cnt;
+            fa.cand = sa.cand;
+            fa.cap = sa.cap;
+            fa.dense = sa.dense;
+            fa.dense_stride = sa.dense_stride;
+            fa.qsplit = mb < 1024 ? mpad : 1024;         // long query ranges: the row tiles are loaded once per range
+        }
+
         SelectArgs sel{};
         sel.m = mb;
         sel.k = k;
@@ -369,7 +418,8 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             sa.rows_per_lane = 1;
             sa.qsplit = choose_qsplit(bundles, 1, mb, tile);
             da.row_begin = sa.row_begin; da.row_end = sa.row_end; da.rows_per_lane = 1; da.qsplit = sa.qsplit;
-            hipError_t e = p.dot ? traced_scan_dot(da, true, s) : traced_scan(sa, true, s);
+            fa.row_begin = sa.row_begin; fa.row_end = sa.row_end;
+            hipError_t e = p.mfma ? traced_scan_mfma(fa, true, s) : p.dot ? traced_scan_dot(da, true, s) : traced_scan(sa, true, s);
             if (e != hipSuccess) return fail_hip(e);
             sel.row_begin = 0;
             sel.rows = p.first;
@@ -394,7 +444,8 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
             sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, tile);
             da.row_begin = seen; da.row_end = end; da.rows_per_lane = sa.rows_per_lane; da.qsplit = sa.qsplit;
-            hipError_t e = p.dot ? traced_scan_dot(da, false, s) : traced_scan(sa, false, s);
+            fa.row_begin = seen; fa.row_end = end;
+            hipError_t e = p.mfma ? traced_scan_mfma(fa, false, s) : p.dot ? traced_scan_dot(da, false, s) : traced_scan(sa, false, s);
             if (e != hipSuccess) return fail_hip(e);
             sel.row_begin = seen;
             sel.final_group = end >= n;
@@ -589,7 +640,7 @@ int xbq_set_option(const char* name, double value)
         return XBQ_OK;
     }
     if (!std::strcmp(name, "kernel")) {
-        if (!(value == 0 || value == 1)) return XBQ_EINVAL;
+        if (!(value == 0 || value == 1 || value == 2)) return XBQ_EINVAL;
         g_opt.kernel = static_cast<int>(value);
         return XBQ_OK;
     }

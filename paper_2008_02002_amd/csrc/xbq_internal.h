@@ -133,6 +133,23 @@ hipError_t launch_scan_dot(const DotArgs& a, bool dense, hipStream_t s);
 hipError_t launch_nibbles_db(const uint32_t* codes, int64_t n, int d, int bits, uint32_t* out, hipStream_t s);
 hipError_t launch_nibbles_q(const uint32_t* codes, int m, int d, int bits, uint32_t* out, int32_t* vsum, hipStream_t s);
 
+// Cross-check scan on the matrix cores (int8 MFMA): see xbq_mfma.hip.
+struct MfmaArgs {
+    const uint8_t* dbb;      // int8 rows of the database, [rows_padded][32 W]
+    int64_t rows_padded;     // bundles * 64
+    int64_t row_begin, row_end;   // row_begin a multiple of 32
+    const uint8_t* qb;       // int8 rows of the queries, [m_padded][32 W]
+    int m, m_padded;         // m_padded a multiple of 32
+    int qsplit, qranges, row_blocks;   // qsplit a multiple of 32
+    int W;
+    int full;                // d (2^Bq - 1)(2^Bd - 1)
+    const uint32_t* thr; uint32_t* cnt; uint64_t* cand; int cap;
+    uint32_t* dense; int dense_stride;
+};
+hipError_t launch_scan_mfma(const MfmaArgs& a, bool dense, hipStream_t s);
+hipError_t launch_bytes_db(const uint32_t* codes, int64_t n, int d, int bits, uint32_t* out, hipStream_t s);
+hipError_t launch_bytes_q(const uint32_t* codes, int m, int m_pad, int d, int bits, uint32_t* out, hipStream_t s);
+
 // Histogram selection (few queries): see xbq_hist.hip.
 struct HistArgs {
     const uint32_t* db;      // XBQ_BUNDLE64 codes

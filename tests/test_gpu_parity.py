@@ -250,13 +250,14 @@ DOT = [
 ]
 
 
+@pytest.mark.parametrize("kernel", [1, 2], ids=["dot8", "mfma"])
 @pytest.mark.parametrize("n,d,m,qb,db,k", DOT)
-def test_dot_product_cross_check_scan_gives_the_same_result(n, d, m, qb, db, k):
-    _say(f"dot cross-check n={n} d={d} m={m} {qb}x{db} k={k}")
+def test_dot_product_cross_check_scan_gives_the_same_result(n, d, m, qb, db, k, kernel):
+    _say(f"cross-check kernel={kernel} n={n} d={d} m={m} {qb}x{db} k={k}")
     Xdb = _rand(n, d, seed=n + d + 7)
     Xq = _rand(m, d, seed=n + d + 8)
     want = gu.oracle_search_asym(Xdb, Xq, db, qb, k, 2.1)
-    xbq.xbq_set_option("kernel", 1)
+    xbq.xbq_set_option("kernel", kernel)
     xbq.xbq_set_option("selector", 1)
     try:
         gu.assert_same(gu.gpu_search_asym(Xdb, Xq, db, qb, k, 2.1), want, "dot cross-check")
