@@ -10,6 +10,14 @@
 // by 16 bytes so the 16-byte operand reads of 32 lanes hit different banks) and every wavefront
 // multiplies each query tile with its R row tiles: 32 x 32 scores per v_mfma_i32_32x32x32_i8
 // chain.  The threshold test runs on the accumulator registers (16 compares per 1024 pairs).
+//
+// Survivors.  With 1024 pairs per accumulator tile almost every tile has a survivor, so the
+// returning global atomic that reserves a slot in the query's candidate list must not sit in
+// the loop.  Each wavefront appends its survivors to a record list of its own in LDS (the
+// slot comes from ballot ranks and a wavefront-uniform count: no atomic at all); once per
+// query tile it issues one global atomic per record and only stores the keys one iteration
+// later, when the slots have long come back.  A record that does not fit the list takes the
+// direct path (append_keys).
 
 #include "xbq_device.h"
 
@@ -92,6 +100,12 @@ __global__ __launch_bounds__(kBlock) void scan_mfma(const MfmaArgs a)
     constexpr int LROW = DK + 16;                        // LDS row stride: odd multiple of 16 bytes
     __shared__ __attribute__((aligned(16))) uint8_t tile[2][32 * LROW];
     __shared__ __attribute__((aligned(16))) int tau[2][32];
+    constexpr int RC = 2 * kLanes;                       // records per wavefront and query tile: two per lane
+    __shared__ uint64_t rec_key[4][RC];
+    __shared__ uint32_t rec_q[4][RC];
+    uint32_t recorded = 0;                               // records of this wavefront in the current query tile
+    uint32_t pend_q[2] = {0, 0}, pend_pos[2] = {0xffffffffu, 0xffffffffu};
+    uint64_t pend_key[2] = {0, 0};
     const int lane = lane_id();
     const int wave = threadIdx.x >> 6;
     const int half = lane >> 5, col = lane & 31;
@@ -190,16 +204,31 @@ __global__ __launch_bounds__(kBlock) void scan_mfma(const MfmaArgs a)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             const bool pass = acc[v] > tv[v] && row_ok;          // tau is INT_MAX for q >= m
-                            if (__ballot(pass) != 0) {
-                                const int qa = qt + 8 * (v >> 2) + (v & 3);      // lanes 0..31; lanes 32..63: qa + 4
+                            const uint64_t mask = __ballot(pass);
+                            if (mask != 0) {
+                                const uint32_t q = static_cast<uint32_t>(qt + 8 * (v >> 2) + 4 * half + (v & 3));
                                 const uint32_t D = static_cast<uint32_t>((a.full - acc[v]) >> 1);
-                                append_keys(pass && half == 0, D, row[r], &a.cnt[qa < a.m ? qa : 0],
-                                            a.cand + static_cast<size_t>(qa < a.m ? qa : 0) * a.cap,
-                                            static_cast<uint32_t>(a.cap));
-                                const int qb = qa + 4;
-                                append_keys(pass && half == 1, D, row[r], &a.cnt[qb < a.m ? qb : 0],
-                                            a.cand + static_cast<size_t>(qb < a.m ? qb : 0) * a.cap,
-                                            static_cast<uint32_t>(a.cap));
+                                const uint32_t slot = recorded +
+                                    __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                    __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+                                recorded += static_cast<uint32_t>(__popcll(mask));
+                                const bool fits = slot < static_cast<uint32_t>(RC);
+                                if (pass && fits) {
+                                    rec_key[wave][slot] = make_key(D, row[r]);
+                                    rec_q[wave][slot] = q;
+                                }
+                                // the rare record that does not fit goes straight to global memory
+                                // (per half: the two halves of a register belong to different queries)
+                                const bool spill = pass && !fits;
+                                if (__ballot(spill) != 0) {
+                                    const uint32_t qa = static_cast<uint32_t>(qt + 8 * (v >> 2) + (v & 3));
+                                    const uint32_t q0s = qa < static_cast<uint32_t>(a.m) ? qa : 0u;
+                                    const uint32_t q1s = qa + 4 < static_cast<uint32_t>(a.m) ? qa + 4 : 0u;
+                                    append_keys(spill && half == 0, D, row[r], &a.cnt[q0s],
+                                                a.cand + static_cast<size_t>(q0s) * a.cap, static_cast<uint32_t>(a.cap));
+                                    append_keys(spill && half == 1, D, row[r], &a.cnt[q1s],
+                                                a.cand + static_cast<size_t>(q1s) * a.cap, static_cast<uint32_t>(a.cap));
+                                }
                             }
                         }
                     }
@@ -209,6 +238,34 @@ __global__ __launch_bounds__(kBlock) void scan_mfma(const MfmaArgs a)
         if (more) commit(cur ^ 1);
         __syncthreads();
         cur ^= 1;
+        if (!DENSE) {
+            // slots reserved one iteration ago have come back: store those keys ...
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                if (pend_pos[i] < static_cast<uint32_t>(a.cap))
+                    a.cand[static_cast<size_t>(pend_q[i]) * a.cap + pend_pos[i]] = pend_key[i];
+                pend_pos[i] = 0xffffffffu;
+            }
+            // ... and reserve slots for the records this wavefront made in this query tile (its own
+            // LDS writes, read back in program order: no barrier involved)
+            const uint32_t have = recorded < static_cast<uint32_t>(RC) ? recorded : static_cast<uint32_t>(RC);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t slot = lane + i * kLanes;
+                if (slot < have) {
+                    pend_q[i] = rec_q[wave][slot];
+                    pend_key[i] = rec_key[wave][slot];
+                    pend_pos[i] = atomicAdd(&a.cnt[pend_q[i]], 1u);
+                }
+            }
+            recorded = 0;
+        }
+    }
+    if (!DENSE) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (pend_pos[i] < static_cast<uint32_t>(a.cap))
+                a.cand[static_cast<size_t>(pend_q[i]) * a.cap + pend_pos[i]] = pend_key[i];
     }
 }
 
