@@ -267,30 +267,33 @@ def main():
     # the cross-check scan (same integers from packed 4-bit dot products, d <= 256): what the
     # other formulation costs on this chip.  Reported beside the headline, never instead of it.
     if args.refine < 0 and w.d <= 256 and not any(kv.startswith("kernel=") for kv in args.set):
-        xbq.xbq_set_option("kernel", 1)
-        try:
-            ws2 = torch.empty(xbq.xbq_search_workspace_bytes(w.n, w.m, w.d, bits, k), dtype=torch.uint8, device="cuda")
-            idx2 = torch.empty_like(idx)
-            sc2 = torch.empty_like(score)
-            xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws2, idx=idx2, score=sc2)
-            torch.cuda.synchronize()
-            xbq.xbq_trace_enable(True)
-            b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            b0.record()
-            for _ in range(3):
+        for kernel, label, note in ((1, "cross_check_dot8", "v_dot8_i32_i4 on nibble-packed codes"),
+                                    (2, "cross_check_mfma", "v_mfma_i32_32x32x32_i8 on int8-decoded codes")):
+            xbq.xbq_set_option("kernel", kernel)
+            try:
+                ws2 = torch.empty(xbq.xbq_search_workspace_bytes(w.n, w.m, w.d, bits, k), dtype=torch.uint8,
+                                  device="cuda")
+                idx2 = torch.empty_like(idx)
+                sc2 = torch.empty_like(score)
                 xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws2, idx=idx2, score=sc2)
-            b1.record()
-            torch.cuda.synchronize()
-            dms, _, _ = xbq.xbq_trace_read()
-            xbq.xbq_trace_enable(False)
-            out["cross_check_dot8"] = {
-                "search_ms": b0.elapsed_time(b1) / 3, "scan_ms": dms / 3,
-                "queries_per_s_search_only": w.m / (b0.elapsed_time(b1) / 3 * 1e-3),
-                "identical_to_xor_path": bool(torch.equal(idx2, idx) and torch.equal(sc2, score)),
-                "note": "v_dot8_i32_i4 on nibble-packed codes; not the paper's XOR + popcount method"}
-            del ws2, idx2, sc2
-        finally:
-            xbq.xbq_set_option("kernel", 0)
+                torch.cuda.synchronize()
+                xbq.xbq_trace_enable(True)
+                b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                b0.record()
+                for _ in range(3):
+                    xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws2, idx=idx2, score=sc2)
+                b1.record()
+                torch.cuda.synchronize()
+                dms, _, _ = xbq.xbq_trace_read()
+                xbq.xbq_trace_enable(False)
+                out[label] = {
+                    "search_ms": b0.elapsed_time(b1) / 3, "scan_ms": dms / 3,
+                    "queries_per_s_search_only": w.m / (b0.elapsed_time(b1) / 3 * 1e-3),
+                    "identical_to_xor_path": bool(torch.equal(idx2, idx) and torch.equal(sc2, score)),
+                    "note": note + "; not the paper's XOR + popcount method"}
+                del ws2, idx2, sc2
+            finally:
+                xbq.xbq_set_option("kernel", 0)
     if not args.no_recall:
         r, nq = recall_at_k(Xdb, Xq, idx, k)
         out["recall_at_k"] = {"value": r, "queries": nq, "against": "exact fp32 cosine (torch matmul + topk)"}
