@@ -59,13 +59,45 @@ def cpu_baseline(w, bits, db_bits, k, scale, budget_s=15.0):
 def recall_at_k(Xdb_dev, Xq_dev, idx_dev, k, nq=256):
     """Precision@K (Section 5) of the returned rows against exact fp32 cosine, first nq queries."""
     import torch
-    nq = min(nq, Xq_dev.shape[0])
+    nq = min(nq, Xq_dev.shape[0], idx_dev.shape[0])
     sim = Xq_dev[:nq] @ Xdb_dev.T
     real = torch.topk(sim, k, dim=1).indices
     hits = 0
     for i in range(nq):
         hits += len(set(real[i].tolist()) & set(idx_dev[i].tolist()))
     return hits / float(nq * k), nq
+
+
+def fp32_reference_error(Xdb_dev, Xq_dev, nq=16, rows=100_000):
+    """Largest absolute difference between the fp32 cosine matrix the recall figure is taken
+    against and the same products in float64, on the first nq queries x first `rows` rows."""
+    nq = min(nq, Xq_dev.shape[0])
+    rows = min(rows, Xdb_dev.shape[0])
+    s32 = Xq_dev[:nq] @ Xdb_dev[:rows].T
+    s64 = Xq_dev[:nq].double() @ Xdb_dev[:rows].double().T
+    return float((s32.double() - s64).abs().max())
+
+
+def recall_by_scale(xbq, wl, w, Xdb, Xq, bits, db_bits, k, nq=256):
+    """Recall of the plain search at the three scale choices of Section 3.6: none (1), the
+    conservative 1 / max|x| and the relaxed 1 / (98th percentile of |x|)."""
+    import torch
+    nq = min(nq, w.m)
+    head = wl.database(w, 0, min(w.n, 100_000))
+    scales = {"1": 1.0, "1/max": wl.choose_scale(head, 1.0), "1/q98": wl.choose_scale(head, 0.98)}
+    db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, db_bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
+    q = torch.empty(xbq.xbq_code_bytes(nq, w.d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
+    ws = torch.empty(xbq.xbq_search_workspace_bytes(w.n, nq, w.d, bits, k), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((nq, k), dtype=torch.int32, device="cuda")
+    score = torch.empty((nq, k), dtype=torch.int32, device="cuda")
+    out = {}
+    for name, s in scales.items():
+        xbq.xbq_encode(Xdb, db_bits, s, xbq.BUNDLE64, out=db)
+        xbq.xbq_encode(Xq[:nq], bits, s, xbq.ROWS, out=q)
+        xbq.xbq_search_asym(db, w.n, db_bits, q, nq, bits, w.d, k, workspace=ws, idx=idx, score=score)
+        torch.cuda.synchronize()
+        out[name] = {"scale": s, "recall": recall_at_k(Xdb, Xq, idx, k, nq)[0]}
+    return out
 
 
 def main():
@@ -297,8 +329,11 @@ def main():
     if not args.no_recall:
         r, nq = recall_at_k(Xdb, Xq, idx, k)
         out["recall_at_k"] = {"value": r, "queries": nq, "against": "exact fp32 cosine (torch matmul + topk)"}
+        out["recall_at_k"]["fp32_reference_max_abs_err_vs_f64"] = fp32_reference_error(Xdb, Xq)
         if args.refine >= 0:
             out["recall_at_k"]["mean_candidates"] = float(ncand.float().mean())
+        else:
+            out["recall_at_k"]["by_scale"] = recall_by_scale(xbq, wl, w, Xdb, Xq, bits, db_bits, k)
     del Xdb
     torch.cuda.empty_cache()
     if not args.no_cpu:
