@@ -215,6 +215,26 @@ def main():
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_scan_launch:"):
                 traffic = float(line.split(":")[1])
+    # what the chip sustains on the two streams the rooflines are about (register-only XOR +
+    # population count; a streaming read of the fp32 database), beside the published peaks
+    pe0, pe1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pout, pops = xbq.xbq_probe_valu(20000)
+    torch.cuda.synchronize()
+    pe0.record()
+    xbq.xbq_probe_valu(20000, out=pout)
+    pe1.record()
+    torch.cuda.synchronize()
+    valu_measured = pops / (pe0.elapsed_time(pe1) * 1e-3) / 1e12
+    xbq.xbq_probe_read(Xdb, out=pout)
+    torch.cuda.synchronize()
+    pe0.record()
+    for _ in range(5):
+        xbq.xbq_probe_read(Xdb, out=pout)
+    pe1.record()
+    torch.cuda.synchronize()
+    read_measured = 5 * Xdb.numel() * 4 / (pe0.elapsed_time(pe1) * 1e-3)
+    del pout
+
     out = {
         "metric": "queries/s, 1M x d128 4-bit K=100 (encode + XOR/popcount scan + top-K)"
                   if w.name == "C2" else f"queries/s, {w.name}",
@@ -241,6 +261,8 @@ def main():
             "unit": "T lane-op/s (32-bit integer)",
             "frac": achieved / peak,
             "traffic": traffic,
+            "measured_peak": valu_measured,
+            "frac_of_measured_peak": achieved / valu_measured,
             "scan_ms_per_step": scan_ms / args.steps,
             "launches_per_step": launches / args.steps,
             "avg_launch_ms": scan_ms / max(launches, 1),
@@ -248,7 +270,9 @@ def main():
         },
         "encode": {"db_ms": enc_ms,
                    "GBps": w.n * cm.encode_bytes_per_row(w.d, db_bits) / 1e9 / (enc_ms * 1e-3),
-                   "hbm_frac": w.n * cm.encode_bytes_per_row(w.d, db_bits) / (enc_ms * 1e-3) / cm.HBM_BYTES_PER_S},
+                   "hbm_frac": w.n * cm.encode_bytes_per_row(w.d, db_bits) / (enc_ms * 1e-3) / cm.HBM_BYTES_PER_S,
+                   "measured_streaming_read_GBps": read_measured / 1e9,
+                   "frac_of_measured_read": w.n * cm.encode_bytes_per_row(w.d, db_bits) / (enc_ms * 1e-3) / read_measured},
     }
     # the regime the paper measured (Section 5: single-query requests): one query against the
     # resident codes, bound by the HBM stream of the database codes

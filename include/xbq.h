@@ -144,6 +144,26 @@ int xbq_trace_enable(int on);
 int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
 
 /*
+ * Measurement aids: the rates this chip sustains on the two streams the search is bound by,
+ * for quoting a kernel against a measured ceiling beside the published one.  Both are
+ * asynchronous on `stream` and timed by the caller; `out` is device memory of at least
+ * xbq_probe_out_bytes() bytes (XBQ_EWORKSPACE otherwise) that receives a checkable result.
+ *   xbq_probe_valu  the credited instruction pair of the scan (Section 3.3, Eq. 6: XOR with a
+ *                   scalar operand, population count with accumulate) from registers only, 8
+ *                   wavefronts per SIMD.  Thread t (0 <= t < xbq_probe_out_bytes()/4) holds
+ *                   x_j = (t+1)*0x9E3779B1 + j*0x85EBCA77 (mod 2^32), j < 16, and writes
+ *                   out[t] = sum over i < 4*iters, j < 16 of POPCNT(x_j ^ (seed + i)).
+ *                   *lane_ops (host, may be NULL) receives the XOR + population-count lane
+ *                   operations of the launch.  1 <= iters <= 2^24.
+ *   xbq_probe_read  reads `bytes` bytes (multiple of 16, 16-byte aligned, device) once with
+ *                   16-byte loads; out[w], w < 2048, is the sum (mod 2^32) of the 32-bit words
+ *                   read by workgroup w, so the sum of out[] is the sum of all words.
+ */
+size_t xbq_probe_out_bytes(void);
+int xbq_probe_valu(uint32_t* out, size_t out_bytes, uint32_t seed, int iters, double* lane_ops, void* stream);
+int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_bytes, void* stream);
+
+/*
  * Tuning knobs (process-wide, host side only):
  *   "growth"  upper bound on rows-after-a-group / rows-before-it (default 4.0; lowered
  *             automatically for large k so the survivor lists stay short)

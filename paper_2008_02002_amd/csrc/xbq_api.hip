@@ -626,6 +626,26 @@ int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs)
     return XBQ_OK;
 }
 
+size_t xbq_probe_out_bytes(void) { return probe_out_bytes(); }
+
+int xbq_probe_valu(uint32_t* out, size_t out_bytes, uint32_t seed, int iters, double* lane_ops, void* stream)
+{
+    if (!out || reinterpret_cast<uintptr_t>(out) % 4 || iters < 1 || iters > (1 << 24)) return XBQ_EINVAL;
+    if (out_bytes < probe_out_bytes()) return XBQ_EWORKSPACE;
+    if (lane_ops) *lane_ops = probe_valu_lane_ops(iters);
+    const hipError_t e = launch_probe_valu(out, seed, iters, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XBQ_OK : fail_hip(e);
+}
+
+int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_bytes, void* stream)
+{
+    if (!buf || !out || reinterpret_cast<uintptr_t>(buf) % 16 || reinterpret_cast<uintptr_t>(out) % 4 || bytes % 16)
+        return XBQ_EINVAL;
+    if (out_bytes < probe_out_bytes()) return XBQ_EWORKSPACE;
+    const hipError_t e = launch_probe_read(buf, bytes, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XBQ_OK : fail_hip(e);
+}
+
 int xbq_set_option(const char* name, double value)
 {
     if (!name) return XBQ_EINVAL;

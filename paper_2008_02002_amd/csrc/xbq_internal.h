@@ -180,4 +180,10 @@ hipError_t launch_clear(uint32_t* p, int64_t count, hipStream_t s);
 hipError_t launch_scan_hist(const HistArgs& a, hipStream_t s);
 hipError_t launch_hist_collect(const CollectArgs& a, hipStream_t s);
 
+// xbq_probe.hip: sustained-rate probes (measurement aids)
+size_t probe_out_bytes();
+double probe_valu_lane_ops(int iters);
+hipError_t launch_probe_valu(uint32_t* out, uint32_t seed, int iters, hipStream_t s);
+hipError_t launch_probe_read(const void* buf, size_t bytes, uint32_t* out, hipStream_t s);
+
 }  // namespace xbq

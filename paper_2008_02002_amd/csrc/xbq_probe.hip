@@ -1,0 +1,79 @@
+// Measurement aids: what this chip sustains on the two streams the rooflines of the search are
+// quoted against.  probe_xor_popcount issues the scan's credited instruction pair (v_xor_b32
+// with a scalar operand, v_bcnt_u32_b32 with accumulate; Section 3.3, Eq. 6) from registers
+// only; probe_read streams a buffer from memory with 16-byte loads.  Both write a checkable
+// result so that nothing can be optimised away, and both are timed by the caller.
+
+#include "xbq_device.h"
+
+namespace xbq {
+
+constexpr int kProbeBlocks = 256 * 8;      // 8 workgroups of 4 wavefronts per compute unit: 8 wavefronts per SIMD
+constexpr int kProbeWords = 16;            // row words held per lane, as in the 4-bit d = 128 scan
+constexpr int kProbeUnroll = 4;
+
+// out[thread] = sum over it < iters * kProbeUnroll, j < kProbeWords of POPCNT(x_j ^ (seed + it)),
+// x_j = (thread + 1) * 0x9E3779B1 + j * 0x85EBCA77 (mod 2^32), thread = global thread number.
+__global__ __launch_bounds__(kBlock) void probe_xor_popcount(uint32_t* out, uint32_t seed, int iters)
+{
+    const uint32_t thread = blockIdx.x * kBlock + threadIdx.x;
+    uint32_t x[kProbeWords];
+#pragma unroll
+    for (int j = 0; j < kProbeWords; ++j) x[j] = (thread + 1u) * 0x9E3779B1u + static_cast<uint32_t>(j) * 0x85EBCA77u;
+    uint32_t acc[4] = {0, 0, 0, 0};
+    uint32_t y = seed;                                   // uniform: lives in a scalar register
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < kProbeUnroll; ++u) {
+#pragma unroll
+            for (int j = 0; j < kProbeWords; ++j) acc[j & 3] = popcount_add(x[j] ^ y, acc[j & 3]);
+            ++y;
+        }
+    }
+    out[thread] = acc[0] + acc[1] + acc[2] + acc[3];
+}
+
+// out[workgroup] = sum (mod 2^32) of the 32-bit words this workgroup read, grid-stride.
+__global__ __launch_bounds__(kBlock) void probe_read(const uint4* __restrict__ p, size_t n16, uint32_t* out)
+{
+    __shared__ uint32_t total;
+    if (threadIdx.x == 0) total = 0;
+    __syncthreads();
+    uint32_t s = 0;
+    const size_t stride = static_cast<size_t>(gridDim.x) * kBlock;
+    size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {      // four loads in flight per lane
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], e = p[i + 3 * stride];
+        s += a.x + a.y + a.z + a.w + b.x + b.y + b.z + b.w + c.x + c.y + c.z + c.w + e.x + e.y + e.z + e.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = p[i];
+        s += a.x + a.y + a.z + a.w;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_down(s, off);
+    if (lane_id() == 0) atomicAdd(&total, s);
+    __syncthreads();
+    if (threadIdx.x == 0) out[blockIdx.x] = total;
+}
+
+size_t probe_out_bytes() { return static_cast<size_t>(kProbeBlocks) * kBlock * sizeof(uint32_t); }
+
+double probe_valu_lane_ops(int iters)
+{
+    return 2.0 * kProbeWords * kProbeUnroll * static_cast<double>(iters) * kProbeBlocks * kBlock;
+}
+
+hipError_t launch_probe_valu(uint32_t* out, uint32_t seed, int iters, hipStream_t s)
+{
+    hipLaunchKernelGGL(probe_xor_popcount, dim3(kProbeBlocks), dim3(kBlock), 0, s, out, seed, iters);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_read(const void* buf, size_t bytes, uint32_t* out, hipStream_t s)
+{
+    hipLaunchKernelGGL(probe_read, dim3(kProbeBlocks), dim3(kBlock), 0, s, static_cast<const uint4*>(buf), bytes / 16, out);
+    return hipGetLastError();
+}
+
+}  // namespace xbq

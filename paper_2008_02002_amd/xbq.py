@@ -20,7 +20,7 @@ REFINE_MAX_CANDIDATES = 2048
 EXPORTS = (
     "xbq_version", "xbq_strerror", "xbq_last_hip_error", "xbq_code_bytes", "xbq_encode",
     "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_trace_enable", "xbq_trace_read",
-    "xbq_set_option",
+    "xbq_probe_out_bytes", "xbq_probe_valu", "xbq_probe_read", "xbq_set_option",
 )
 
 _lib = None
@@ -68,6 +68,11 @@ def lib() -> ctypes.CDLL:
         L.xbq_trace_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64),
                                      ctypes.POINTER(ctypes.c_double)]
         L.xbq_trace_read.restype = i32
+        L.xbq_probe_out_bytes.restype = sz
+        L.xbq_probe_valu.argtypes = [vp, sz, ctypes.c_uint32, i32, ctypes.POINTER(ctypes.c_double), vp]
+        L.xbq_probe_valu.restype = i32
+        L.xbq_probe_read.argtypes = [vp, sz, vp, sz, vp]
+        L.xbq_probe_read.restype = i32
         L.xbq_set_option.argtypes = [ctypes.c_char_p, ctypes.c_double]
         L.xbq_set_option.restype = i32
         _lib = L
@@ -202,3 +207,33 @@ def xbq_trace_read():
     ms, n, pairs = ctypes.c_double(), ctypes.c_int64(), ctypes.c_double()
     _check(lib().xbq_trace_read(ctypes.byref(ms), ctypes.byref(n), ctypes.byref(pairs)), "xbq_trace_read")
     return ms.value, n.value, pairs.value
+
+
+def xbq_probe_out_bytes() -> int:
+    return lib().xbq_probe_out_bytes()
+
+
+def xbq_probe_valu(iters: int, seed: int = 1, out=None):
+    """Launch the XOR + population-count rate probe.  Returns (out uint32-as-int32 CUDA tensor,
+    lane operations of the launch)."""
+    import torch
+    if out is None:
+        out = torch.empty(xbq_probe_out_bytes() // 4, dtype=torch.int32, device="cuda")
+    ops = ctypes.c_double()
+    _check(lib().xbq_probe_valu(ctypes.c_void_p(out.data_ptr()), out.numel() * out.element_size(), seed & 0xffffffff,
+                                int(iters), ctypes.byref(ops), _stream()), "xbq_probe_valu")
+    return out, ops.value
+
+
+def xbq_probe_read(buf, out=None):
+    """Launch the streaming-read probe over a contiguous CUDA tensor.  Returns the per-workgroup
+    word sums (uint32 as int32, the first 2048 entries of out)."""
+    import torch
+    if not (buf.is_cuda and buf.is_contiguous()):
+        raise ValueError("buf must be a contiguous CUDA tensor")
+    if out is None:
+        out = torch.empty(xbq_probe_out_bytes() // 4, dtype=torch.int32, device=buf.device)
+    _check(lib().xbq_probe_read(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                ctypes.c_void_p(out.data_ptr()), out.numel() * out.element_size(), _stream()),
+           "xbq_probe_read")
+    return out[:2048]

@@ -1,0 +1,64 @@
+"""The two rate probes of the library write a checkable result: compare it with the closed
+definition their header comment gives (plain NumPy here, nothing of the method)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from paper_2008_02002_amd import xbq
+
+
+def _popcount(a):
+    a = a.astype(np.uint64)
+    c = np.zeros(a.shape, dtype=np.uint64)
+    for s in range(32):
+        c += (a >> np.uint64(s)) & np.uint64(1)
+    return c
+
+
+@pytest.mark.parametrize("iters,seed", [(1, 0), (5, 0xfffffffe), (64, 12345)])
+def test_probe_valu_result(iters, seed):
+    import torch
+    print("probe valu", iters, seed, flush=True)
+    out, ops = xbq.xbq_probe_valu(iters, seed)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint32)
+    nthreads = xbq.xbq_probe_out_bytes() // 4
+    assert got.shape == (nthreads,)
+    assert ops == 2.0 * 16 * 4 * iters * nthreads
+    t = np.concatenate([np.arange(0, 2048), np.arange(nthreads - 2048, nthreads)]).astype(np.uint64)
+    want = np.zeros(t.shape, dtype=np.uint64)
+    for j in range(16):
+        x = ((t + 1) * 0x9E3779B1 + j * 0x85EBCA77) & 0xffffffff
+        for i in range(4 * iters):
+            want += _popcount(x ^ np.uint64((seed + i) & 0xffffffff))
+    assert np.array_equal(got[t.astype(np.int64)].astype(np.uint64), want & 0xffffffff)
+
+
+@pytest.mark.parametrize("nbytes", [16, 4096, 1 << 20, (1 << 26) + 16 * 12345])
+def test_probe_read_sums_every_word_once(nbytes):
+    import torch
+    print("probe read", nbytes, flush=True)
+    g = torch.Generator(device="cpu").manual_seed(nbytes)
+    words = torch.randint(-2**31, 2**31 - 1, (nbytes // 4,), dtype=torch.int32, generator=g)
+    dev = words.cuda()
+    out = xbq.xbq_probe_read(dev)
+    torch.cuda.synchronize()
+    got = int(out.cpu().numpy().view(np.uint32).astype(np.uint64).sum()) & 0xffffffff
+    want = int(words.numpy().view(np.uint32).astype(np.uint64).sum()) & 0xffffffff
+    assert got == want
+
+
+def test_probe_argument_errors():
+    import ctypes
+    import torch
+    L = xbq.lib()
+    small = torch.empty(16, dtype=torch.int32, device="cuda")
+    big = torch.empty(xbq.xbq_probe_out_bytes() // 4, dtype=torch.int32, device="cuda")
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    assert L.xbq_probe_valu(p(small), 64, 0, 1, None, None) == xbq.EWORKSPACE
+    assert L.xbq_probe_valu(p(big), big.numel() * 4, 0, 0, None, None) == xbq.EINVAL
+    assert L.xbq_probe_valu(None, big.numel() * 4, 0, 1, None, None) == xbq.EINVAL
+    assert L.xbq_probe_read(p(big), 24, p(big), big.numel() * 4, None) == xbq.EINVAL          # not a multiple of 16
+    assert L.xbq_probe_read(ctypes.c_void_p(big.data_ptr() + 4), 16, p(big), big.numel() * 4, None) == xbq.EINVAL
+    assert L.xbq_probe_read(p(big), 16, p(small), 64, None) == xbq.EWORKSPACE
