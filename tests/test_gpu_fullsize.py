@@ -144,3 +144,31 @@ def test_c2_full_size_refine_4x3():
     gu.assert_refined_matches((idx[sub], sim[sub], cand[sub]), X, Xq[sub], D, k, extra, xbq.REFINE_MAX_CANDIDATES)
     real, _ = od.exact_cosine_topk(X, Xq[sub[:16]], k)
     assert od.precision_at_k(idx[sub[:16]], real) > 0.9
+
+
+def test_c5_full_size_refine_hits_the_candidate_bound():
+    """Algorithm 1 on the largest workload: 3.84 GB of fp32 rows (row offsets beyond 2^31
+    bytes in the refine gather) and candidate lists that reach the documented bound."""
+    import torch
+    from oracle import definition as od
+    w = wl.WORKLOADS["C5"]
+    k, extra, bits = 100, 200, 4
+    X, scale = wl.database(w), wl.workload_scale(w)
+    Xq = wl.queries(w)
+    xd, xq = torch.from_numpy(X).cuda(), torch.from_numpy(Xq).cuda()
+    db = xbq.xbq_encode(xd, bits, scale, xbq.BUNDLE64)
+    q = xbq.xbq_encode(xq, bits, scale, xbq.ROWS)
+    idx, sim, cand = xbq.xbq_search_refine(xd, db, bits, xq, q, bits, k, extra)
+    torch.cuda.synchronize()
+    idx, sim, cand = idx.cpu().numpy(), sim.cpu().numpy(), cand.cpu().numpy()
+    del xd, db
+    _say("C5 refine: searched on the GPU")
+    assert cand.max() == xbq.REFINE_MAX_CANDIDATES
+    sub = np.concatenate([np.arange(8), w.m - 1 - np.arange(8)])
+    S = oc.scores(oc.encode(X, bits, scale), oc.encode(Xq[sub], bits, scale), w.d)
+    D = od.distance_from_score(S, w.d, bits, bits)
+    del S
+    _say("C5 refine: oracle distances done")
+    gu.assert_refined_matches((idx[sub], sim[sub], cand[sub]), X, Xq[sub], D, k, extra, xbq.REFINE_MAX_CANDIDATES)
+    real, _ = od.exact_cosine_topk(X, Xq[sub], k)
+    assert od.precision_at_k(idx[sub], real) > 0.95
