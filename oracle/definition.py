@@ -296,6 +296,44 @@ def k_select(dist: np.ndarray, X_db: np.ndarray, X_q: np.ndarray, K: int, extra:
     return idx, sim, count
 
 
+def k_select_candidates_by_levels(dist_row: np.ndarray, K: int, extra: int, limit: int) -> np.ndarray:
+    """Algorithm 1's candidate list L under a bound on its length that keeps distance levels
+    whole: maxDistance starts at (K-th smallest distance) + extraDistance as printed and, while
+    more than ``limit`` rows lie within it, is lowered one unit at a time, never below the K-th
+    smallest distance itself.  If the rows within the K-th smallest distance alone exceed the
+    limit (ties), L is the K best rows by (distance, row).  With limit >= number of rows within
+    the printed boundary this is Algorithm 1 unchanged.  Returned in (distance, row) order."""
+    dist_row = np.asarray(dist_row, dtype=np.int64)
+    d_k = kth_distance_by_histogram(dist_row, K)
+    max_distance = d_k + extra
+    while max_distance >= d_k:
+        rows = np.nonzero(dist_row <= max_distance)[0]
+        if len(rows) <= limit:
+            return rows[np.lexsort((rows, dist_row[rows]))]
+        max_distance -= 1
+    rows = np.arange(len(dist_row))
+    return rows[np.lexsort((rows, dist_row))][:K]
+
+
+def k_select_by_levels(dist: np.ndarray, X_db: np.ndarray, X_q: np.ndarray, K: int, extra: int, limit: int):
+    """Algorithm 1 with :func:`k_select_candidates_by_levels` as its candidate list: refine by
+    the exact inner product (float64), sort (similarity descending, ties to the lower row),
+    first K.  Returns (idx [m, K], similarity float64 [m, K], |L| [m])."""
+    m = dist.shape[0]
+    idx = np.empty((m, K), dtype=np.int64)
+    sim = np.empty((m, K), dtype=np.float64)
+    count = np.empty(m, dtype=np.int64)
+    Xq = np.asarray(X_q, dtype=np.float64)
+    for q in range(m):
+        L = k_select_candidates_by_levels(dist[q], K, extra, limit)
+        count[q] = len(L)
+        s = np.asarray(X_db[L], dtype=np.float64) @ Xq[q]
+        order = np.lexsort((L, -s))[:K]
+        idx[q] = L[order]
+        sim[q] = s[order]
+    return idx, sim, count
+
+
 def distance_from_score(S, d: int, Bq: int, Bd: int):
     """Inverse of :func:`score_from_distance`."""
     return (d * ((1 << Bq) - 1) * ((1 << Bd) - 1) - np.asarray(S, dtype=np.int64)) // 2

@@ -369,6 +369,71 @@ def test_k_select_refines_within_candidates_and_precision_grows_with_extra():
     assert prev == 1.0
 
 
+def test_candidates_by_levels_hand_case():
+    # distances of 10 rows, K = 3: sorted (D,row) = (1,r4) (2,r0) (2,r7) (3,r2) (3,r5) (3,r9) (5,r1) (6,r3) (6,r8) (9,r6)
+    D = np.array([2, 5, 3, 6, 1, 3, 9, 2, 6, 3])
+    f = od.k_select_candidates_by_levels
+    assert od.kth_distance_by_histogram(D, 3) == 2
+    assert f(D, 3, 0, 100).tolist() == [4, 0, 7]                       # D <= 2
+    assert f(D, 3, 1, 100).tolist() == [4, 0, 7, 2, 5, 9]              # D <= 3
+    assert f(D, 3, 3, 100).tolist() == [4, 0, 7, 2, 5, 9, 1]           # D <= 5
+    assert f(D, 3, 100, 100).tolist() == [4, 0, 7, 2, 5, 9, 1, 3, 8, 6]
+    # bound on the length: levels stay whole, the boundary moves down
+    assert f(D, 3, 4, 8).tolist() == [4, 0, 7, 2, 5, 9, 1]             # D <= 6 would be 9 rows: back to D <= 5
+    assert f(D, 3, 4, 6).tolist() == [4, 0, 7, 2, 5, 9]                # D <= 3
+    assert f(D, 3, 4, 5).tolist() == [4, 0, 7]                         # D <= 3 is 6 rows: D <= 2
+    assert f(D, 3, 4, 3).tolist() == [4, 0, 7]
+    # K = 4: the K-th smallest distance is 3 and six rows lie within it; a limit of 5 cannot hold them
+    assert od.kth_distance_by_histogram(D, 4) == 3
+    assert f(D, 4, 2, 5).tolist() == [4, 0, 7, 2]                      # the K best by (distance, row)
+    assert f(D, 4, 2, 6).tolist() == [4, 0, 7, 2, 5, 9]
+
+
+def test_candidates_by_levels_properties():
+    _, _, D = _kselect_case(35, n=2500, m=6)
+    n = D.shape[1]
+    for q in range(D.shape[0]):
+        for K, extra in ((1, 0), (10, 7), (10, 60), (100, 25)):
+            whole = od.k_select_candidates(D[q], K, extra)
+            # a generous limit leaves Algorithm 1's list untouched
+            assert od.k_select_candidates_by_levels(D[q], K, extra, n).tolist() == whole.tolist()
+            assert od.k_select_candidates_by_levels(D[q], K, extra, len(whole)).tolist() == whole.tolist()
+            for limit in (K, K + 1, len(whole) - 1, max(K, len(whole) // 2), max(K, len(whole) // 7)):
+                if limit < K:
+                    continue
+                L = od.k_select_candidates_by_levels(D[q], K, extra, limit)
+                assert K <= len(L) <= max(limit, K)
+                keys = [(int(D[q, r]), int(r)) for r in L]
+                assert keys == sorted(keys)
+                assert L.tolist() == whole[:len(L)].tolist()                  # a prefix of the printed list
+                d_k = sorted(D[q].tolist())[K - 1]
+                top = int(D[q, L[-1]])
+                inside = int((D[q] <= top).sum())
+                if inside == len(L):                                          # whole levels ...
+                    sd = np.sort(D[q])
+                    above = sd[sd > top]
+                    if len(above) and above[0] <= d_k + extra:                # ... and the next occupied one would not fit
+                        assert int(np.searchsorted(sd, above[0], side="right")) > limit
+                else:                                                         # ties at the K-th distance exceed the limit
+                    assert top == d_k and len(L) == K and int((D[q] <= d_k).sum()) > limit
+
+
+def test_k_select_by_levels_equals_k_select_when_nothing_is_cut():
+    Xd, Xq, D = _kselect_case(36, n=1500, m=5)
+    for extra in (0, 12, 90):
+        a = od.k_select(D, Xd, Xq, 10, extra)
+        b = od.k_select_by_levels(D, Xd, Xq, 10, extra, limit=1500)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    # and it re-ranks exactly its own candidate list
+    idx, sim, count = od.k_select_by_levels(D, Xd, Xq, 10, 90, limit=200)
+    for q in range(Xq.shape[0]):
+        L = od.k_select_candidates_by_levels(D[q], 10, 90, 200).tolist()
+        assert count[q] == len(L) <= 200
+        want = sorted(L, key=lambda r: (-float(Xd[r].astype(np.float64) @ Xq[q].astype(np.float64)), r))[:10]
+        assert idx[q].tolist() == want
+
+
 def test_distance_from_score_roundtrip():
     D = np.array([[0, 5, 77], [1, 2, 3]])
     assert np.array_equal(od.distance_from_score(od.score_from_distance(D, 50, 4, 3), 50, 4, 3), D)
