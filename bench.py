@@ -130,6 +130,9 @@ def main():
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--refine", type=int, default=-1, metavar="EXTRA",
                     help="time the candidate search + fp32 refine (xbq_search_refine) with this extra distance")
+    ap.add_argument("--k-select", type=int, default=-1, metavar="EXTRA",
+                    help="time Algorithm 1 with the whole candidate list (xbq_k_select) with this extra distance")
+    ap.add_argument("--max-candidates", type=int, default=1 << 17, help="candidate bound of --k-select")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (reference for HBM byte counters)")
     ap.add_argument("--set", action="append", default=[], metavar="NAME=VALUE",
@@ -168,7 +171,13 @@ def main():
         Xdb[lo:hi] = torch.from_numpy(wl.database(w, lo, hi)).cuda()
     db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, db_bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
     q = torch.empty(xbq.xbq_code_bytes(w.m, w.d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
-    if args.refine >= 0:
+    if args.k_select >= 0 and args.refine >= 0:
+        sys.exit("bench.py: --refine and --k-select exclude each other")
+    if args.k_select >= 0:
+        wsb = xbq.lib().xbq_k_select_workspace_bytes(w.n, w.m, w.d, bits, k, args.k_select, args.max_candidates)
+        sim = torch.empty((w.m, k), dtype=torch.float32, device="cuda")
+        ncand = torch.empty((w.m,), dtype=torch.int32, device="cuda")
+    elif args.refine >= 0:
         wsb = xbq.lib().xbq_search_refine_workspace_bytes(w.n, w.m, w.d, bits, k)
         sim = torch.empty((w.m, k), dtype=torch.float32, device="cuda")
         ncand = torch.empty((w.m,), dtype=torch.int32, device="cuda")
@@ -179,7 +188,10 @@ def main():
     score = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
 
     def search():
-        if args.refine >= 0:
+        if args.k_select >= 0:
+            xbq.xbq_k_select(Xdb, db, db_bits, Xq, q, bits, k, args.k_select, args.max_candidates, workspace=ws,
+                             idx=idx, sim=sim, cand=ncand)
+        elif args.refine >= 0:
             xbq.xbq_search_refine(Xdb, db, db_bits, Xq, q, bits, k, args.refine, workspace=ws, idx=idx, sim=sim,
                                   cand=ncand)
         else:
@@ -268,7 +280,9 @@ def main():
         "config": {"workload": f"{w.name}: n={w.n} d={w.d} m={w.m} bits={bits}" +
                                (f"x{db_bits}" if db_bits != bits else "") + f" K={k} ({w.kind}, seed {w.seed})",
                    "scale": scale, "options": args.set,
-                   "path": "xbq_search_refine extra=%d" % args.refine if args.refine >= 0 else "xbq_search"},
+                   "path": ("xbq_k_select extra=%d max_candidates=%d" % (args.k_select, args.max_candidates)
+                            if args.k_select >= 0 else
+                            "xbq_search_refine extra=%d" % args.refine if args.refine >= 0 else "xbq_search")},
         "roofline": {
             "bound": "alu",
             "kernel": "scan (XOR + population count), all launches of one step",
@@ -292,7 +306,8 @@ def main():
     }
     # the regime the paper measured (Section 5: single-query requests): one query against the
     # resident codes, bound by the HBM stream of the database codes
-    if args.refine < 0:
+    plain = args.refine < 0 and args.k_select < 0
+    if plain:
         for mq in (1, 8):
             if mq > w.m:
                 continue
@@ -338,7 +353,7 @@ def main():
             del idx1, sc1, ws1
     # the cross-check scan (same integers from packed 4-bit dot products, d <= 256): what the
     # other formulation costs on this chip.  Reported beside the headline, never instead of it.
-    if args.refine < 0 and w.d <= 256 and not any(kv.startswith("kernel=") for kv in args.set):
+    if plain and w.d <= 256 and not any(kv.startswith("kernel=") for kv in args.set):
         for kernel, label, note in ((1, "cross_check_dot8", "v_dot8_i32_i4 on nibble-packed codes"),
                                     (2, "cross_check_mfma", "v_mfma_i32_32x32x32_i8 on int8-decoded codes")):
             xbq.xbq_set_option("kernel", kernel)
@@ -370,8 +385,9 @@ def main():
         r, nq = recall_at_k(Xdb, Xq, idx, k)
         out["recall_at_k"] = {"value": r, "queries": nq, "against": "exact fp32 cosine (torch matmul + topk, in row slabs)"}
         out["recall_at_k"]["fp32_reference_max_abs_err_vs_f64"] = fp32_reference_error(Xdb, Xq)
-        if args.refine >= 0:
+        if not plain:
             out["recall_at_k"]["mean_candidates"] = float(ncand.float().mean())
+            out["recall_at_k"]["max_candidates"] = int(ncand.max())
         else:
             out["recall_at_k"]["by_scale"] = recall_by_scale(xbq, wl, w, Xdb, Xq, bits, db_bits, k)
     del Xdb

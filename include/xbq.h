@@ -51,6 +51,8 @@ extern "C" {
 #define XBQ_MAX_BITS 4      /* bits per coordinate: 1..4                              */
 #define XBQ_MAX_DIM  2048   /* d: 1..2048                                             */
 #define XBQ_MAX_K    1024   /* k: 1..min(n, 1024)  (Section 5 evaluates K up to 1000) */
+#define XBQ_MAX_EXTRA 4095  /* extra distance of xbq_k_select                          */
+#define XBQ_MAX_CANDIDATES (1 << 22)   /* candidate bound of xbq_k_select              */
 
 int xbq_version(void);
 const char* xbq_strerror(int code);
@@ -132,6 +134,29 @@ int xbq_search_refine(const float* X_db, const uint32_t* db_codes, int64_t n, in
                       const float* X_q, const uint32_t* q_codes, int64_t m, int q_bits, int d, int k,
                       int extra_distance, int32_t* idx, float* similarity, int32_t* candidates,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Algorithm 1 (K-Select) with its candidate list taken whole.  For each query: D_K = the K-th
+ * smallest distance over all rows (the exact search above); L = every row with
+ * D <= D_K + extra_distance; the K rows of L with the largest fp32 inner product with the
+ * query are returned, sorted by (similarity descending, row ascending) -- the outputs mean what
+ * they mean for xbq_search_refine, and candidates[q] = |L|.
+ * max_candidates (k .. XBQ_MAX_CANDIDATES) bounds |L| and sizes the workspace (8 bytes per
+ * slot per query of a batch; queries are processed in batches so that the lists stay near
+ * 2 GiB).  A query with more rows than that within its boundary has the boundary lowered, one
+ * distance unit at a time and never below D_K, until the rows within it fit; if the rows with
+ * D <= D_K alone do not fit (ties), L is the K best rows by (D, row).
+ * 0 <= extra_distance <= XBQ_MAX_EXTRA.  Cost: two scans of the database per call (the exact
+ * search, then the collection) plus the refine, and a third scan for a batch in which some
+ * query had its boundary lowered; xbq_search_refine needs one scan, and its list is at most
+ * 2048 rows.
+ */
+size_t xbq_k_select_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int k, int extra_distance,
+                                    int64_t max_candidates);
+int xbq_k_select(const float* X_db, const uint32_t* db_codes, int64_t n, int db_bits,
+                 const float* X_q, const uint32_t* q_codes, int64_t m, int q_bits, int d, int k,
+                 int extra_distance, int64_t max_candidates, int32_t* idx, float* similarity,
+                 int32_t* candidates, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement aid.  While tracing is on, xbq_search brackets every launch of the scan

@@ -184,7 +184,7 @@ hipError_t traced_scan(const ScanArgs& a, bool dense, hipStream_t s)
         e = hipEventRecord(g_trace.ev[g_trace.used + 1], s);
         if (e != hipSuccess) return e;
         g_trace.used += 2;
-        g_trace.pairs += static_cast<double>(a.row_end - a.row_begin) * a.m;
+        if (a.run_flag == nullptr) g_trace.pairs += static_cast<double>(a.row_end - a.row_begin) * a.m;   // a flagged launch may do nothing
     }
     return hipSuccess;
 }
@@ -481,6 +481,150 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
     return XBQ_OK;
 }
 
+// Algorithm 1 with the whole candidate list: the plain exact search of a batch of queries, then
+// one collecting scan over all rows with the threshold D_K + extra + 1, then the refine.
+struct KPlan {
+    int64_t batch = 0;       // queries per batch: the candidate lists of a batch stay near 2 GiB
+    int cap = 0, parts = 1;
+    size_t inner = 0;        // workspace of the plain search of one batch
+    size_t off_idx1 = 0, off_score1 = 0, off_dk = 0, off_thr = 0, off_cnt = 0, off_q = 0, off_parts = 0, off_list = 0;
+    size_t off_thr2 = 0, off_flag = 0, off_levels = 0;
+    size_t total = 0;
+};
+
+KPlan make_kplan(int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_candidates, int extra)
+{
+    KPlan kp;
+    kp.cap = static_cast<int>(max_candidates < n ? max_candidates : n);
+    int64_t batch = (int64_t(1) << 31) / (int64_t(8) * kp.cap);
+    if (batch < 1) batch = 1;
+    if (batch > 8192) batch = 8192;
+    kp.batch = m < batch ? m : batch;
+    const Plan whole = make_plan(n, kp.batch, d, q_bits, k, false);
+    kp.inner = whole.total;
+    if (m % kp.batch) {                                   // a short last batch may take the few-query path
+        const size_t t = make_plan(n, m % kp.batch, d, q_bits, k, false).total;
+        if (t > kp.inner) kp.inner = t;
+    }
+    int parts = kp.batch >= 1024 ? 1 : static_cast<int>((1024 + kp.batch - 1) / kp.batch);
+    if (parts > kSortCap / k) parts = kSortCap / k;
+    const int pieces = (kp.cap + 2047) / 2048;
+    if (parts > pieces) parts = pieces;
+    kp.parts = parts < 1 ? 1 : parts;
+    const size_t b = static_cast<size_t>(kp.batch);
+    size_t off = align_up(kp.inner, 256);
+    kp.off_idx1 = off;   off = align_up(off + b * k * sizeof(int32_t), 256);
+    kp.off_score1 = off; off = align_up(off + b * k * sizeof(int32_t), 256);
+    kp.off_dk = off;     off = align_up(off + b * sizeof(uint32_t), 256);
+    kp.off_thr = off;    off = align_up(off + b * sizeof(uint32_t), 256);
+    kp.off_cnt = off;    off = align_up(off + b * sizeof(uint32_t), 256);
+    kp.off_thr2 = off;   off = align_up(off + b * sizeof(uint32_t), 256);
+    kp.off_flag = off;   off = align_up(off + sizeof(uint32_t), 256);
+    kp.off_levels = off; off = align_up(off + b * (static_cast<size_t>(extra) + 2) * sizeof(uint32_t), 256);
+    kp.off_q = off;
+    if (whole.wc) off = align_up(off + b * whole.nchunks * q_bits * whole.wc * sizeof(uint32_t), 256);
+    kp.off_parts = off;  off = align_up(off + b * kp.parts * k * sizeof(uint64_t), 256);
+    kp.off_list = off;   off = align_up(off + b * static_cast<size_t>(kp.cap) * sizeof(uint64_t), 256);
+    kp.total = off;
+    return kp;
+}
+
+int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
+{
+    const int64_t n = job.n, m = job.m;
+    const int d = job.d, k = job.k, W = words32(d);
+    for (int64_t qb = 0; qb < m; qb += kp.batch) {
+        const int mb = static_cast<int>(m - qb < kp.batch ? m - qb : kp.batch);
+        const uint32_t* q_rows = job.q_codes + qb * (static_cast<int64_t>(job.q_bits) * W);
+        const Plan p = make_plan(n, mb, d, job.q_bits, k, false);
+        if (p.total > kp.inner) return XBQ_EWORKSPACE;    // cannot happen: make_kplan took the larger of the two
+        SearchJob plain = job;
+        plain.q_codes = q_rows;
+        plain.m = mb;
+        plain.extra = -1;
+        plain.idx = reinterpret_cast<int32_t*>(ws + kp.off_idx1);
+        plain.score = reinterpret_cast<int32_t*>(ws + kp.off_score1);
+        const int rc = run_search(plain, p, ws, s);
+        if (rc != XBQ_OK) return rc;
+
+        KSelectArgs ka{};
+        ka.db = job.db_codes;
+        ka.n = n;
+        ka.q_rows = q_rows;
+        ka.m = mb;
+        ka.k = k;
+        ka.d = d;
+        ka.W = W;
+        ka.q_bits = job.q_bits;
+        ka.db_bits = job.db_bits;
+        ka.extra = job.extra;
+        ka.cap = kp.cap;
+        ka.idx1 = plain.idx;
+        ka.score1 = plain.score;
+        ka.dk = reinterpret_cast<uint32_t*>(ws + kp.off_dk);
+        ka.thr = reinterpret_cast<uint32_t*>(ws + kp.off_thr);
+        ka.cnt = reinterpret_cast<uint32_t*>(ws + kp.off_cnt);
+        ka.list = reinterpret_cast<uint64_t*>(ws + kp.off_list);
+        ka.X_db = job.X_db;
+        ka.X_q = job.X_q + qb * d;
+        ka.parts = kp.parts;
+        ka.part_keys = reinterpret_cast<uint64_t*>(ws + kp.off_parts);
+        ka.idx = job.idx + qb * k;
+        ka.sim = job.similarity + qb * k;
+        ka.count = job.candidates ? job.candidates + qb : nullptr;
+        ka.levels = reinterpret_cast<uint32_t*>(ws + kp.off_levels);
+        ka.thr2 = reinterpret_cast<uint32_t*>(ws + kp.off_thr2);
+        ka.flag = reinterpret_cast<uint32_t*>(ws + kp.off_flag);
+        hipError_t e = launch_kselect_bound(ka, s);
+        if (e != hipSuccess) return fail_hip(e);
+        e = launch_clear(ka.levels, static_cast<int64_t>(mb) * (job.extra + 2), s);
+        if (e != hipSuccess) return fail_hip(e);
+
+        ScanArgs sa{};
+        sa.db = job.db_codes;
+        sa.n = n;
+        sa.m = mb;
+        sa.q_bits = job.q_bits;
+        sa.db_bits = job.db_bits;
+        sa.W = W;
+        sa.wc = p.wc;
+        sa.nchunks = p.nchunks;
+        sa.thr = ka.thr;
+        sa.cnt = ka.cnt;
+        sa.cand = ka.list;
+        sa.cap = kp.cap;
+        if (p.wc) {
+            uint32_t* qc = reinterpret_cast<uint32_t*>(ws + kp.off_q);
+            e = launch_repack_queries(q_rows, mb, job.q_bits, W, p.wc, p.nchunks, qc, s);
+            if (e != hipSuccess) return fail_hip(e);
+            sa.q = qc;
+        } else {
+            sa.q = q_rows;
+        }
+        sa.row_begin = 0;
+        sa.row_end = n;
+        const int64_t bundles = (n + kLanes - 1) / kLanes;
+        const int rpl_max = (p.wc == 0 && job.db_bits * W <= 16) ? 2 : 1;
+        sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
+        sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, p.wc ? kTileQ : 1);
+        sa.levels = ka.levels;
+        sa.level_base = ka.dk;
+        sa.level_stride = job.extra + 2;
+        e = traced_scan(sa, false, s);
+        if (e != hipSuccess) return fail_hip(e);
+        e = launch_kselect_levels(ka, s);
+        if (e != hipSuccess) return fail_hip(e);
+        sa.thr = ka.thr2;                                 // second collection: lowered bounds only
+        sa.levels = nullptr;
+        sa.run_flag = ka.flag;
+        e = traced_scan(sa, false, s);
+        if (e != hipSuccess) return fail_hip(e);
+        e = launch_kselect_refine(ka, s);
+        if (e != hipSuccess) return fail_hip(e);
+    }
+    return XBQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -589,6 +733,44 @@ int xbq_search_refine(const float* X_db, const uint32_t* db_codes, int64_t n, in
     job.d = d; job.k = k; job.extra = extra_distance;
     job.idx = idx; job.X_db = X_db; job.X_q = X_q; job.similarity = similarity; job.candidates = candidates;
     return run_search(job, p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+size_t xbq_k_select_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int k, int extra_distance,
+                                    int64_t max_candidates)
+{
+    if (!valid_search_sizes(n, m, d, q_bits, k)) return 0;
+    if (extra_distance < 0 || extra_distance > XBQ_MAX_EXTRA) return 0;
+    if (max_candidates < k || max_candidates > XBQ_MAX_CANDIDATES) return 0;
+    if (n == 0 || m == 0) return 256;
+    return make_kplan(n, m, d, q_bits, k, max_candidates, extra_distance).total;
+}
+
+int xbq_k_select(const float* X_db, const uint32_t* db_codes, int64_t n, int db_bits, const float* X_q,
+                 const uint32_t* q_codes, int64_t m, int q_bits, int d, int k, int extra_distance,
+                 int64_t max_candidates, int32_t* idx, float* similarity, int32_t* candidates, void* workspace,
+                 size_t workspace_bytes, void* stream)
+{
+    if (d < 1 || db_bits < 1 || q_bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
+    if (!valid_shape(d, db_bits) || !valid_shape(d, q_bits) || !scan_supports_bits(q_bits, db_bits))
+        return XBQ_EUNSUPPORTED;
+    if (!valid_search_sizes(n, m, d, q_bits, k)) return XBQ_EINVAL;
+    if (extra_distance < 0 || extra_distance > XBQ_MAX_EXTRA) return XBQ_EINVAL;
+    if (max_candidates < k || max_candidates > XBQ_MAX_CANDIDATES) return XBQ_EINVAL;
+    if (n == 0 || m == 0) return XBQ_OK;
+    if (!X_db || !X_q || !db_codes || !q_codes || !idx || !similarity || !workspace) return XBQ_EINVAL;
+    if (reinterpret_cast<uintptr_t>(db_codes) % 4 || reinterpret_cast<uintptr_t>(q_codes) % 4 ||
+        reinterpret_cast<uintptr_t>(X_db) % 4 || reinterpret_cast<uintptr_t>(X_q) % 4 ||
+        reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(similarity) % 4 ||
+        reinterpret_cast<uintptr_t>(candidates) % 4 || reinterpret_cast<uintptr_t>(workspace) % 256)
+        return XBQ_EINVAL;
+    const KPlan kp = make_kplan(n, m, d, q_bits, k, max_candidates, extra_distance);
+    if (workspace_bytes < kp.total) return XBQ_EWORKSPACE;
+    SearchJob job{};
+    job.db_codes = db_codes; job.n = n; job.db_bits = db_bits;
+    job.q_codes = q_codes; job.m = m; job.q_bits = q_bits;
+    job.d = d; job.k = k; job.extra = extra_distance;
+    job.idx = idx; job.X_db = X_db; job.X_q = X_q; job.similarity = similarity; job.candidates = candidates;
+    return run_k_select(job, kp, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 int xbq_trace_enable(int on)

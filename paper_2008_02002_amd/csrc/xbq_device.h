@@ -78,6 +78,14 @@ __device__ __forceinline__ void append_keys(bool pass, uint32_t D, uint32_t row,
     if (pass && pos < cap) list[pos] = make_key(D, row);
 }
 
+// Optional bookkeeping of the threshold mode: one count per passing row in its distance level.
+__device__ __forceinline__ void count_level(bool pass, uint32_t D, int q, const ScanArgs& a)
+{
+    if (!pass) return;
+    const uint32_t base = a.level_base[q];
+    atomicAdd(&a.levels[static_cast<size_t>(q) * a.level_stride + (D < base ? 0u : D - base + 1u)], 1u);
+}
+
 // Workgroup -> (row block, query range) of the scan kernels.  The grid is one-dimensional.
 // Hardware hands consecutive workgroup ids to the 8 XCDs in turn, each XCD with its own L2,
 // so the id is split as (id % 8, id / 8): XCD c works through row blocks c, c + 8, c + 16, ...
@@ -111,6 +119,36 @@ __device__ inline void bitonic_sort_lds(uint64_t* keys, int P)
             __syncthreads();
         }
     }
+}
+
+// Eq. 6 for one (row, query) with run-time sizes; the slow path of the exact rescans.
+__device__ inline uint32_t distance_generic(const uint32_t* db, int64_t row, const uint32_t* yq, int BQ, int BD, int W)
+{
+    const uint32_t* xb = db + (row / kLanes) * (static_cast<int64_t>(BD) * W * kLanes) + (row % kLanes);
+    uint32_t D = 0;
+    for (int w = 0; w < W; ++w) {
+        uint32_t x[XBQ_MAX_BITS], y[XBQ_MAX_BITS];
+        for (int b = 0; b < BD; ++b) x[b] = xb[(b * W + w) * kLanes];
+        for (int b = 0; b < BQ; ++b) y[b] = yq[b * W + w];
+        for (int i = 0; i < BD; ++i)
+            for (int j = 0; j < BQ; ++j) D += static_cast<uint32_t>(__builtin_popcount(x[i] ^ y[j])) << (i + j);
+    }
+    return D;
+}
+
+// fp32 similarity as the upper half of a 64-bit sort key: ascending keys = descending floats.
+__device__ __forceinline__ uint32_t descending_bits(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);     // ascending order of floats as unsigned
+    return ~u;                                           // reversed: larger float = smaller key
+}
+
+__device__ __forceinline__ float bits_to_float_descending(uint32_t k)
+{
+    uint32_t u = ~k;
+    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+    return __uint_as_float(u);
 }
 
 }  // namespace xbq

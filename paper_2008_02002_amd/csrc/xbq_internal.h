@@ -50,6 +50,14 @@ struct ScanArgs {
     // dense mode: every D is stored
     uint32_t* dense;         // [m][dense_stride], column = row - row_begin
     int dense_stride;
+    // threshold mode, optional (nullptr = off): count the passing rows of query q by distance
+    // level: levels[q][0] for D < level_base[q], levels[q][D - level_base[q] + 1] otherwise.
+    // The caller guarantees thr[q] - level_base[q] < level_stride.
+    uint32_t* levels;        // [m][level_stride]
+    const uint32_t* level_base;   // [m]
+    int level_stride;
+    // optional (nullptr = off): the launch does nothing when *run_flag == 0
+    const uint32_t* run_flag;
 };
 
 // True if codes of W words per plane are served by the register-resident scan.
@@ -179,6 +187,36 @@ struct CollectArgs {
 hipError_t launch_clear(uint32_t* p, int64_t count, hipStream_t s);
 hipError_t launch_scan_hist(const HistArgs& a, hipStream_t s);
 hipError_t launch_hist_collect(const CollectArgs& a, hipStream_t s);
+
+// Algorithm 1 with the whole candidate list (xbq_kselect.hip), one batch of queries.
+struct KSelectArgs {
+    const uint32_t* db;      // XBQ_BUNDLE64 codes
+    int64_t n;
+    const uint32_t* q_rows;  // XBQ_ROWS codes of this batch
+    int m, k, d, W;
+    int q_bits, db_bits;
+    int extra;               // 0 .. XBQ_MAX_EXTRA
+    int cap;                 // candidate slots per query (>= k)
+    const int32_t* idx1;     // [m][k] exact top-K of the plain search
+    const int32_t* score1;   // [m][k]
+    uint32_t* dk;            // [m] K-th smallest distance
+    uint32_t* thr;           // [m] threshold of the collecting scan
+    uint32_t* cnt;           // [m] rows within the bound (may exceed cap until kselect_levels ran)
+    uint64_t* list;          // [m][cap] candidate keys, any order
+    uint32_t* levels;        // [m][extra + 2] rows per distance level, counted by the collecting scan
+    uint32_t* thr2;          // [m] threshold of the second collecting scan (0: query is done)
+    uint32_t* flag;          // [1] set when some query needs the second collecting scan
+    const float* X_db;       // [n][d]
+    const float* X_q;        // [m][d] (this batch)
+    int parts;               // workgroups per query in refine_wide; parts * k <= kSortCap
+    uint64_t* part_keys;     // [m][parts][k]
+    int32_t* idx;            // [m][k]
+    float* sim;              // [m][k]
+    int32_t* count;          // [m] or nullptr
+};
+hipError_t launch_kselect_bound(const KSelectArgs& a, hipStream_t s);
+hipError_t launch_kselect_levels(const KSelectArgs& a, hipStream_t s);
+hipError_t launch_kselect_refine(const KSelectArgs& a, hipStream_t s);
 
 // xbq_probe.hip: sustained-rate probes (measurement aids)
 size_t probe_out_bytes();

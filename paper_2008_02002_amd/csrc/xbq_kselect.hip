@@ -1,0 +1,199 @@
+// Algorithm 1 (K-Select, Section 4) with its candidate list taken whole: every row whose
+// distance is within (K-th smallest distance) + extra distance is refined with the exact fp32
+// inner product, however many rows that is, up to a bound the caller chooses to size the
+// workspace.
+//
+// The exact top-K search has already run and gives each query its K-th smallest distance D_K.
+// Then:
+//   kselect_bound     threshold of the query = D_K + extra + 1, candidate count = 0
+//   (scan kernels)    one pass over all rows in threshold mode appends every row below it and
+//                     counts the passing rows per distance level
+//   kselect_levels    only for a query whose rows within the bound exceed the list: the level
+//                     counts give the largest distance whose rows still fit (whole distance
+//                     levels, never below D_K); if the ties at D_K alone do not fit, the list
+//                     is the K best rows by (distance, row)
+//   (scan kernels)    a second collecting pass for the queries whose bound was lowered; it
+//                     returns at once when there is none
+//   refine_wide       similarities of the candidates in pieces of 2048, a running top-K in LDS;
+//                     a query's list may be split over several workgroups
+//   refine_merge      merges the pieces' top-K and writes rows, similarities and |L|
+
+#include "xbq_device.h"
+
+namespace xbq {
+
+constexpr int kLevelBins = XBQ_MAX_EXTRA + 2;            // below D_K, then D_K .. D_K + extra
+constexpr int kRefinePiece = 2048;                       // candidates per sort: K + piece <= kSortCap
+
+__global__ __launch_bounds__(kBlock) void kselect_bound(const KSelectArgs a)
+{
+    const int q = blockIdx.x * kBlock + threadIdx.x;
+    if (q == 0) a.flag[0] = 0;
+    if (q >= a.m) return;
+    const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
+    const uint32_t dk = static_cast<uint32_t>((full - a.score1[static_cast<size_t>(q) * a.k + a.k - 1]) / 2);
+    a.dk[q] = dk;
+    a.thr[q] = dk + static_cast<uint32_t>(a.extra) + 1u;
+    a.cnt[q] = 0;
+}
+
+// One workgroup per query.  A query whose rows within the bound fit its list is done
+// (thr2 = 0).  Otherwise the level counts of the collecting scan give the largest distance
+// whose rows still fit (whole levels, never below D_K): the list is emptied and the query
+// takes part in a second collecting scan with that distance as its bound.  If the ties at D_K
+// alone do not fit, the list becomes the K best rows by (distance, row).
+__global__ __launch_bounds__(kBlock) void kselect_levels(const KSelectArgs a)
+{
+    __shared__ uint32_t hist[kLevelBins];
+    __shared__ uint32_t s_level;
+    const int q = blockIdx.x;
+    if (a.cnt[q] <= static_cast<uint32_t>(a.cap)) {              // same value in every lane
+        if (threadIdx.x == 0) a.thr2[q] = 0;
+        return;
+    }
+    const int bins = a.extra + 2;
+    const uint32_t* lv = a.levels + static_cast<size_t>(q) * bins;
+    for (int t = threadIdx.x; t < bins; t += kBlock) hist[t] = lv[t];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        // level j (j >= 1) = all rows with D <= D_K + j - 1; the largest one that fits
+        uint32_t cum = hist[0], level = 0;
+        for (int j = 1; j < bins; ++j) {
+            cum += hist[j];
+            if (cum > static_cast<uint32_t>(a.cap)) break;
+            level = static_cast<uint32_t>(j);
+        }
+        s_level = level;
+    }
+    __syncthreads();
+    if (s_level == 0) {                                  // the ties at D_K alone do not fit
+        uint64_t* list = a.list + static_cast<size_t>(q) * a.cap;
+        const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
+        for (int t = threadIdx.x; t < a.k; t += kBlock) {
+            const size_t at = static_cast<size_t>(q) * a.k + t;
+            list[t] = make_key(static_cast<uint32_t>((full - a.score1[at]) / 2), static_cast<uint32_t>(a.idx1[at]));
+        }
+        if (threadIdx.x == 0) {
+            a.cnt[q] = static_cast<uint32_t>(a.k);
+            a.thr2[q] = 0;
+        }
+        return;
+    }
+    if (threadIdx.x == 0) {
+        a.cnt[q] = 0;
+        a.thr2[q] = a.dk[q] + s_level;                   // D < D_K + level  <=>  D <= D_K + level - 1
+        a.flag[0] = 1;
+    }
+}
+
+// grid = m * parts.  Piece `part` of query q's list: running top-K of (similarity descending,
+// row ascending) keys, written sorted to part_keys[q][part][0 .. k), padded with kPadKey.
+__global__ __launch_bounds__(kBlock) void refine_wide(const KSelectArgs a)
+{
+    extern __shared__ uint64_t lds64[];
+    uint64_t* keys = lds64;                              // kSortCap keys
+    float* qv = reinterpret_cast<float*>(lds64 + kSortCap);   // d floats
+    const int q = blockIdx.x / a.parts, part = blockIdx.x - q * a.parts;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t c = a.cnt[q];
+    const int have = c < static_cast<uint32_t>(a.cap) ? static_cast<int>(c) : a.cap;
+    const int per = (have + a.parts - 1) / a.parts;
+    const int begin = part * per < have ? part * per : have;
+    const int end = begin + per < have ? begin + per : have;
+    const float* xq = a.X_q + static_cast<size_t>(q) * a.d;
+    for (int t = threadIdx.x; t < a.d; t += kBlock) qv[t] = xq[t];
+    __syncthreads();
+    const uint64_t* list = a.list + static_cast<size_t>(q) * a.cap;
+    int held = 0;
+    constexpr int U = 4;                                 // candidates in flight per wavefront
+    for (int base = begin; base < end; base += kRefinePiece) {
+        const int nc = end - base < kRefinePiece ? end - base : kRefinePiece;
+        for (int t0 = wave * U; t0 < nc; t0 += (kBlock / kLanes) * U) {
+            uint32_t row[U];
+            float s[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int t = t0 + u < nc ? t0 + u : nc - 1;             // the tail repeats the last candidate
+                row[u] = static_cast<uint32_t>(list[base + t] & 0xffffffffu);
+                s[u] = 0.0f;
+            }
+            for (int col = lane; col < a.d; col += kLanes) {
+                float xv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) xv[u] = a.X_db[static_cast<size_t>(row[u]) * a.d + col];
+                const float qc = qv[col];
+#pragma unroll
+                for (int u = 0; u < U; ++u) s[u] = fmaf(xv[u], qc, s[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) s[u] += __shfl_xor(s[u], off);
+                if (lane == 0 && t0 + u < nc)
+                    keys[held + t0 + u] = (static_cast<uint64_t>(descending_bits(s[u])) << 32) | row[u];
+            }
+        }
+        const int total = held + nc;
+        const int P = next_pow2(total);
+        for (int t = total + threadIdx.x; t < P; t += kBlock) keys[t] = kPadKey;
+        __syncthreads();
+        bitonic_sort_lds(keys, P);
+        held = total < a.k ? total : a.k;
+    }
+    uint64_t* out = a.part_keys + (static_cast<size_t>(q) * a.parts + part) * a.k;
+    for (int t = threadIdx.x; t < a.k; t += kBlock) out[t] = t < held ? keys[t] : kPadKey;
+}
+
+__global__ __launch_bounds__(kBlock) void refine_merge(const KSelectArgs a)
+{
+    __shared__ uint64_t keys[kSortCap];
+    const int q = blockIdx.x;
+    const int total = a.parts * a.k;
+    const int P = next_pow2(total);
+    const uint64_t* in = a.part_keys + static_cast<size_t>(q) * total;
+    for (int t = threadIdx.x; t < P; t += kBlock) keys[t] = t < total ? in[t] : kPadKey;
+    __syncthreads();
+    if (a.parts > 1) bitonic_sort_lds(keys, P);
+    for (int t = threadIdx.x; t < a.k; t += kBlock) {
+        const uint64_t key = keys[t];
+        a.idx[static_cast<size_t>(q) * a.k + t] = static_cast<int32_t>(key & 0xffffffffu);
+        a.sim[static_cast<size_t>(q) * a.k + t] = bits_to_float_descending(static_cast<uint32_t>(key >> 32));
+    }
+    if (a.count != nullptr && threadIdx.x == 0) {
+        const uint32_t c = a.cnt[q];
+        a.count[q] = static_cast<int32_t>(c < static_cast<uint32_t>(a.cap) ? c : static_cast<uint32_t>(a.cap));
+    }
+}
+
+static bool kselect_args_ok(const KSelectArgs& a)
+{
+    return a.m >= 1 && a.k >= 1 && a.k <= XBQ_MAX_K && a.cap >= a.k && a.extra >= 0 && a.extra <= XBQ_MAX_EXTRA &&
+           a.parts >= 1 && static_cast<int64_t>(a.parts) * a.k <= kSortCap && a.k + kRefinePiece <= kSortCap;
+}
+
+hipError_t launch_kselect_bound(const KSelectArgs& a, hipStream_t s)
+{
+    if (!kselect_args_ok(a)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kselect_bound, dim3((a.m + kBlock - 1) / kBlock), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_kselect_levels(const KSelectArgs& a, hipStream_t s)
+{
+    if (!kselect_args_ok(a)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kselect_levels, dim3(a.m), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_kselect_refine(const KSelectArgs& a, hipStream_t s)
+{
+    if (!kselect_args_ok(a)) return hipErrorInvalidValue;
+    const size_t lds = kSortCap * sizeof(uint64_t) + static_cast<size_t>(a.d) * sizeof(float);
+    hipLaunchKernelGGL(refine_wide, dim3(static_cast<unsigned>(a.m) * a.parts), dim3(kBlock), lds, s, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(refine_merge, dim3(a.m), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace xbq

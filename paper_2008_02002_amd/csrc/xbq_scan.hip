@@ -31,6 +31,7 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
     const int wave = threadIdx.x >> 6;
     int row_block, qrange;
     if (!decode_tile(a.row_blocks, a.qranges, row_block, qrange)) return;
+    if (!DENSE && a.run_flag != nullptr && ((uniform_ptr)a.run_flag)[0] == 0) return;
     const int64_t bundle0 = a.row_begin / kLanes + (static_cast<int64_t>(row_block) * 4 + wave) * R;
     if (bundle0 * kLanes >= a.row_end) return;
     const int64_t last_bundle = (a.n - 1) / kLanes;
@@ -75,9 +76,12 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
             for (int r = 0; r < R; ++r) any |= D[r] < t;
             if (__builtin_expect(__ballot(any) != 0, 0)) {
 #pragma unroll
-                for (int r = 0; r < R; ++r)
-                    append_keys(D[r] < t && row[r] < a.row_end, D[r], row[r], &a.cnt[q], a.cand + static_cast<size_t>(q) * a.cap,
+                for (int r = 0; r < R; ++r) {
+                    const bool pass = D[r] < t && row[r] < a.row_end;
+                    append_keys(pass, D[r], row[r], &a.cnt[q], a.cand + static_cast<size_t>(q) * a.cap,
                                 static_cast<uint32_t>(a.cap));
+                    if (a.levels != nullptr) count_level(pass, D[r], q, a);
+                }
             }
         }
     }
@@ -96,6 +100,7 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
     const int wave = threadIdx.x >> 6;
     int row_block, qrange;
     if (!decode_tile(a.row_blocks, a.qranges, row_block, qrange)) return;
+    if (!DENSE && a.run_flag != nullptr && ((uniform_ptr)a.run_flag)[0] == 0) return;
     const int64_t bundle = a.row_begin / kLanes + static_cast<int64_t>(row_block) * 4 + wave;
     if (bundle * kLanes >= a.row_end) return;
     const int W = a.W;
@@ -140,6 +145,7 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
                     const uint32_t thr = ((uniform_ptr)a.thr)[q];
                     append_keys(acc[t] < thr && valid, acc[t], row, &a.cnt[q], a.cand + static_cast<size_t>(q) * a.cap,
                                 static_cast<uint32_t>(a.cap));
+                    if (a.levels != nullptr) count_level(acc[t] < thr && valid, acc[t], q, a);
                 }
             }
         }

@@ -75,21 +75,6 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
     write_topk(a, q, keys, a.rows, &scratch);
 }
 
-// Eq. 6 for one (row, query) with run-time sizes; slow path used only by the rescan.
-__device__ uint32_t distance_generic(const uint32_t* db, int64_t row, const uint32_t* yq, int BQ, int BD, int W)
-{
-    const uint32_t* xb = db + (row / kLanes) * (static_cast<int64_t>(BD) * W * kLanes) + (row % kLanes);
-    uint32_t D = 0;
-    for (int w = 0; w < W; ++w) {
-        uint32_t x[XBQ_MAX_BITS], y[XBQ_MAX_BITS];
-        for (int b = 0; b < BD; ++b) x[b] = xb[(b * W + w) * kLanes];
-        for (int b = 0; b < BQ; ++b) y[b] = yq[b * W + w];
-        for (int i = 0; i < BD; ++i)
-            for (int j = 0; j < BQ; ++j) D += static_cast<uint32_t>(__builtin_popcount(x[i] ^ y[j])) << (i + j);
-    }
-    return D;
-}
-
 // Exact re-score of rows [row_begin, row_end) for one query, starting from its current
 // top-K.  keys[] holds the best K so far plus survivors; it is compacted (sorted, cut to K,
 // threshold tightened) whenever another full workgroup of survivors might not fit.
@@ -177,20 +162,6 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r)
 // with coalesced loads and reduces the products across its lanes; the similarities are then
 // sorted (descending, ties to the lower row) as 64-bit keys.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t descending_bits(float v)
-{
-    uint32_t u = __float_as_uint(v);
-    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);     // ascending order of floats as unsigned
-    return ~u;                                           // reversed: larger float = smaller key
-}
-
-__device__ __forceinline__ float bits_to_float_descending(uint32_t k)
-{
-    uint32_t u = ~k;
-    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
-    return __uint_as_float(u);
-}
-
 __global__ __launch_bounds__(kBlock) void refine_topk(const RefineArgs a)
 {
     extern __shared__ uint64_t lds64[];

@@ -19,7 +19,7 @@ REFINE_MAX_CANDIDATES = 2048
 
 EXPORTS = (
     "xbq_version", "xbq_strerror", "xbq_last_hip_error", "xbq_code_bytes", "xbq_encode",
-    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_trace_enable", "xbq_trace_read",
+    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_k_select_workspace_bytes", "xbq_k_select", "xbq_trace_enable", "xbq_trace_read",
     "xbq_probe_out_bytes", "xbq_probe_valu", "xbq_probe_read", "xbq_set_option",
 )
 
@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.xbq_search_refine_workspace_bytes.restype = sz
         L.xbq_search_refine.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
         L.xbq_search_refine.restype = i32
+        L.xbq_k_select_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32, i64]
+        L.xbq_k_select_workspace_bytes.restype = sz
+        L.xbq_k_select.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, i32, i32, i32, i64, vp, vp, vp, vp, sz, vp]
+        L.xbq_k_select.restype = i32
         L.xbq_trace_enable.argtypes = [i32]
         L.xbq_trace_enable.restype = i32
         L.xbq_trace_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64),
@@ -195,6 +199,35 @@ def xbq_search_refine(X_db, db_codes, db_bits: int, X_q, q_codes, q_bits: int, k
                                  int(extra_distance), p(idx), p(sim), p(cand), p(workspace),
                                  workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "xbq_search_refine")
+    return idx, sim, cand
+
+
+def xbq_k_select(X_db, db_codes, db_bits: int, X_q, q_codes, q_bits: int, k: int, extra_distance: int,
+                 max_candidates: int, workspace=None, idx=None, sim=None, cand=None):
+    """Algorithm 1 with the whole candidate list.  Returns (idx int32 [m, k], similarity fp32
+    [m, k], candidates int32 [m]) CUDA tensors."""
+    import torch
+    n, d = X_db.shape
+    m = X_q.shape[0]
+    for t in (X_db, X_q):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+            raise ValueError("X_db and X_q must be contiguous fp32 CUDA tensors")
+    need = lib().xbq_k_select_workspace_bytes(n, m, d, q_bits, k, int(extra_distance), int(max_candidates))
+    if need == 0:
+        raise XbqError(EINVAL, "xbq_k_select_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X_db.device)
+    if idx is None:
+        idx = torch.empty((m, k), dtype=torch.int32, device=X_db.device)
+    if sim is None:
+        sim = torch.empty((m, k), dtype=torch.float32, device=X_db.device)
+    if cand is None:
+        cand = torch.empty((m,), dtype=torch.int32, device=X_db.device)
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    rc = lib().xbq_k_select(p(X_db), p(db_codes), n, db_bits, p(X_q), p(q_codes), m, q_bits, d, k,
+                            int(extra_distance), int(max_candidates), p(idx), p(sim), p(cand), p(workspace),
+                            workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "xbq_k_select")
     return idx, sim, cand
 
 

@@ -106,21 +106,33 @@ def oracle_distances(Xdb, Xq, db_bits: int, q_bits: int, scale: float):
     return od.distance_from_score(S, d, q_bits, db_bits)
 
 
-def assert_refined_matches(got, Xdb, Xq, D, k, extra, limit, tol=2e-6):
+def gpu_k_select(Xdb, Xq, db_bits: int, q_bits: int, k: int, extra: int, max_candidates: int, scale: float):
+    import torch
+    xd, xq = to_dev(Xdb), to_dev(Xq)
+    db = xbq.xbq_encode(xd, db_bits, scale, xbq.BUNDLE64)
+    q = xbq.xbq_encode(xq, q_bits, scale, xbq.ROWS)
+    idx, sim, cand = xbq.xbq_k_select(xd, db, db_bits, xq, q, q_bits, k, extra, max_candidates)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), sim.cpu().numpy(), cand.cpu().numpy()
+
+
+def assert_refined_matches(got, Xdb, Xq, D, k, extra, limit, tol=2e-6, by_levels=False):
     """Compare with Algorithm 1 run by the oracle.  The candidate count is an integer and
     must match exactly.  Similarities are fp32 sums on the GPU and float64 in the oracle:
     they must agree within tol, and a returned row may differ from the oracle's row at the
     same rank only if their exact similarities are within tol (a tie at fp32 resolution)."""
     from oracle import definition as od
     gi, gs, gc = got
-    ridx, rsim, rcount = od.k_select(D, Xdb, Xq, k, extra, limit)
+    select = od.k_select_by_levels if by_levels else od.k_select
+    candidates = od.k_select_candidates_by_levels if by_levels else od.k_select_candidates
+    ridx, rsim, rcount = select(D, Xdb, Xq, k, extra, limit)
     assert np.array_equal(gc, rcount), "candidate counts differ"
     X64 = Xdb.astype(np.float64)
     for q in range(Xq.shape[0]):
         exact = X64[gi[q]] @ Xq[q].astype(np.float64)
         assert np.abs(exact - gs[q]).max() <= tol, "similarity is not the inner product of the returned row"
         assert len(set(gi[q].tolist())) == k
-        L = set(od.k_select_candidates(D[q], k, extra, limit).tolist())
+        L = set(candidates(D[q], k, extra, limit).tolist())
         assert set(gi[q].tolist()) <= L, "a returned row is not a candidate"
         diff = gi[q] != ridx[q]
         assert (np.abs(exact[diff] - rsim[q][diff]) <= tol).all(), "rank differs beyond fp32 resolution"

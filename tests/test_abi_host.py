@@ -135,6 +135,41 @@ def test_search_refine_argument_errors(L):
     assert L.xbq_search_refine_workspace_bytes(1000, 10, 128, 4, 0) == 0
 
 
+def test_k_select_argument_errors(L):
+    fake = ctypes.c_void_p(0x1000)
+    null = ctypes.c_void_p(0)
+
+    def s(xdb=fake, xq=fake, n=1000, m=10, d=128, k=10, extra=5, cap=500, db_bits=3, q_bits=4, sim=fake, wsb=1 << 40):
+        return L.xbq_k_select(xdb, fake, n, db_bits, xq, fake, m, q_bits, d, k, extra, cap, fake, sim, null,
+                              fake, wsb, null)
+
+    assert s(xdb=null) == xbq.EINVAL
+    assert s(sim=null) == xbq.EINVAL
+    assert s(extra=-1) == xbq.EINVAL
+    assert s(extra=4096) == xbq.EINVAL
+    assert s(cap=9) == xbq.EINVAL                       # fewer candidates than k
+    assert s(cap=(1 << 22) + 1) == xbq.EINVAL
+    assert s(k=0) == xbq.EINVAL
+    assert s(k=1001) == xbq.EINVAL
+    assert s(db_bits=4, q_bits=3) == xbq.EUNSUPPORTED
+    f0 = L.xbq_k_select_workspace_bytes
+    f = lambda n, m, d, b, k, cap, extra=5: f0(n, m, d, b, k, extra, cap)
+    need = f(1000, 10, 128, 4, 10, 500)
+    assert need > L.xbq_search_workspace_bytes(1000, 10, 128, 4, 10) + 10 * 500 * 8
+    assert s(wsb=need - 1) == xbq.EWORKSPACE
+    assert s(m=0) == xbq.OK and s(n=0, k=1, cap=1) == xbq.OK
+    assert f(1000, 10, 128, 4, 10, 9) == 0 and f(1000, 10, 128, 4, 0, 500) == 0
+    assert f(1000, 10, 128, 4, 10, 500, extra=-1) == 0 and f(1000, 10, 128, 4, 10, 500, extra=4096) == 0
+    assert f(1000, 10, 128, 4, 10, 500, extra=4095) > need                  # level counters
+    # the candidate lists of a batch stay near 2 GiB however many queries there are; a bound above n counts as n
+    big = f(2_000_000, 10_000, 200, 4, 10, 1 << 17)
+    assert (1 << 31) <= big < (1 << 32)
+    assert f(2_000_000, 1_000_000, 200, 4, 10, 1 << 17) == big
+    assert f(1000, 10, 128, 4, 10, 1 << 20) == f(1000, 10, 128, 4, 10, 1000)
+    # a short last batch that takes the few-query path (stored distances) is covered
+    assert f(10_000_000, 8192 + 3, 96, 4, 10, 1 << 15) >= L.xbq_search_workspace_bytes(10_000_000, 3, 96, 4, 10)
+
+
 def test_workspace_bytes(L):
     f = L.xbq_search_workspace_bytes
     assert f(1000, 10, 128, 4, 0) == 0

@@ -172,3 +172,34 @@ def test_c5_full_size_refine_hits_the_candidate_bound():
     gu.assert_refined_matches((idx[sub], sim[sub], cand[sub]), X, Xq[sub], D, k, extra, xbq.REFINE_MAX_CANDIDATES)
     real, _ = od.exact_cosine_topk(X, Xq[sub], k)
     assert od.precision_at_k(idx[sub], real) > 0.95
+
+
+def test_c4_full_size_k_select_long_lists():
+    """Algorithm 1 with the whole candidate list on the clustered workload: lists of tens of
+    thousands of rows, some cut back to whole distance levels, five batches of queries."""
+    import torch
+    from oracle import definition as od
+    w = wl.WORKLOADS["C4"]
+    k, extra, bits, limit = 10, 120, 3, 1 << 17
+    X, scale = wl.database(w), wl.workload_scale(w)
+    Xq = wl.queries(w)
+    xd, xq = torch.from_numpy(X).cuda(), torch.from_numpy(Xq).cuda()
+    db = xbq.xbq_encode(xd, bits, scale, xbq.BUNDLE64)
+    q = xbq.xbq_encode(xq, bits, scale, xbq.ROWS)
+    idx, sim, cand = xbq.xbq_k_select(xd, db, bits, xq, q, bits, k, extra, limit)
+    torch.cuda.synchronize()
+    idx, sim, cand = idx.cpu().numpy(), sim.cpu().numpy(), cand.cpu().numpy()
+    del xd, db
+    _say(f"C4 k_select: searched on the GPU, lists of {cand.min()} .. {cand.max()} rows")
+    assert cand.max() > 100_000 and cand.max() <= limit
+    # the queries with the longest lists (cut or nearly so), the shortest, and both ends of the batch order
+    order = np.argsort(cand)
+    sub = np.unique(np.concatenate([order[:3], order[-5:], np.arange(3), w.m - 1 - np.arange(3), [2047, 2048]]))
+    S = oc.scores(oc.encode(X, bits, scale), oc.encode(Xq[sub], bits, scale), w.d)
+    D = od.distance_from_score(S, w.d, bits, bits)
+    del S
+    _say("C4 k_select: oracle distances done")
+    gu.assert_refined_matches((idx[sub], sim[sub], cand[sub]), X, Xq[sub], D, k, extra, limit, by_levels=True)
+    printed = np.array([(D[i] <= np.sort(D[i])[k - 1] + extra).sum() for i in range(len(sub))])
+    _say(f"C4 k_select: rows within the printed boundary {printed.tolist()}, lists {cand[sub].tolist()}")
+    assert (printed > limit).any(), "no sampled query had its list cut"

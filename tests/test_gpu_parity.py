@@ -237,6 +237,66 @@ def test_refine_on_clustered_rows_and_sorted_rows():
     gu.assert_refined_matches(got, Xs, Xq[:4], D, 10, 50, xbq.REFINE_MAX_CANDIDATES)
 
 
+KSELECT = [
+    # n, d, m, q_bits, db_bits, k, extra, max_candidates
+    (6000, 128, 20, 4, 4, 10, 0, 6000),            # nothing cut: Algorithm 1 as printed
+    (6000, 128, 20, 4, 3, 10, 60, 6000),
+    (30000, 96, 40, 4, 4, 100, 200, 30000),        # lists of several thousand rows, several refine pieces
+    (20000, 200, 30, 4, 3, 10, 64, 20000),
+    (4000, 960, 12, 4, 3, 10, 300, 4000),          # long codes: the chunked scan collects
+    (3000, 64, 10, 3, 3, 1024, 10, 3000),
+    (3000, 128, 1100, 4, 4, 10, 30, 3000),         # many queries: one refine workgroup per query
+    (9000, 128, 3, 4, 4, 5, 4095, 9000),           # largest extra distance: every row is a candidate
+    (900, 33, 1, 2, 2, 900, 0, 900),               # k = n
+    (20000, 128, 24, 4, 4, 10, 120, 700),          # lists cut back to whole distance levels
+    (20000, 128, 24, 4, 3, 100, 120, 130),
+    (20000, 96, 24, 3, 3, 10, 50, 10),             # max_candidates = k
+    (5000, 16, 9, 1, 1, 20, 3, 40),                # one-bit codes: few levels, massive ties
+]
+
+
+@pytest.mark.parametrize("n,d,m,qb,db,k,extra,limit", KSELECT)
+def test_k_select_matches_algorithm_1_with_whole_levels(n, d, m, qb, db, k, extra, limit):
+    _say(f"k_select n={n} d={d} m={m} {qb}x{db} k={k} extra={extra} max_candidates={limit}")
+    rng = np.random.default_rng(n + d + extra + limit)
+    Xdb = rng.standard_normal((n, d)).astype(np.float32)
+    Xdb /= np.linalg.norm(Xdb, axis=1, keepdims=True)
+    Xq = rng.standard_normal((m, d)).astype(np.float32)
+    Xq /= np.linalg.norm(Xq, axis=1, keepdims=True)
+    scale = wl.choose_scale(Xdb)
+    got = gu.gpu_k_select(Xdb, Xq, db, qb, k, extra, limit, scale)
+    sub = np.arange(m) if m <= 48 else np.concatenate([np.arange(24), m - 1 - np.arange(24)])
+    D = gu.oracle_distances(Xdb, Xq[sub], db, qb, scale)
+    gu.assert_refined_matches(tuple(x[sub] for x in got), Xdb, Xq[sub], D, k, extra, limit, by_levels=True)
+
+
+def test_k_select_ties_at_the_kth_distance_exceed_the_bound():
+    # 40 distinct rows repeated 100 times: every distance level holds a multiple of 100 rows
+    rng = np.random.default_rng(77)
+    base = rng.standard_normal((40, 64)).astype(np.float32)
+    base /= np.linalg.norm(base, axis=1, keepdims=True)
+    Xdb = np.ascontiguousarray(np.tile(base, (100, 1)))
+    Xq = base[:6] + 0.05 * rng.standard_normal((6, 64)).astype(np.float32)
+    Xq /= np.linalg.norm(Xq, axis=1, keepdims=True)
+    for k, extra, limit in ((10, 5, 50), (10, 5, 100), (150, 0, 160), (150, 40, 250), (3, 4095, 3)):
+        _say(f"k_select ties k={k} extra={extra} max_candidates={limit}")
+        got = gu.gpu_k_select(Xdb, Xq, 4, 4, k, extra, limit, 2.0)
+        D = gu.oracle_distances(Xdb, Xq, 4, 4, 2.0)
+        gu.assert_refined_matches(got, Xdb, Xq, D, k, extra, limit, by_levels=True)
+
+
+def test_k_select_in_batches_and_on_clustered_rows():
+    # a candidate bound of 40 000 rows makes batches of 6 710 queries: 7 000 queries take two
+    w = wl.scaled_down(wl.WORKLOADS["C4"], n=40_000, m=7_000)
+    Xdb, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
+    _say("k_select two batches, C4 stand-in")
+    got = gu.gpu_k_select(Xdb, Xq, 3, 4, 10, 80, 40_000, scale)
+    sub = np.concatenate([np.arange(12), 6709 + np.arange(3), 6999 - np.arange(10)])
+    D = gu.oracle_distances(Xdb, Xq[sub], 3, 4, scale)
+    gu.assert_refined_matches(tuple(x[sub] for x in got), Xdb, Xq[sub], D, 10, 80, 40_000, by_levels=True)
+    assert got[2].max() > xbq.REFINE_MAX_CANDIDATES          # lists longer than the other entry point can hold
+
+
 DOT = [
     # n, d, m, q_bits, db_bits, k   (the cross-check scan serves d <= 256)
     (5000, 128, 300, 4, 4, 10),
