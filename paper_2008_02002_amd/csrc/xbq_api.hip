@@ -508,7 +508,7 @@ KPlan make_kplan(int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_can
     }
     int parts = kp.batch >= 1024 ? 1 : static_cast<int>((1024 + kp.batch - 1) / kp.batch);
     if (parts > kSortCap / k) parts = kSortCap / k;
-    const int pieces = (kp.cap + 2047) / 2048;
+    const int pieces = (kp.cap + 1023) / 1024;
     if (parts > pieces) parts = pieces;
     kp.parts = parts < 1 ? 1 : parts;
     const size_t b = static_cast<size_t>(kp.batch);

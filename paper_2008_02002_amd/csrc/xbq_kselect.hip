@@ -14,7 +14,7 @@
 //                     is the K best rows by (distance, row)
 //   (scan kernels)    a second collecting pass for the queries whose bound was lowered; it
 //                     returns at once when there is none
-//   refine_wide       similarities of the candidates in pieces of 2048, a running top-K in LDS;
+//   refine_wide       similarities of the candidates in pieces, a running top-K in LDS;
 //                     a query's list may be split over several workgroups
 //   refine_merge      merges the pieces' top-K and writes rows, similarities and |L|
 
@@ -23,7 +23,7 @@
 namespace xbq {
 
 constexpr int kLevelBins = XBQ_MAX_EXTRA + 2;            // below D_K, then D_K .. D_K + extra
-constexpr int kRefinePiece = 2048;                       // candidates per sort: K + piece <= kSortCap
+constexpr int kRefineSort = 2048;                        // keys per sort of refine_wide: K best so far + new ones
 
 __global__ __launch_bounds__(kBlock) void kselect_bound(const KSelectArgs a)
 {
@@ -86,15 +86,65 @@ __global__ __launch_bounds__(kBlock) void kselect_levels(const KSelectArgs a)
     }
 }
 
+// Similarities of candidates list[0 .. nc) with the query in LDS, one wavefront per U candidates
+// at a time, written as sort keys to keys[0 .. nc).  VEC: rows are read 16 bytes per lane (d a
+// multiple of 4, X_db 16-byte aligned), so one load covers 256 coordinates of a row.
+template <bool VEC, int U>
+__device__ __forceinline__ void similarities(const KSelectArgs& a, const uint64_t* list, int nc, const float* qv,
+                                             uint64_t* keys)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int t0 = wave * U; t0 < nc; t0 += (kBlock / kLanes) * U) {
+        uint32_t row[U];
+        float s[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int t = t0 + u < nc ? t0 + u : nc - 1;                 // the tail repeats the last candidate
+            row[u] = static_cast<uint32_t>(list[t] & 0xffffffffu);
+            s[u] = 0.0f;
+        }
+        if (VEC) {
+            const int d4 = a.d >> 2;
+            const float4* q4 = reinterpret_cast<const float4*>(qv);
+            for (int col = lane; col < d4; col += kLanes) {
+                float4 xv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    xv[u] = reinterpret_cast<const float4*>(a.X_db + static_cast<size_t>(row[u]) * a.d)[col];
+                const float4 qc = q4[col];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    s[u] = fmaf(xv[u].w, qc.w, fmaf(xv[u].z, qc.z, fmaf(xv[u].y, qc.y, fmaf(xv[u].x, qc.x, s[u]))));
+            }
+        } else {
+            for (int col = lane; col < a.d; col += kLanes) {
+                float xv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) xv[u] = a.X_db[static_cast<size_t>(row[u]) * a.d + col];
+                const float qc = qv[col];
+#pragma unroll
+                for (int u = 0; u < U; ++u) s[u] = fmaf(xv[u], qc, s[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) s[u] += __shfl_xor(s[u], off);
+            if (lane == 0 && t0 + u < nc) keys[t0 + u] = (static_cast<uint64_t>(descending_bits(s[u])) << 32) | row[u];
+        }
+    }
+}
+
 // grid = m * parts.  Piece `part` of query q's list: running top-K of (similarity descending,
 // row ascending) keys, written sorted to part_keys[q][part][0 .. k), padded with kPadKey.
+// Each round sorts the K best so far together with as many new candidates as fill kRefineSort.
+template <bool VEC>
 __global__ __launch_bounds__(kBlock) void refine_wide(const KSelectArgs a)
 {
     extern __shared__ uint64_t lds64[];
-    uint64_t* keys = lds64;                              // kSortCap keys
-    float* qv = reinterpret_cast<float*>(lds64 + kSortCap);   // d floats
+    uint64_t* keys = lds64;                              // kRefineSort keys
+    float* qv = reinterpret_cast<float*>(lds64 + kRefineSort);   // d floats, 16-byte aligned
     const int q = blockIdx.x / a.parts, part = blockIdx.x - q * a.parts;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t c = a.cnt[q];
     const int have = c < static_cast<uint32_t>(a.cap) ? static_cast<int>(c) : a.cap;
     const int per = (have + a.parts - 1) / a.parts;
@@ -105,40 +155,17 @@ __global__ __launch_bounds__(kBlock) void refine_wide(const KSelectArgs a)
     __syncthreads();
     const uint64_t* list = a.list + static_cast<size_t>(q) * a.cap;
     int held = 0;
-    constexpr int U = 4;                                 // candidates in flight per wavefront
-    for (int base = begin; base < end; base += kRefinePiece) {
-        const int nc = end - base < kRefinePiece ? end - base : kRefinePiece;
-        for (int t0 = wave * U; t0 < nc; t0 += (kBlock / kLanes) * U) {
-            uint32_t row[U];
-            float s[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = t0 + u < nc ? t0 + u : nc - 1;             // the tail repeats the last candidate
-                row[u] = static_cast<uint32_t>(list[base + t] & 0xffffffffu);
-                s[u] = 0.0f;
-            }
-            for (int col = lane; col < a.d; col += kLanes) {
-                float xv[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) xv[u] = a.X_db[static_cast<size_t>(row[u]) * a.d + col];
-                const float qc = qv[col];
-#pragma unroll
-                for (int u = 0; u < U; ++u) s[u] = fmaf(xv[u], qc, s[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) s[u] += __shfl_xor(s[u], off);
-                if (lane == 0 && t0 + u < nc)
-                    keys[held + t0 + u] = (static_cast<uint64_t>(descending_bits(s[u])) << 32) | row[u];
-            }
-        }
+    for (int base = begin; base < end;) {
+        const int room = kRefineSort - held;
+        const int nc = end - base < room ? end - base : room;
+        similarities<VEC, VEC ? 8 : 4>(a, list + base, nc, qv, keys + held);
         const int total = held + nc;
         const int P = next_pow2(total);
         for (int t = total + threadIdx.x; t < P; t += kBlock) keys[t] = kPadKey;
         __syncthreads();
         bitonic_sort_lds(keys, P);
         held = total < a.k ? total : a.k;
+        base += nc;
     }
     uint64_t* out = a.part_keys + (static_cast<size_t>(q) * a.parts + part) * a.k;
     for (int t = threadIdx.x; t < a.k; t += kBlock) out[t] = t < held ? keys[t] : kPadKey;
@@ -168,7 +195,7 @@ __global__ __launch_bounds__(kBlock) void refine_merge(const KSelectArgs a)
 static bool kselect_args_ok(const KSelectArgs& a)
 {
     return a.m >= 1 && a.k >= 1 && a.k <= XBQ_MAX_K && a.cap >= a.k && a.extra >= 0 && a.extra <= XBQ_MAX_EXTRA &&
-           a.parts >= 1 && static_cast<int64_t>(a.parts) * a.k <= kSortCap && a.k + kRefinePiece <= kSortCap;
+           a.parts >= 1 && static_cast<int64_t>(a.parts) * a.k <= kSortCap && 2 * a.k <= kRefineSort;
 }
 
 hipError_t launch_kselect_bound(const KSelectArgs& a, hipStream_t s)
@@ -188,8 +215,12 @@ hipError_t launch_kselect_levels(const KSelectArgs& a, hipStream_t s)
 hipError_t launch_kselect_refine(const KSelectArgs& a, hipStream_t s)
 {
     if (!kselect_args_ok(a)) return hipErrorInvalidValue;
-    const size_t lds = kSortCap * sizeof(uint64_t) + static_cast<size_t>(a.d) * sizeof(float);
-    hipLaunchKernelGGL(refine_wide, dim3(static_cast<unsigned>(a.m) * a.parts), dim3(kBlock), lds, s, a);
+    const size_t lds = kRefineSort * sizeof(uint64_t) + static_cast<size_t>(a.d) * sizeof(float);
+    const dim3 grid(static_cast<unsigned>(a.m) * a.parts);
+    if (a.d % 4 == 0 && reinterpret_cast<uintptr_t>(a.X_db) % 16 == 0)
+        hipLaunchKernelGGL(refine_wide<true>, grid, dim3(kBlock), lds, s, a);
+    else
+        hipLaunchKernelGGL(refine_wide<false>, grid, dim3(kBlock), lds, s, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(refine_merge, dim3(a.m), dim3(kBlock), 0, s, a);
