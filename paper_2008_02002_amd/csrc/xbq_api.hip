@@ -231,6 +231,7 @@ struct SearchJob {
     const float* X_q;
     float* similarity;
     int32_t* candidates;
+    bool lists_only = false;   // refine mode: stop after the candidate lists are built
 };
 
 // Histogram selection: queries in passes of kHistMaxQueries, three launches per pass.
@@ -461,7 +462,7 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             if (e != hipSuccess) return fail_hip(e);
             seen = end;
         }
-        if (refine) {
+        if (refine && !job.lists_only) {
             RefineArgs ra{};
             ra.X_db = job.X_db;
             ra.X_q = job.X_q + qb * d;
@@ -481,16 +482,27 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
     return XBQ_OK;
 }
 
-// Algorithm 1 with the whole candidate list: the plain exact search of a batch of queries, then
-// one collecting scan over all rows with the threshold D_K + extra + 1, then the refine.
+// Algorithm 1 with the whole candidate list.  First stage of a batch of queries: the plain exact
+// search when they are few (histogram path), else the bounded candidate search, whose lists are
+// already whole for most queries.  Then up to two collecting scans over all rows for the
+// queries that need them, then the refine.
 struct KPlan {
     int64_t batch = 0;       // queries per batch: the candidate lists of a batch stay near 2 GiB
     int cap = 0, parts = 1;
-    size_t inner = 0;        // workspace of the plain search of one batch
-    size_t off_idx1 = 0, off_score1 = 0, off_dk = 0, off_thr = 0, off_cnt = 0, off_q = 0, off_parts = 0, off_list = 0;
+    size_t inner = 0;        // workspace of the first stage of one batch
+    size_t off_idx1 = 0, off_score1 = 0, off_best = 0, off_dk = 0, off_thr = 0, off_cnt = 0, off_q = 0, off_parts = 0,
+           off_list = 0;
     size_t off_thr2 = 0, off_flag = 0, off_levels = 0;
     size_t total = 0;
 };
+
+// The first stage of a batch of mb queries and its workspace.
+Plan first_stage_plan(int64_t n, int64_t mb, int d, int q_bits, int k, bool& few)
+{
+    const Plan plain = make_plan(n, mb, d, q_bits, k, false);
+    few = plain.hist;
+    return few ? plain : make_plan(n, mb, d, q_bits, k, true);
+}
 
 KPlan make_kplan(int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_candidates, int extra)
 {
@@ -500,10 +512,11 @@ KPlan make_kplan(int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_can
     if (batch < 1) batch = 1;
     if (batch > 8192) batch = 8192;
     kp.batch = m < batch ? m : batch;
-    const Plan whole = make_plan(n, kp.batch, d, q_bits, k, false);
+    bool few = false;
+    const Plan whole = first_stage_plan(n, kp.batch, d, q_bits, k, few);
     kp.inner = whole.total;
     if (m % kp.batch) {                                   // a short last batch may take the few-query path
-        const size_t t = make_plan(n, m % kp.batch, d, q_bits, k, false).total;
+        const size_t t = first_stage_plan(n, m % kp.batch, d, q_bits, k, few).total;
         if (t > kp.inner) kp.inner = t;
     }
     int parts = kp.batch >= 1024 ? 1 : static_cast<int>((1024 + kp.batch - 1) / kp.batch);
@@ -515,11 +528,12 @@ KPlan make_kplan(int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_can
     size_t off = align_up(kp.inner, 256);
     kp.off_idx1 = off;   off = align_up(off + b * k * sizeof(int32_t), 256);
     kp.off_score1 = off; off = align_up(off + b * k * sizeof(int32_t), 256);
+    kp.off_best = off;   off = align_up(off + b * k * sizeof(uint64_t), 256);
     kp.off_dk = off;     off = align_up(off + b * sizeof(uint32_t), 256);
     kp.off_thr = off;    off = align_up(off + b * sizeof(uint32_t), 256);
     kp.off_cnt = off;    off = align_up(off + b * sizeof(uint32_t), 256);
     kp.off_thr2 = off;   off = align_up(off + b * sizeof(uint32_t), 256);
-    kp.off_flag = off;   off = align_up(off + sizeof(uint32_t), 256);
+    kp.off_flag = off;   off += 256;                      // two flags; cleared together with the levels behind them
     kp.off_levels = off; off = align_up(off + b * (static_cast<size_t>(extra) + 2) * sizeof(uint32_t), 256);
     kp.off_q = off;
     if (whole.wc) off = align_up(off + b * whole.nchunks * q_bits * whole.wc * sizeof(uint32_t), 256);
@@ -536,18 +550,31 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
     for (int64_t qb = 0; qb < m; qb += kp.batch) {
         const int mb = static_cast<int>(m - qb < kp.batch ? m - qb : kp.batch);
         const uint32_t* q_rows = job.q_codes + qb * (static_cast<int64_t>(job.q_bits) * W);
-        const Plan p = make_plan(n, mb, d, job.q_bits, k, false);
+        bool few = false;
+        const Plan p = first_stage_plan(n, mb, d, job.q_bits, k, few);
         if (p.total > kp.inner) return XBQ_EWORKSPACE;    // cannot happen: make_kplan took the larger of the two
-        SearchJob plain = job;
-        plain.q_codes = q_rows;
-        plain.m = mb;
-        plain.extra = -1;
-        plain.idx = reinterpret_cast<int32_t*>(ws + kp.off_idx1);
-        plain.score = reinterpret_cast<int32_t*>(ws + kp.off_score1);
-        const int rc = run_search(plain, p, ws, s);
-        if (rc != XBQ_OK) return rc;
 
         KSelectArgs ka{};
+        SearchJob first = job;
+        first.q_codes = q_rows;
+        first.m = mb;
+        first.X_q = job.X_q + qb * d;
+        if (few) {
+            first.extra = -1;
+            first.idx = reinterpret_cast<int32_t*>(ws + kp.off_idx1);
+            first.score = reinterpret_cast<int32_t*>(ws + kp.off_score1);
+            ka.idx1 = first.idx;
+            ka.score1 = first.score;
+        } else {
+            first.lists_only = true;                      // candidate lists of at most kRefineKeep keys, no refine
+            first.idx = job.idx + qb * k;                 // not written
+            ka.topk1 = reinterpret_cast<const uint64_t*>(ws + p.off_topk);
+            ka.len1 = reinterpret_cast<const uint32_t*>(ws + p.off_len);
+            ka.keep1 = p.keep_max;
+        }
+        const int rc = run_search(first, p, ws, s);
+        if (rc != XBQ_OK) return rc;
+
         ka.db = job.db_codes;
         ka.n = n;
         ka.q_rows = q_rows;
@@ -559,8 +586,7 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
         ka.db_bits = job.db_bits;
         ka.extra = job.extra;
         ka.cap = kp.cap;
-        ka.idx1 = plain.idx;
-        ka.score1 = plain.score;
+        ka.best = reinterpret_cast<uint64_t*>(ws + kp.off_best);
         ka.dk = reinterpret_cast<uint32_t*>(ws + kp.off_dk);
         ka.thr = reinterpret_cast<uint32_t*>(ws + kp.off_thr);
         ka.cnt = reinterpret_cast<uint32_t*>(ws + kp.off_cnt);
@@ -575,9 +601,9 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
         ka.levels = reinterpret_cast<uint32_t*>(ws + kp.off_levels);
         ka.thr2 = reinterpret_cast<uint32_t*>(ws + kp.off_thr2);
         ka.flag = reinterpret_cast<uint32_t*>(ws + kp.off_flag);
-        hipError_t e = launch_kselect_bound(ka, s);
+        hipError_t e = launch_clear(ka.flag, 64 + static_cast<int64_t>(mb) * (job.extra + 2), s);    // flags + levels
         if (e != hipSuccess) return fail_hip(e);
-        e = launch_clear(ka.levels, static_cast<int64_t>(mb) * (job.extra + 2), s);
+        e = launch_kselect_first(ka, s);
         if (e != hipSuccess) return fail_hip(e);
 
         ScanArgs sa{};
@@ -610,13 +636,14 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
         sa.levels = ka.levels;
         sa.level_base = ka.dk;
         sa.level_stride = job.extra + 2;
+        sa.run_flag = ka.flag;                            // first collection: queries whose list is not whole yet
         e = traced_scan(sa, false, s);
         if (e != hipSuccess) return fail_hip(e);
         e = launch_kselect_levels(ka, s);
         if (e != hipSuccess) return fail_hip(e);
         sa.thr = ka.thr2;                                 // second collection: lowered bounds only
         sa.levels = nullptr;
-        sa.run_flag = ka.flag;
+        sa.run_flag = ka.flag + 1;
         e = traced_scan(sa, false, s);
         if (e != hipSuccess) return fail_hip(e);
         e = launch_kselect_refine(ka, s);

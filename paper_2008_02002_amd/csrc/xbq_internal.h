@@ -197,15 +197,20 @@ struct KSelectArgs {
     int q_bits, db_bits;
     int extra;               // 0 .. XBQ_MAX_EXTRA
     int cap;                 // candidate slots per query (>= k)
-    const int32_t* idx1;     // [m][k] exact top-K of the plain search
+    // first stage, one of two forms:
+    const int32_t* idx1;     // [m][k] exact top-K of the plain search (few queries), with score1
     const int32_t* score1;   // [m][k]
+    const uint64_t* topk1;   // [m][keep1] sorted candidate keys of the bounded candidate search
+    const uint32_t* len1;    // [m] keys held in topk1[q]; keep1 means the list may have been cut
+    int keep1;
+    uint64_t* best;          // [m][k] the K best keys by (D, row), written by the kselect_from_* kernels
     uint32_t* dk;            // [m] K-th smallest distance
     uint32_t* thr;           // [m] threshold of the collecting scan
     uint32_t* cnt;           // [m] rows within the bound (may exceed cap until kselect_levels ran)
     uint64_t* list;          // [m][cap] candidate keys, any order
     uint32_t* levels;        // [m][extra + 2] rows per distance level, counted by the collecting scan
     uint32_t* thr2;          // [m] threshold of the second collecting scan (0: query is done)
-    uint32_t* flag;          // [1] set when some query needs the second collecting scan
+    uint32_t* flag;          // [2] set when some query needs the first / the second collecting scan
     const float* X_db;       // [n][d]
     const float* X_q;        // [m][d] (this batch)
     int parts;               // workgroups per query in refine_wide; parts * k <= kSortCap
@@ -214,7 +219,7 @@ struct KSelectArgs {
     float* sim;              // [m][k]
     int32_t* count;          // [m] or nullptr
 };
-hipError_t launch_kselect_bound(const KSelectArgs& a, hipStream_t s);
+hipError_t launch_kselect_first(const KSelectArgs& a, hipStream_t s);
 hipError_t launch_kselect_levels(const KSelectArgs& a, hipStream_t s);
 hipError_t launch_kselect_refine(const KSelectArgs& a, hipStream_t s);
 

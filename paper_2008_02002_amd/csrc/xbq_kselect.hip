@@ -3,9 +3,13 @@
 // inner product, however many rows that is, up to a bound the caller chooses to size the
 // workspace.
 //
-// The exact top-K search has already run and gives each query its K-th smallest distance D_K.
+// A first stage has already run and gives each query its K-th smallest distance D_K: for few
+// queries the plain exact search; otherwise the bounded candidate search, which for most
+// queries already holds the whole list (then nothing below touches them again).
 // Then:
-//   kselect_bound     threshold of the query = D_K + extra + 1, candidate count = 0
+//   kselect_from_*    threshold of the query = D_K + extra + 1, candidate count = 0; or, for a
+//                     query whose bounded list is whole and fits, the list is copied and the
+//                     threshold is 0
 //   (scan kernels)    one pass over all rows in threshold mode appends every row below it and
 //                     counts the passing rows per distance level
 //   kselect_levels    only for a query whose rows within the bound exceed the list: the level
@@ -25,16 +29,45 @@ namespace xbq {
 constexpr int kLevelBins = XBQ_MAX_EXTRA + 2;            // below D_K, then D_K .. D_K + extra
 constexpr int kRefineSort = 2048;                        // keys per sort of refine_wide: K best so far + new ones
 
-__global__ __launch_bounds__(kBlock) void kselect_bound(const KSelectArgs a)
+// First stage was the plain exact search (few queries): every query is collected by the scan.
+// One workgroup per query.
+__global__ __launch_bounds__(kBlock) void kselect_from_topk(const KSelectArgs a)
 {
-    const int q = blockIdx.x * kBlock + threadIdx.x;
-    if (q == 0) a.flag[0] = 0;
-    if (q >= a.m) return;
+    const int q = blockIdx.x;
     const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
-    const uint32_t dk = static_cast<uint32_t>((full - a.score1[static_cast<size_t>(q) * a.k + a.k - 1]) / 2);
-    a.dk[q] = dk;
-    a.thr[q] = dk + static_cast<uint32_t>(a.extra) + 1u;
-    a.cnt[q] = 0;
+    for (int t = threadIdx.x; t < a.k; t += kBlock) {
+        const size_t at = static_cast<size_t>(q) * a.k + t;
+        a.best[at] = make_key(static_cast<uint32_t>((full - a.score1[at]) / 2), static_cast<uint32_t>(a.idx1[at]));
+    }
+    if (threadIdx.x == 0) {
+        const uint32_t dk = static_cast<uint32_t>((full - a.score1[static_cast<size_t>(q) * a.k + a.k - 1]) / 2);
+        a.dk[q] = dk;
+        a.thr[q] = dk + static_cast<uint32_t>(a.extra) + 1u;
+        a.cnt[q] = 0;
+        a.flag[0] = 1;
+    }
+}
+
+// First stage was the bounded candidate search (keys sorted by (D, row), at most keep1 per
+// query).  A list shorter than keep1 is every row within the boundary: if it also fits the
+// caller's bound the query is done and skips the collecting scans (threshold 0).
+__global__ __launch_bounds__(kBlock) void kselect_from_lists(const KSelectArgs a)
+{
+    const int q = blockIdx.x;
+    const uint64_t* src = a.topk1 + static_cast<size_t>(q) * a.keep1;
+    const uint32_t len = a.len1[q];
+    const uint32_t dk = static_cast<uint32_t>(src[a.k - 1] >> 32);
+    const bool whole = len < static_cast<uint32_t>(a.keep1) && len <= static_cast<uint32_t>(a.cap);
+    uint64_t* list = a.list + static_cast<size_t>(q) * a.cap;
+    if (whole)
+        for (uint32_t t = threadIdx.x; t < len; t += kBlock) list[t] = src[t];
+    for (int t = threadIdx.x; t < a.k; t += kBlock) a.best[static_cast<size_t>(q) * a.k + t] = src[t];
+    if (threadIdx.x == 0) {
+        a.dk[q] = dk;
+        a.cnt[q] = whole ? len : 0u;
+        a.thr[q] = whole ? 0u : dk + static_cast<uint32_t>(a.extra) + 1u;
+        if (!whole) a.flag[0] = 1;
+    }
 }
 
 // One workgroup per query.  A query whose rows within the bound fit its list is done
@@ -68,11 +101,7 @@ __global__ __launch_bounds__(kBlock) void kselect_levels(const KSelectArgs a)
     __syncthreads();
     if (s_level == 0) {                                  // the ties at D_K alone do not fit
         uint64_t* list = a.list + static_cast<size_t>(q) * a.cap;
-        const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
-        for (int t = threadIdx.x; t < a.k; t += kBlock) {
-            const size_t at = static_cast<size_t>(q) * a.k + t;
-            list[t] = make_key(static_cast<uint32_t>((full - a.score1[at]) / 2), static_cast<uint32_t>(a.idx1[at]));
-        }
+        for (int t = threadIdx.x; t < a.k; t += kBlock) list[t] = a.best[static_cast<size_t>(q) * a.k + t];
         if (threadIdx.x == 0) {
             a.cnt[q] = static_cast<uint32_t>(a.k);
             a.thr2[q] = 0;
@@ -82,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void kselect_levels(const KSelectArgs a)
     if (threadIdx.x == 0) {
         a.cnt[q] = 0;
         a.thr2[q] = a.dk[q] + s_level;                   // D < D_K + level  <=>  D <= D_K + level - 1
-        a.flag[0] = 1;
+        a.flag[1] = 1;
     }
 }
 
@@ -198,10 +227,15 @@ static bool kselect_args_ok(const KSelectArgs& a)
            a.parts >= 1 && static_cast<int64_t>(a.parts) * a.k <= kSortCap && 2 * a.k <= kRefineSort;
 }
 
-hipError_t launch_kselect_bound(const KSelectArgs& a, hipStream_t s)
+hipError_t launch_kselect_first(const KSelectArgs& a, hipStream_t s)
 {
     if (!kselect_args_ok(a)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kselect_bound, dim3((a.m + kBlock - 1) / kBlock), dim3(kBlock), 0, s, a);
+    if (a.topk1 != nullptr) {
+        if (a.keep1 < a.k) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(kselect_from_lists, dim3(a.m), dim3(kBlock), 0, s, a);
+    } else {
+        hipLaunchKernelGGL(kselect_from_topk, dim3(a.m), dim3(kBlock), 0, s, a);
+    }
     return hipGetLastError();
 }
 
