@@ -146,10 +146,9 @@ int xbq_search_refine(const float* X_db, const uint32_t* db_codes, int64_t n, in
  * 2 GiB).  A query with more rows than that within its boundary has the boundary lowered, one
  * distance unit at a time and never below D_K, until the rows within it fit; if the rows with
  * D <= D_K alone do not fit (ties), L is the K best rows by (D, row).
- * 0 <= extra_distance <= XBQ_MAX_EXTRA.  Cost: two scans of the database per call (the exact
- * search, then the collection) plus the refine, and a third scan for a batch in which some
- * query had its boundary lowered; xbq_search_refine needs one scan, and its list is at most
- * 2048 rows.
+ * 0 <= extra_distance <= XBQ_MAX_EXTRA.  Cost: that of xbq_search_refine while every list of a
+ * batch stays below 2048 rows and max_candidates; otherwise one more scan of the database
+ * collects the longer lists, and another one if some query had its boundary lowered.
  */
 size_t xbq_k_select_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int k, int extra_distance,
                                     int64_t max_candidates);
