@@ -52,7 +52,7 @@ def test_nothing_shipped_reads_scratch_or_reference_folders():
 
 def test_header_cites_the_paper_for_every_compute_entry_point():
     text = open(os.path.join(ROOT, "include", "xbq.h")).read()
-    for name in ("xbq_encode", "xbq_search", "xbq_search_asym", "xbq_search_refine"):
+    for name in ("xbq_encode", "xbq_search", "xbq_search_asym", "xbq_search_refine", "xbq_k_select"):
         decl = text.index(name + "(")
         block = text[max(0, decl - 3000):decl]
         assert re.search(r"Section|Algorithm|Eq\.", block), name
