@@ -252,6 +252,11 @@ KSELECT = [
     (20000, 128, 24, 4, 3, 100, 120, 130),
     (20000, 96, 24, 3, 3, 10, 50, 10),             # max_candidates = k
     (5000, 16, 9, 1, 1, 20, 3, 40),                # one-bit codes: few levels, massive ties
+    (2000, 2048, 18, 4, 4, 5, 100, 2000),          # widest rows the library takes
+    (3000, 64, 40, 3, 3, 1024, 10, 3000),          # largest k, first stage = bounded candidate search
+    (50, 32, 20, 2, 2, 7, 2, 50),                  # fewer rows than a bundle
+    (5000, 128, 200, 4, 3, 10, 40, 64),            # whole bounded lists that exceed the caller's bound
+    (6000, 100, 300, 4, 4, 10, 4095, 6000),        # every row a candidate for 300 queries
 ]
 
 
