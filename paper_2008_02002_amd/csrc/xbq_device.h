@@ -60,6 +60,33 @@ __device__ __forceinline__ uint32_t xor_popcount(const uint32_t (&x)[BD][WC], co
     return D;
 }
 
+// The same sums left apart: acc[c] += sum over i + j = c, w of POPCNT(x_i[w] ^ y_j[w]).  For rows
+// that come in several chunks of words the Horner combination is then done once per row, not
+// once per chunk.
+template <int BQ, int BD, int WC>
+__device__ __forceinline__ void xor_popcount_classes(const uint32_t (&x)[BD][WC], const uint32_t (&y)[BQ][WC],
+                                                     uint32_t (&acc)[BQ + BD - 1])
+{
+#pragma unroll
+    for (int c = 0; c < BQ + BD - 1; ++c)
+#pragma unroll
+        for (int i = 0; i < BD; ++i) {
+            const int j = c - i;
+            if (j < 0 || j >= BQ) continue;
+#pragma unroll
+            for (int w = 0; w < WC; ++w) acc[c] = popcount_add(x[i][w] ^ y[j][w], acc[c]);
+        }
+}
+
+template <int C>
+__device__ __forceinline__ uint32_t combine_classes(const uint32_t (&acc)[C])
+{
+    uint32_t D = acc[C - 1];
+#pragma unroll
+    for (int c = C - 2; c >= 0; --c) D = (D << 1) + acc[c];
+    return D;
+}
+
 // Append the keys of the lanes with `pass` set to list[0 .. cap): one atomic per wavefront on
 // *counter reserves the slots, v_mbcnt ranks the lanes.  Keys past cap are dropped; the
 // counter still counts them, which is how an overflow is seen later.

@@ -92,7 +92,8 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
 // so the B*WC words a (query, chunk) step needs are contiguous.  Words past W are zero on
 // both sides and add nothing to D.
 // ---------------------------------------------------------------------------------------
-template <int BQ, int BD, int WC, bool DENSE>
+// EXACT: W is a multiple of WC, so no chunk reaches past the row's words and the loads need no guard.
+template <int BQ, int BD, int WC, bool DENSE, bool EXACT>
 __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
 {
     constexpr int TQ = kTileQ;
@@ -111,9 +112,12 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
     const int q0 = qrange * a.qsplit;
     const int q1 = q0 + a.qsplit < a.m ? q0 + a.qsplit : a.m;
     for (int qt = q0; qt < q1; qt += TQ) {
-        uint32_t acc[TQ];
+        constexpr int C = BQ + BD - 1;
+        uint32_t cls[TQ][C];                          // one running sum per query and weight class
 #pragma unroll
-        for (int t = 0; t < TQ; ++t) acc[t] = 0;
+        for (int t = 0; t < TQ; ++t)
+#pragma unroll
+            for (int c = 0; c < C; ++c) cls[t][c] = 0;
         for (int c = 0; c < a.nchunks; ++c) {
             uint32_t x[BD][WC];
 #pragma unroll
@@ -121,7 +125,7 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
 #pragma unroll
                 for (int w = 0; w < WC; ++w) {
                     const int ww = c * WC + w;
-                    x[b][w] = ww < W ? xb[(b * W + ww) * kLanes] : 0u;
+                    x[b][w] = (EXACT || ww < W) ? xb[(b * W + ww) * kLanes] : 0u;
                 }
 #pragma unroll
             for (int t = 0; t < TQ; ++t) {
@@ -132,9 +136,12 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
                 for (int b = 0; b < BQ; ++b)
 #pragma unroll
                     for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
-                acc[t] += xor_popcount<BQ, BD, WC>(x, y);
+                xor_popcount_classes<BQ, BD, WC>(x, y, cls[t]);
             }
         }
+        uint32_t acc[TQ];
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) acc[t] = combine_classes<C>(cls[t]);
 #pragma unroll
         for (int t = 0; t < TQ; ++t) {
             const int q = qt + t;
@@ -236,8 +243,9 @@ static hipError_t launch_chunked_bw(ScanArgs a, bool dense, int64_t bundles, hip
 {
     dim3 grid;
     if (!tile_grid(a, bundles, 4, grid)) return hipErrorInvalidValue;
-    if (dense) hipLaunchKernelGGL((scan_chunked<BQ, BD, WC, true>), grid, dim3(kBlock), 0, s, a);
-    else       hipLaunchKernelGGL((scan_chunked<BQ, BD, WC, false>), grid, dim3(kBlock), 0, s, a);
+    if (dense)               hipLaunchKernelGGL((scan_chunked<BQ, BD, WC, true, false>), grid, dim3(kBlock), 0, s, a);
+    else if (a.W % WC == 0)  hipLaunchKernelGGL((scan_chunked<BQ, BD, WC, false, true>), grid, dim3(kBlock), 0, s, a);
+    else                     hipLaunchKernelGGL((scan_chunked<BQ, BD, WC, false, false>), grid, dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
