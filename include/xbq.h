@@ -196,6 +196,9 @@ int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_byte
  *   "selector"          0 = automatic, 1 = threshold filter with growing row groups (many
  *                       queries), 2 = histogram selection (few queries; Section 4.1)
  *   "hist_max_queries"  automatic choice: histogram selection up to this many queries
+ *   "kselect_lists_min" xbq_k_select starts a batch of at least this many queries from the
+ *                       bounded candidate search, a smaller one from the plain search
+ *                       (default 128, the measured crossover; results do not depend on it)
  *   "kernel"            0 = XOR + population count (the method of the paper, default);
  *                       1 = cross-check scan that gets the same integer distances from packed
  *                       4-bit dot products, 2 = from an int8 matrix product on the matrix

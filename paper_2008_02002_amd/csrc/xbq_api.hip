@@ -30,6 +30,7 @@ struct Options {
     int selector = 0;                // 0 automatic, 1 threshold filter, 2 histogram
     int hist_max_queries = 16;       // automatic choice: histogram selection up to this many queries
     int kernel = 0;                  // 0 XOR + population count; cross-checks: 1 packed 4-bit dots, 2 int8 MFMA
+    int kselect_lists_min = 128;     // xbq_k_select: batches of at least this many queries start from bounded lists
 } g_opt;
 
 struct Trace {
@@ -496,11 +497,13 @@ struct KPlan {
     size_t total = 0;
 };
 
-// The first stage of a batch of mb queries and its workspace.
+// The first stage of a batch of mb queries and its workspace: the plain search (few = true) for
+// few queries, where the longer schedule of the bounded candidate search costs more than the
+// collecting scan it may save; else the bounded candidate search.
 Plan first_stage_plan(int64_t n, int64_t mb, int d, int q_bits, int k, bool& few)
 {
     const Plan plain = make_plan(n, mb, d, q_bits, k, false);
-    few = plain.hist;
+    few = plain.hist || mb < g_opt.kselect_lists_min;
     return few ? plain : make_plan(n, mb, d, q_bits, k, true);
 }
 
@@ -605,6 +608,21 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
         if (e != hipSuccess) return fail_hip(e);
         e = launch_kselect_first(ka, s);
         if (e != hipSuccess) return fail_hip(e);
+
+        if (p.hist && mb <= kHistMaxQueries) {
+            // one histogram pass scored these queries and its stored distances are still in the
+            // workspace: collect from them instead of scanning the codes again
+            const uint32_t* dist = reinterpret_cast<const uint32_t*>(ws + p.hoff_dist);
+            e = launch_kselect_collect_stored(ka, dist, false, s);
+            if (e != hipSuccess) return fail_hip(e);
+            e = launch_kselect_levels(ka, s);
+            if (e != hipSuccess) return fail_hip(e);
+            e = launch_kselect_collect_stored(ka, dist, true, s);
+            if (e != hipSuccess) return fail_hip(e);
+            e = launch_kselect_refine(ka, s);
+            if (e != hipSuccess) return fail_hip(e);
+            continue;
+        }
 
         ScanArgs sa{};
         sa.db = job.db_codes;
@@ -881,6 +899,11 @@ int xbq_set_option(const char* name, double value)
     if (!std::strcmp(name, "hist_max_queries")) {
         if (!(value >= 0 && value <= (1 << 20))) return XBQ_EINVAL;
         g_opt.hist_max_queries = static_cast<int>(value);
+        return XBQ_OK;
+    }
+    if (!std::strcmp(name, "kselect_lists_min")) {
+        if (!(value >= 0 && value <= (1 << 20))) return XBQ_EINVAL;
+        g_opt.kselect_lists_min = static_cast<int>(value);
         return XBQ_OK;
     }
     if (!std::strcmp(name, "qsplit")) {

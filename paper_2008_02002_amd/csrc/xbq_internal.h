@@ -221,6 +221,8 @@ struct KSelectArgs {
 };
 hipError_t launch_kselect_first(const KSelectArgs& a, hipStream_t s);
 hipError_t launch_kselect_levels(const KSelectArgs& a, hipStream_t s);
+// Collection from stored distances dist[m][n] (few queries); second = with the lowered bounds.
+hipError_t launch_kselect_collect_stored(const KSelectArgs& a, const uint32_t* dist, bool second, hipStream_t s);
 hipError_t launch_kselect_refine(const KSelectArgs& a, hipStream_t s);
 
 // xbq_probe.hip: sustained-rate probes (measurement aids)

@@ -70,6 +70,90 @@ __global__ __launch_bounds__(kBlock) void kselect_from_lists(const KSelectArgs a
     }
 }
 
+// Few queries, first stage = histogram search: every distance is already stored (dist[q][n]), so
+// the collection reads those instead of scanning the codes again.  grid = m * blocks_per_query
+// workgroups of rows_per_block rows; per round of 16 rows per thread the workgroup reserves its
+// slots with one atomic, so a query with a very long list does not serialise on its counter.
+// `thr`: a row passes when D < thr[q]; thr[q] == 0 means the query needs nothing.  `levels` may
+// be nullptr (second collection).
+__global__ __launch_bounds__(kBlock) void kselect_collect_stored(const KSelectArgs a, const uint32_t* dist,
+                                                                 const uint32_t* thr, uint32_t* levels,
+                                                                 int rows_per_block, int blocks_per_query)
+{
+    __shared__ uint32_t lvl[kLevelBins];
+    __shared__ uint32_t wave_tot[kBlock / kLanes];
+    __shared__ uint32_t base_s;
+    const int q = blockIdx.x / blocks_per_query;
+    const int chunk = blockIdx.x - q * blocks_per_query;
+    const uint32_t t = thr[q];
+    if (t == 0) return;                                  // same value in every lane
+    const uint32_t dk = a.dk[q];
+    const int bins = a.extra + 2;
+    if (levels != nullptr) {
+        for (int i = threadIdx.x; i < bins; i += kBlock) lvl[i] = 0;
+    }
+    __syncthreads();
+    const uint32_t* dq = dist + static_cast<size_t>(q) * a.n;
+    uint64_t* list = a.list + static_cast<size_t>(q) * a.cap;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r_begin = static_cast<int64_t>(chunk) * rows_per_block;
+    const int64_t r_end = r_begin + rows_per_block < a.n ? r_begin + rows_per_block : a.n;
+    for (int64_t r0 = r_begin; r0 < r_end; r0 += 16 * kBlock) {
+        uint32_t D[4][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t row = r0 + (static_cast<int64_t>(u) * kBlock + threadIdx.x) * 4;
+            if (row + 3 < r_end && (reinterpret_cast<uintptr_t>(dq + row) & 15) == 0) {
+                const uint4 v = *reinterpret_cast<const uint4*>(dq + row);
+                D[u][0] = v.x; D[u][1] = v.y; D[u][2] = v.z; D[u][3] = v.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) D[u][e] = row + e < r_end ? dq[row + e] : 0xffffffffu;
+            }
+        }
+        uint32_t mine = 0;                               // rows of this thread that pass
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mine += D[u][e] < t ? 1u : 0u;
+        uint32_t incl = mine;                            // inclusive scan inside the wavefront
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t v = __shfl_up(incl, off);
+            if (lane >= off) incl += v;
+        }
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t total = 0;
+            for (int w = 0; w < kBlock / kLanes; ++w) total += wave_tot[w];
+            base_s = total ? atomicAdd(&a.cnt[q], total) : 0u;
+        }
+        __syncthreads();
+        uint32_t pos = base_s + incl - mine;
+        for (int w = 0; w < wave; ++w) pos += wave_tot[w];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (D[u][e] < t) {
+                    const int64_t row = r0 + (static_cast<int64_t>(u) * kBlock + threadIdx.x) * 4 + e;
+                    if (pos < static_cast<uint32_t>(a.cap)) list[pos] = make_key(D[u][e], static_cast<uint32_t>(row));
+                    ++pos;
+                    if (levels != nullptr) atomicAdd(&lvl[D[u][e] < dk ? 0u : D[u][e] - dk + 1u], 1u);
+                }
+            }
+        __syncthreads();                                 // wave_tot and base_s are reused by the next round
+    }
+    if (levels != nullptr) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < bins; i += kBlock) {
+            const uint32_t v = lvl[i];
+            if (v) atomicAdd(&levels[static_cast<size_t>(q) * bins + i], v);
+        }
+    }
+}
+
 // One workgroup per query.  A query whose rows within the bound fit its list is done
 // (thr2 = 0).  Otherwise the level counts of the collecting scan give the largest distance
 // whose rows still fit (whole levels, never below D_K): the list is emptied and the query
@@ -236,6 +320,17 @@ hipError_t launch_kselect_first(const KSelectArgs& a, hipStream_t s)
     } else {
         hipLaunchKernelGGL(kselect_from_topk, dim3(a.m), dim3(kBlock), 0, s, a);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_kselect_collect_stored(const KSelectArgs& a, const uint32_t* dist, bool second, hipStream_t s)
+{
+    if (!kselect_args_ok(a) || dist == nullptr) return hipErrorInvalidValue;
+    const int rows_per_block = 16 * kBlock;              // one round: workgroups are cheap, parallelism is not
+    const int64_t bpq = (a.n + rows_per_block - 1) / rows_per_block;
+    if (bpq * a.m > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kselect_collect_stored, dim3(static_cast<unsigned>(bpq * a.m)), dim3(kBlock), 0, s, a, dist,
+                       second ? a.thr2 : a.thr, second ? nullptr : a.levels, rows_per_block, static_cast<int>(bpq));
     return hipGetLastError();
 }
 

@@ -257,6 +257,9 @@ KSELECT = [
     (50, 32, 20, 2, 2, 7, 2, 50),                  # fewer rows than a bundle
     (5000, 128, 200, 4, 3, 10, 40, 64),            # whole bounded lists that exceed the caller's bound
     (6000, 100, 300, 4, 4, 10, 4095, 6000),        # every row a candidate for 300 queries
+    (20001, 128, 5, 4, 4, 10, 120, 700),           # few queries: collection from the stored distances, lists cut
+    (9001, 96, 8, 4, 3, 100, 60, 9001),            # eight queries, row count not a multiple of four
+    (70000, 64, 2, 3, 3, 10, 300, 70000),          # several workgroups per query, most rows candidates
 ]
 
 
@@ -273,6 +276,25 @@ def test_k_select_matches_algorithm_1_with_whole_levels(n, d, m, qb, db, k, extr
     sub = np.arange(m) if m <= 48 else np.concatenate([np.arange(24), m - 1 - np.arange(24)])
     D = gu.oracle_distances(Xdb, Xq[sub], db, qb, scale)
     gu.assert_refined_matches(tuple(x[sub] for x in got), Xdb, Xq[sub], D, k, extra, limit, by_levels=True)
+
+
+def test_k_select_result_does_not_depend_on_the_first_stage():
+    rng = np.random.default_rng(5)
+    Xdb = rng.standard_normal((30000, 128)).astype(np.float32)
+    Xdb /= np.linalg.norm(Xdb, axis=1, keepdims=True)
+    Xq = rng.standard_normal((150, 128)).astype(np.float32)
+    Xq /= np.linalg.norm(Xq, axis=1, keepdims=True)
+    scale = wl.choose_scale(Xdb)
+    D = gu.oracle_distances(Xdb, Xq[:20], 4, 4, scale)
+    try:
+        for lists_min in (0, 1 << 20):
+            for extra, limit in ((40, 30000), (200, 3000)):
+                _say(f"k_select first stage: lists_min={lists_min} extra={extra} max_candidates={limit}")
+                xbq.xbq_set_option("kselect_lists_min", lists_min)
+                got = gu.gpu_k_select(Xdb, Xq, 4, 4, 10, extra, limit, scale)
+                gu.assert_refined_matches(tuple(x[:20] for x in got), Xdb, Xq[:20], D, 10, extra, limit, by_levels=True)
+    finally:
+        xbq.xbq_set_option("kselect_lists_min", 128)
 
 
 def test_k_select_ties_at_the_kth_distance_exceed_the_bound():
