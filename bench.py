@@ -342,10 +342,32 @@ def main():
             torch.cuda.synchronize()
             graph_ms = g0.elapsed_time(g1) / reps
             del graph
+            # Algorithm 1 in full for the same queries (extra distance 100, fp32 refine), the request
+            # the paper times: xbq_k_select on resident codes and resident fp32 rows
+            ks_cap = min(w.n, 8192)
+            ks_ws = torch.empty(xbq.lib().xbq_k_select_workspace_bytes(w.n, mq, w.d, bits, k, 100, ks_cap),
+                                dtype=torch.uint8, device="cuda")
+            ks_sim = torch.empty((mq, k), dtype=torch.float32, device="cuda")
+            ks_cnt = torch.empty((mq,), dtype=torch.int32, device="cuda")
+            for _ in range(3):
+                xbq.xbq_k_select(Xdb, db, db_bits, Xq[:mq], q, bits, k, 100, ks_cap, workspace=ks_ws, idx=idx1,
+                                 sim=ks_sim, cand=ks_cnt)
+            torch.cuda.synchronize()
+            k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            k0.record()
+            for _ in range(reps):
+                xbq.xbq_k_select(Xdb, db, db_bits, Xq[:mq], q, bits, k, 100, ks_cap, workspace=ks_ws, idx=idx1,
+                                 sim=ks_sim, cand=ks_cnt)
+            k1.record()
+            torch.cuda.synchronize()
+            ks_ms = k0.elapsed_time(k1) / reps
+            ks_mean = float(ks_cnt.float().mean())
+            del ks_ws, ks_sim, ks_cnt
             stream_bytes = w.n * (cm.code_bytes_per_row(w.d, db_bits) + 4 * mq)     # codes in, distances out
             out.setdefault("few_queries", []).append({
                 "queries": mq, "search_ms": lat_ms, "queries_per_s": mq / (lat_ms * 1e-3),
                 "graph_replay_ms": graph_ms, "graph_queries_per_s": mq / (graph_ms * 1e-3),
+                "k_select_extra100_ms": ks_ms, "k_select_mean_candidates": ks_mean,
                 "scan_kernel_ms": sms / reps, "scan_launches": sl / reps,
                 "scan_GBps": stream_bytes / 1e9 / (sms / reps * 1e-3),
                 "scan_hbm_frac": stream_bytes / (sms / reps * 1e-3) / cm.HBM_BYTES_PER_S,
