@@ -11,7 +11,7 @@ PKG = os.path.join(ROOT, "paper_2008_02002_amd")
 
 def _sources(top, exts):
     for base, dirs, files in os.walk(top):
-        dirs[:] = [x for x in dirs if x not in ("__pycache__", "_work", "gpurun_out", ".git")]
+        dirs[:] = [x for x in dirs if not x.startswith(("_", "."))]
         for f in files:
             if f.endswith(exts):
                 yield os.path.join(base, f)
