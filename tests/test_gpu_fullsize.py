@@ -203,3 +203,39 @@ def test_c4_full_size_k_select_long_lists():
     printed = np.array([(D[i] <= np.sort(D[i])[k - 1] + extra).sum() for i in range(len(sub))])
     _say(f"C4 k_select: rows within the printed boundary {printed.tolist()}, lists {cand[sub].tolist()}")
     assert (printed > limit).any(), "no sampled query had its list cut"
+
+
+def test_input_of_more_than_2_31_elements():
+    """One encode call and one search over 2.3 M x 960 fp32 values (2.2e9 elements, 8.8 GB; the
+    codes alone pass 2^30 bytes): every offset in the path has to be 64-bit."""
+    import torch
+    w = wl.scaled_down(wl.WORKLOADS["C3"], n=2_300_000, m=6)
+    assert w.n * w.d > 2**31
+    bits, k = 4, 10
+    X, Xq, scale = wl.database(w), wl.queries(w), wl.workload_scale(w)
+    xd = torch.from_numpy(X).cuda()
+    db = xbq.xbq_encode(xd, bits, scale, xbq.BUNDLE64)             # one call over the whole array
+    torch.cuda.synchronize()
+    _say("large input: encoded on the GPU")
+    planes = oc.encode(X, bits, scale)
+    W = (w.d + 31) // 32
+    tail = slice(w.n - 70_000, w.n)                                 # rows whose fp32 offsets lie beyond 2^31 elements
+    got = gu.bundle_as_rows(db.cpu().numpy().view(np.uint32), w.n, bits, W)[tail]
+    assert np.array_equal(got, oc.planes_as_u32(planes[tail], w.d))
+    head = gu.bundle_as_rows(db[:1024 * bits * W].cpu().numpy().view(np.uint32), 1024, bits, W)
+    assert np.array_equal(head, oc.planes_as_u32(planes[:1024], w.d))
+    q = xbq.xbq_encode(torch.from_numpy(Xq).cuda(), bits, scale, xbq.ROWS)
+    for sel in (1, 2):                                              # threshold schedule, then histogram selection
+        xbq.xbq_set_option("selector", sel)
+        try:
+            idx, score = xbq.xbq_search(db, w.n, q, w.m, w.d, bits, k)
+            torch.cuda.synchronize()
+        finally:
+            xbq.xbq_set_option("selector", 0)
+        _say(f"large input: searched, selector {sel}")
+        gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), oc.search(planes, oc.encode(Xq, bits, scale), w.d, k),
+                       f"large input selector {sel}")
+    ridx, rsim, rc = xbq.xbq_search_refine(xd, db, bits, torch.from_numpy(Xq).cuda(), q, bits, k, 50)
+    torch.cuda.synchronize()
+    exact = np.einsum("qkd,qd->qk", X[ridx.cpu().numpy()].astype(np.float64), Xq.astype(np.float64))
+    assert np.abs(exact - rsim.cpu().numpy()).max() <= 2e-6        # the refine gathered the right rows
