@@ -499,6 +499,52 @@ def test_search_can_be_captured_in_a_hip_graph_and_replayed():
             gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), want, f"graph replay {rep}, m={m}")
 
 
+def test_k_select_can_be_captured_in_a_hip_graph_and_replayed():
+    """Same for Algorithm 1 with the whole candidate list: its flags, counters and level counts
+    are cleared by kernels, and the collecting scans that have nothing to do return by themselves."""
+    import torch
+    n, d, bits, k, extra, limit = 40_000, 96, 4, 10, 80, 1500
+    rng = np.random.default_rng(7)
+    Xdb = rng.standard_normal((n, d)).astype(np.float32)
+    Xdb /= np.linalg.norm(Xdb, axis=1, keepdims=True)
+    scale = wl.choose_scale(Xdb)
+    xd = gu.to_dev(Xdb)
+    db = xbq.xbq_encode(xd, bits, scale, xbq.BUNDLE64)
+    for m in (4, 12, 200):                  # stored distances; plain search + scans; bounded lists + scans
+        xq = torch.zeros((m, d), dtype=torch.float32, device="cuda")
+        q = torch.zeros(xbq.xbq_code_bytes(m, d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
+        ws = torch.empty(xbq.lib().xbq_k_select_workspace_bytes(n, m, d, bits, k, extra, limit), dtype=torch.uint8,
+                         device="cuda")
+        idx = torch.empty((m, k), dtype=torch.int32, device="cuda")
+        sim = torch.empty((m, k), dtype=torch.float32, device="cuda")
+        cand = torch.empty((m,), dtype=torch.int32, device="cuda")
+
+        def run():
+            xbq.xbq_encode(xq, bits, scale, xbq.ROWS, out=q)
+            xbq.xbq_k_select(xd, db, bits, xq, q, bits, k, extra, limit, workspace=ws, idx=idx, sim=sim, cand=cand)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run()                                         # warm-up outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        for rep in range(3):
+            Xq = rng.standard_normal((m, d)).astype(np.float32)
+            Xq /= np.linalg.norm(Xq, axis=1, keepdims=True)
+            xq.copy_(torch.from_numpy(Xq))                # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            sub = np.arange(min(m, 16))
+            D = gu.oracle_distances(Xdb, Xq[sub], bits, bits, scale)
+            got = (idx.cpu().numpy()[sub], sim.cpu().numpy()[sub], cand.cpu().numpy()[sub])
+            gu.assert_refined_matches(got, Xdb, Xq[sub], D, k, extra, limit, by_levels=True)
+
+
 def test_random_shapes_against_the_oracle():
     """Seeded sweep over valid shapes: dimensions around word and chunk boundaries, row counts
     around bundle and group boundaries, every supported pair of code widths, both selectors."""
