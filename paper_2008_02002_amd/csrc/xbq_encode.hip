@@ -42,6 +42,15 @@ __device__ __forceinline__ uint32_t plane_words(uint32_t code, bool valid, int l
     return mine;
 }
 
+// The fp32 input is read once and never again: non-temporal loads keep it from displacing the
+// codes in the caches, and they stream measurably faster on this part.
+typedef float native_float4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_streaming(const float4* p)
+{
+    const native_float4 v = __builtin_nontemporal_load(reinterpret_cast<const native_float4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // XBQ_ROWS: one wavefront per row.
 template <int B>
 __global__ __launch_bounds__(kBlock) void encode_rows(const float* __restrict__ X, int64_t n, int d, float scale,
@@ -88,7 +97,7 @@ __global__ __launch_bounds__(kBlock) void encode_bundle(const float* __restrict_
             const int rr = i / steps, c = ((i - rr * steps) << 6) + lane;
             const int64_t row = bundle * 64 + wave * 16 + rr;
             ok[u] = i < items && row < n && c < d;
-            v[u] = ok[u] ? X[row * d + c] : 0.0f;
+            v[u] = ok[u] ? __builtin_nontemporal_load(X + row * d + c) : 0.0f;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -125,7 +134,7 @@ __device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
 // lanes completes the word.  Lane b of each group stores plane b's word into the LDS tile.
 template <int B>
 __global__ __launch_bounds__(kBlock) void encode_bundle_vec4(const float4* __restrict__ X4, int64_t n, int d,
-                                                             float scale, uint32_t recip, uint32_t* __restrict__ codes)
+                                                             float scale, float inv_slots, uint32_t* __restrict__ codes)
 {
     extern __shared__ uint32_t tile[];                   // B * W * 64 words
     const int W = (d + 31) >> 5;
@@ -142,17 +151,21 @@ __global__ __launch_bounds__(kBlock) void encode_bundle_vec4(const float4* __res
         __syncthreads();
     }
     const int sub = threadIdx.x & 7;                     // position inside the group of 8 lanes
-    constexpr int U = 4;
+    constexpr int U = 8;                                 // 16-byte loads in flight per lane
     for (int i0 = threadIdx.x; i0 < total; i0 += kBlock * U) {
         float4 v[U];
         int r[U], slot[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            // i / slots without an integer division or a full 32-bit multiply: (i + 0.5) / slots is
+            // at least 0.5 / 512 away from an integer, far more than the rounding of the two float
+            // operations on values below 2^16; the 24-bit multiplies below are exact for the same reason
             const int i = i0 + u * kBlock;
-            r[u] = static_cast<int>(__umulhi(static_cast<uint32_t>(i), recip));     // i / slots
-            slot[u] = i - r[u] * slots;
+            r[u] = static_cast<int>((static_cast<float>(i) + 0.5f) * inv_slots);
+            slot[u] = i - static_cast<int>(__umul24(r[u], slots));
             const bool real = i < total && slot[u] < f4_per_row;
-            v[u] = real ? src[r[u] * f4_per_row + slot[u]] : make_float4(0.f, 0.f, 0.f, 0.f);
+            const uint32_t off = __umul24(r[u], f4_per_row) + static_cast<uint32_t>(slot[u]);
+            v[u] = real ? load_streaming(src + off) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -185,13 +198,10 @@ static hipError_t launch_encode_b(const float* X, int64_t n, int d, float scale,
         hipLaunchKernelGGL(encode_rows<B>, dim3(static_cast<unsigned>((n + 3) / 4)), dim3(kBlock), 0, s, X, n, d,
                            scale, codes);
     } else if (d % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0) {
-        // recip = ceil(2^32 / slots), slots = 8 * W >= 8: mulhi(i, recip) == i / slots exactly
-        // for every i < 64 * slots <= 2^15 that the kernel uses
-        const uint32_t slots = 8u * static_cast<uint32_t>(W);
-        const uint32_t recip = static_cast<uint32_t>(((1ull << 32) + slots - 1) / slots);
+        const float inv_slots = 1.0f / static_cast<float>(8 * W);       // slots = 8 * W <= 512 per row
         const size_t lds = static_cast<size_t>(B) * W * 64 * sizeof(uint32_t);
         hipLaunchKernelGGL(encode_bundle_vec4<B>, dim3(static_cast<unsigned>((n + 63) / 64)), dim3(kBlock), lds, s,
-                           reinterpret_cast<const float4*>(X), n, d, scale, recip, codes);
+                           reinterpret_cast<const float4*>(X), n, d, scale, inv_slots, codes);
     } else {
         const size_t lds = static_cast<size_t>(B) * W * 64 * sizeof(uint32_t);
         hipLaunchKernelGGL(encode_bundle<B>, dim3(static_cast<unsigned>((n + 63) / 64)), dim3(kBlock), lds, s, X, n,
