@@ -136,7 +136,8 @@ template <int B>
 __global__ __launch_bounds__(kBlock) void encode_bundle_vec4(const float4* __restrict__ X4, int64_t n, int d,
                                                              float scale, float inv_slots, uint32_t* __restrict__ codes)
 {
-    extern __shared__ uint32_t tile[];                   // B * W * 64 words
+    extern __shared__ uint32_t tile[];                   // B * W rows of 65 words: the pad word spreads the
+                                                         // lanes of a wavefront, which write one column, over the banks
     const int W = (d + 31) >> 5;
     const int slots = 8 * W;                             // float4 slots per row, padding included
     const int f4_per_row = d >> 2;                       // real float4s per row
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(kBlock) void encode_bundle_vec4(const float4* __res
     const float4* src = X4 + row0 * f4_per_row;
     const int words = B * W * 64;
     if (live < 64) {                                     // rows past n must come out as zero words
-        for (int t = threadIdx.x; t < words; t += blockDim.x) tile[t] = 0;
+        for (int t = threadIdx.x; t < words + B * W; t += blockDim.x) tile[t] = 0;
         __syncthreads();
     }
     const int sub = threadIdx.x & 7;                     // position inside the group of 8 lanes
@@ -181,12 +182,12 @@ __global__ __launch_bounds__(kBlock) void encode_bundle_vec4(const float4* __res
                 const uint32_t word = or_reduce8(nib << (4 * sub));
                 if (sub == b) mine = word;
             }
-            if (i < total && sub < B) tile[(sub * W + (slot[u] >> 3)) * 64 + r[u]] = mine;
+            if (i < total && sub < B) tile[(sub * W + (slot[u] >> 3)) * 65 + r[u]] = mine;
         }
     }
     __syncthreads();
     uint32_t* out = codes + bundle * static_cast<int64_t>(words);
-    for (int t = threadIdx.x; t < words; t += blockDim.x) out[t] = tile[t];
+    for (int t = threadIdx.x; t < words; t += blockDim.x) out[t] = tile[t + (t >> 6)];
 }
 
 template <int B>
@@ -199,7 +200,7 @@ static hipError_t launch_encode_b(const float* X, int64_t n, int d, float scale,
                            scale, codes);
     } else if (d % 4 == 0 && reinterpret_cast<uintptr_t>(X) % 16 == 0) {
         const float inv_slots = 1.0f / static_cast<float>(8 * W);       // slots = 8 * W <= 512 per row
-        const size_t lds = static_cast<size_t>(B) * W * 64 * sizeof(uint32_t);
+        const size_t lds = static_cast<size_t>(B) * W * 65 * sizeof(uint32_t);
         hipLaunchKernelGGL(encode_bundle_vec4<B>, dim3(static_cast<unsigned>((n + 63) / 64)), dim3(kBlock), lds, s,
                            reinterpret_cast<const float4*>(X), n, d, scale, inv_slots, codes);
     } else {
