@@ -43,6 +43,13 @@ def lib() -> ctypes.CDLL:
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2008_02002_amd.build`; "
                 "there is no fallback path")
+        # PyTorch ships its own copy of the HIP runtime.  The tensors this binding takes live in
+        # that runtime, so it has to be the one libxbq.so binds to: load it first.  (Loaded the
+        # other way round, the process ends up with two runtimes and launches fail.)
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         i64, i32, vp, f32, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
         L.xbq_version.restype = i32

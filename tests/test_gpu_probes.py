@@ -62,3 +62,24 @@ def test_probe_argument_errors():
     assert L.xbq_probe_read(p(big), 24, p(big), big.numel() * 4, None) == xbq.EINVAL          # not a multiple of 16
     assert L.xbq_probe_read(ctypes.c_void_p(big.data_ptr() + 4), 16, p(big), big.numel() * 4, None) == xbq.EINVAL
     assert L.xbq_probe_read(p(big), 16, p(small), 64, None) == xbq.EWORKSPACE
+
+
+def test_binding_loaded_before_any_other_gpu_use_shares_one_runtime():
+    """A fresh process that touches the binding before anything else has initialised the GPU
+    must still launch on the runtime that owns the tensors."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "from paper_2008_02002_amd import xbq\n"
+        "xbq.xbq_set_option('growth', 4.0)\n"          # loads the library first
+        "import numpy as np, torch\n"
+        "X = torch.from_numpy(np.linspace(-0.9, 0.9, 64 * 32, dtype=np.float32).reshape(64, 32)).cuda()\n"
+        "c = xbq.xbq_encode(X, 4, 1.0, xbq.ROWS); torch.cuda.synchronize()\n"
+        "idx, score = xbq.xbq_search(xbq.xbq_encode(X, 4, 1.0, xbq.BUNDLE64), 64, c, 64, 32, 4, 1)\n"
+        "torch.cuda.synchronize(); print('loaded-first ok', int(c.numel()), int(idx.numel()))\n" % root)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+    assert "loaded-first ok 256 64" in r.stdout
