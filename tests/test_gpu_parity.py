@@ -569,3 +569,66 @@ def test_random_shapes_against_the_oracle():
                            f"trial {trial}")
     finally:
         xbq.xbq_set_option("selector", 0)
+
+
+def test_random_shapes_through_every_search_entry_point():
+    """Seeded sweep like the one above, over the three kinds of search call and four kinds of
+    rows (uniform, Gaussian, all-positive, tight clusters with many near-ties), rows normalised."""
+    rng = np.random.default_rng(31337)
+    dims = [1, 7, 31, 32, 33, 64, 65, 96, 127, 128, 129, 200, 256, 257, 288, 700, 960, 1500, 2048]
+    rows = [1, 2, 63, 64, 65, 128, 1000, 1024, 1025, 1536, 4096, 4097, 5121, 9999, 20011]
+    pairs = [(1, 1), (2, 2), (3, 3), (4, 4), (2, 1), (3, 2), (4, 3)]
+
+    def draw(n, d, kind):
+        if kind == 0:
+            X = rng.uniform(-0.5, 0.5, (n, d))
+        elif kind == 1:
+            X = rng.standard_normal((n, d))
+        elif kind == 2:
+            X = np.abs(rng.standard_normal((n, d)))
+        else:
+            base = rng.standard_normal((max(1, n // 50), d))
+            X = base[rng.integers(len(base), size=n)] + 0.05 * rng.standard_normal((n, d))
+        return (X / np.maximum(np.linalg.norm(X, axis=1, keepdims=True), 1e-9)).astype(np.float32)
+
+    try:
+        for trial in range(60):
+            d = int(rng.choice(dims))
+            n = int(rng.choice(rows))
+            qb, db = pairs[int(rng.integers(len(pairs)))]
+            m = int(rng.choice([1, 3, 8, 9, 17, 40, 130, 300]))
+            k = int(min(n, rng.choice([1, 2, 10, 64, 100, 513, 1024])))
+            kind = int(rng.integers(4))
+            scale = float(rng.choice([1.0, 1.7, 3.3]))
+            call = int(rng.integers(3))
+            Xdb, Xq = draw(n, d, kind), draw(m, d, kind)
+            sub = np.arange(min(m, 16))
+            if call == 0:
+                sel = int(rng.choice([0, 1, 2]))
+                _say(f"trial {trial}: search n={n} d={d} m={m} {qb}x{db} k={k} rows={kind} selector={sel}")
+                xbq.xbq_set_option("selector", sel)
+                gu.assert_same(gu.gpu_search_asym(Xdb, Xq, db, qb, k, scale),
+                               gu.oracle_search_asym(Xdb, Xq, db, qb, k, scale), f"trial {trial}")
+                xbq.xbq_set_option("selector", 0)
+            elif call == 1:
+                extra = int(rng.choice([0, 3, 40, 300, 100000]))
+                _say(f"trial {trial}: refine n={n} d={d} m={m} {qb}x{db} k={k} rows={kind} extra={extra}")
+                got = gu.gpu_search_refine(Xdb, Xq, db, qb, k, extra, scale)
+                D = gu.oracle_distances(Xdb, Xq[sub], db, qb, scale)
+                gu.assert_refined_matches(tuple(x[sub] for x in got), Xdb, Xq[sub], D, k, extra,
+                                          xbq.REFINE_MAX_CANDIDATES)
+            else:
+                extra = int(rng.choice([0, 3, 40, 300, 4095]))
+                limit = int(rng.choice([k, k + 7, max(k, n // 10), max(k, n // 2), n, 4 * n + 5]))
+                lists_min = int(rng.choice([0, 128, 1 << 20]))
+                _say(f"trial {trial}: k_select n={n} d={d} m={m} {qb}x{db} k={k} rows={kind} extra={extra} "
+                     f"max_candidates={limit} lists_min={lists_min}")
+                xbq.xbq_set_option("kselect_lists_min", lists_min)
+                got = gu.gpu_k_select(Xdb, Xq, db, qb, k, extra, limit, scale)
+                xbq.xbq_set_option("kselect_lists_min", 128)
+                D = gu.oracle_distances(Xdb, Xq[sub], db, qb, scale)
+                gu.assert_refined_matches(tuple(x[sub] for x in got), Xdb, Xq[sub], D, k, extra, min(limit, n),
+                                          by_levels=True)
+    finally:
+        xbq.xbq_set_option("selector", 0)
+        xbq.xbq_set_option("kselect_lists_min", 128)
