@@ -296,7 +296,9 @@ def main():
             "scan_ms_per_step": scan_ms / args.steps,
             "launches_per_step": launches / args.steps,
             "avg_launch_ms": scan_ms / max(launches, 1),
+            # the batched scan is not an HBM stream: the codes are read about once per step
             "scan_code_GBps": w.n * cm.code_bytes_per_row(w.d, db_bits) / 1e9 / (scan_ms / args.steps * 1e-3),
+            "traffic_GBps": (traffic / 1e9 / (scan_ms / max(launches, 1) * 1e-3)) if traffic else None,
         },
         "encode": {"db_ms": enc_ms,
                    "GBps": w.n * cm.encode_bytes_per_row(w.d, db_bits) / 1e9 / (enc_ms * 1e-3),
