@@ -61,9 +61,12 @@ __device__ void write_topk(const SelectArgs& a, int q, const uint64_t* keys, int
     if (a.final_group && a.extra < 0) write_result(a, q, keys);
 }
 
+// The sort buffers of select_dense and select_merge are dynamic LDS sized by the host for the
+// launch at hand (a power of two of keys, at most kSortCap): most launches need far less than
+// kSortCap keys, and the smaller footprint lets more workgroups share a compute unit.
 __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
 {
-    __shared__ uint64_t keys[kSortCap];
+    extern __shared__ uint64_t keys[];
     __shared__ int scratch;
     const int q = blockIdx.x;
     const int P = next_pow2(a.rows);
@@ -78,7 +81,7 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
 // Exact re-score of rows [row_begin, row_end) for one query, starting from its current
 // top-K.  keys[] holds the best K so far plus survivors; it is compacted (sorted, cut to K,
 // threshold tightened) whenever another full workgroup of survivors might not fit.
-__device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill)
+__device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int capacity, int* fill)
 {
     const SelectArgs& a = r.sel;
     const uint32_t* yq = r.q_rows + static_cast<size_t>(q) * a.q_bits * r.W;
@@ -94,8 +97,8 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill
             if (D < thr) keys[atomicAdd(fill, 1)] = make_key(D, static_cast<uint32_t>(row));
         }
         __syncthreads();
-        const int have = *fill;                      // <= previous fill + blockDim.x <= kSortCap
-        if (have > kSortCap - static_cast<int>(blockDim.x)) {
+        const int have = *fill;                      // <= previous fill + blockDim.x <= capacity
+        if (have > capacity - static_cast<int>(blockDim.x)) {
             const int P = next_pow2(have);
             for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
             __syncthreads();
@@ -132,15 +135,15 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int* fill
     write_topk(a, q, keys, have, fill);
 }
 
-__global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r)
+__global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int capacity)
 {
-    __shared__ uint64_t keys[kSortCap];
+    extern __shared__ uint64_t keys[];               // `capacity` keys
     __shared__ int fill;
     const SelectArgs& a = r.sel;
     const int q = blockIdx.x;
     const uint32_t c = a.cnt[q];                     // same value in every lane: branches are uniform
     if (c > static_cast<uint32_t>(a.cap)) {          // the list overflowed: nothing of it is used
-        rescan_rows(r, q, keys, &fill);
+        rescan_rows(r, q, keys, capacity, &fill);
         return;
     }
     if (c == 0 && !(a.final_group && a.extra < 0)) return;       // nothing new: list and threshold stand
@@ -216,7 +219,9 @@ hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s)
 {
     if (a.m <= 0) return hipSuccess;
     if (a.rows < a.k || a.rows > kSortCap) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(select_dense, dim3(a.m), dim3(kBlock), 0, s, a);
+    int keys = 1;
+    while (keys < a.rows) keys <<= 1;
+    hipLaunchKernelGGL(select_dense, dim3(a.m), dim3(kBlock), keys * sizeof(uint64_t), s, a);
     return hipGetLastError();
 }
 
@@ -233,7 +238,11 @@ hipError_t launch_select_merge(const MergeArgs& r, hipStream_t s)
 {
     if (r.sel.m <= 0) return hipSuccess;
     if (r.sel.keep_max + r.sel.cap > kSortCap || r.row_end > r.n || r.row_begin < 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(select_merge, dim3(r.sel.m), dim3(kBlock), 0, s, r);
+    // room for the kept keys plus a full survivor list; the exact rescan of an overflowed query
+    // works in the same buffer and needs the kept keys plus two rounds of one key per thread
+    int capacity = 1;
+    while (capacity < r.sel.keep_max + r.sel.cap || capacity < r.sel.keep_max + 2 * kBlock) capacity <<= 1;
+    hipLaunchKernelGGL(select_merge, dim3(r.sel.m), dim3(kBlock), capacity * sizeof(uint64_t), s, r, capacity);
     return hipGetLastError();
 }
 
