@@ -148,6 +148,38 @@ __device__ inline void bitonic_sort_lds(uint64_t* keys, int P)
     }
 }
 
+// Descending variant of the sort above (same contract).
+__device__ inline void bitonic_sort_lds_descending(uint64_t* keys, int P)
+{
+    for (int k = 2; k <= P; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (P >> 1); t += blockDim.x) {
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int l = i | j;
+                const bool down = (i & k) == 0;
+                const uint64_t a = keys[i], b = keys[l];
+                if ((a < b) == down) { keys[i] = b; keys[l] = a; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// Last stage of the ascending sort alone: turns a bitonic sequence of P keys (ascending run
+// followed by a descending run) into an ascending one in log2(P) steps.
+__device__ inline void bitonic_merge_lds(uint64_t* keys, int P)
+{
+    for (int j = P >> 1; j > 0; j >>= 1) {
+        for (int t = threadIdx.x; t < (P >> 1); t += blockDim.x) {
+            const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+            const int l = i | j;
+            const uint64_t a = keys[i], b = keys[l];
+            if (a > b) { keys[i] = b; keys[l] = a; }
+        }
+        __syncthreads();
+    }
+}
+
 // Eq. 6 for one (row, query) with run-time sizes; the slow path of the exact rescans.
 __device__ inline uint32_t distance_generic(const uint32_t* db, int64_t row, const uint32_t* yq, int BQ, int BD, int W)
 {

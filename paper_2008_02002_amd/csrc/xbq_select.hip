@@ -152,10 +152,23 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int ca
     const int P = next_pow2(total);
     const uint64_t* best = a.topk + static_cast<size_t>(q) * a.keep_max;
     const uint64_t* cand = a.cand + static_cast<size_t>(q) * a.cap;
-    for (int t = threadIdx.x; t < P; t += blockDim.x)
-        keys[t] = t < held ? best[t] : (t < total ? cand[t - held] : kPadKey);
-    __syncthreads();
-    if (c != 0) bitonic_sort_lds(keys, P);
+    const int PB = next_pow2(static_cast<int>(c));
+    if (c != 0 && held + PB <= P) {                  // the kept keys and the padded survivors fit side by side
+        // The kept keys are already sorted.  Sort only the survivors, descending, at the end of the
+        // buffer; kept keys (ascending), padding, survivors (descending, their padding first) then
+        // form one bitonic sequence, and a single merge stage finishes the job.
+        const int b0 = P - PB;
+        for (int t = threadIdx.x; t < P; t += blockDim.x)
+            keys[t] = t < held ? best[t] : (t >= b0 && t - b0 < static_cast<int>(c) ? cand[t - b0] : kPadKey);
+        __syncthreads();
+        bitonic_sort_lds_descending(keys + b0, PB);
+        bitonic_merge_lds(keys, P);
+    } else {
+        for (int t = threadIdx.x; t < P; t += blockDim.x)
+            keys[t] = t < held ? best[t] : (t < total ? cand[t - held] : kPadKey);
+        __syncthreads();
+        if (c != 0) bitonic_sort_lds(keys, P);
+    }
     write_topk(a, q, keys, total, &fill);
 }
 
