@@ -30,6 +30,7 @@ struct Options {
     int selector = 0;                // 0 automatic, 1 threshold filter, 2 histogram
     int hist_max_queries = 16;       // automatic choice: histogram selection up to this many queries
     int kernel = 0;                  // 0 XOR + population count; cross-checks: 1 packed 4-bit dots, 2 int8 MFMA
+    double refine_growth = 1.5;      // growth bound of the bounded candidate search
     int kselect_lists_min = 128;     // xbq_k_select: batches of at least this many queries start from bounded lists
 } g_opt;
 
@@ -435,7 +436,7 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             // at a third of the list capacity at most
             double growth = 1.0 + static_cast<double>(p.cap) / (3.0 * k);
             if (growth > g_opt.growth) growth = g_opt.growth;
-            if (refine && growth > 1.5) growth = 1.5;     // the kept list may be as long as the survivor list
+            if (refine && growth > g_opt.refine_growth) growth = g_opt.refine_growth;   // the kept list may be as long as the survivor list
             int64_t size = static_cast<int64_t>(std::ceil(static_cast<double>(seen) * (growth - 1.0)));
             size = (size + 511) / 512 * 512;
             int64_t end = seen + size;
@@ -899,6 +900,11 @@ int xbq_set_option(const char* name, double value)
     if (!std::strcmp(name, "hist_max_queries")) {
         if (!(value >= 0 && value <= (1 << 20))) return XBQ_EINVAL;
         g_opt.hist_max_queries = static_cast<int>(value);
+        return XBQ_OK;
+    }
+    if (!std::strcmp(name, "refine_growth")) {
+        if (!(value >= 1.25 && value <= 64.0)) return XBQ_EINVAL;
+        g_opt.refine_growth = value;
         return XBQ_OK;
     }
     if (!std::strcmp(name, "kselect_lists_min")) {

@@ -195,6 +195,8 @@ def test_options(L):
         assert L.xbq_set_option(b"selector", sel) == xbq.OK
     assert L.xbq_set_option(b"hist_max_queries", 16) == xbq.OK
     assert L.xbq_set_option(b"kernel", 3) == xbq.EINVAL
+    assert L.xbq_set_option(b"refine_growth", 1.0) == xbq.EINVAL
+    assert L.xbq_set_option(b"refine_growth", 1.5) == xbq.OK
     assert L.xbq_set_option(b"kselect_lists_min", -1) == xbq.EINVAL
     assert L.xbq_set_option(b"kselect_lists_min", 128) == xbq.OK
     base = L.xbq_search_workspace_bytes(100_000, 1000, 128, 4, 10)
