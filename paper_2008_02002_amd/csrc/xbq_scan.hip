@@ -14,8 +14,10 @@
 //   scan_resident  - whole code of the row(s) in registers, all queries stream past it;
 //                    the database is read from memory exactly once per query range.
 //   scan_chunked   - for long codes: the row is processed in chunks of WC words per
-//                    plane against a register tile of kTileQ queries, partial distances
-//                    accumulated per query; the database chunk comes from L2.
+//                    plane against a register tile of kTileQ queries, one running sum per
+//                    query and weight class; the database chunk comes from L2.
+// In threshold mode a launch can also count the passing rows per distance level and can be
+// switched off by a flag in device memory (both used by the whole-list form of Algorithm 1).
 
 #include "xbq_device.h"
 
