@@ -27,6 +27,18 @@ design document):
   * The exported score is S = d (2^Bx - 1)(2^By - 1) - 2 (Xbar (x) Ybar), the
     numerator of Eq. 2 of Section 3.3: larger means more similar.
   * Ties in the top-K go to the lower index; output sorted by (S desc, idx asc).
+  * Algorithm 1 keeps every row within its boundary and is silent about memory.
+    Two bounded forms are stated here because the implementation under test
+    documents them: the first ``limit`` candidates in (distance, row) order
+    (:func:`k_select_candidates`), and a boundary lowered by whole distance
+    units until the candidates fit (:func:`k_select_candidates_by_levels`).
+    Without a limit both are the algorithm as printed.
+
+Every function here is pinned by ``tests/test_oracle_pins.py`` against something
+the paper or the mathematics fixes.  The accuracy *figures* computed with
+:func:`precision_at_k` on the synthetic workloads are parity unpinned: the paper
+prints such figures for its own datasets only; the function itself is pinned by a
+hand-counted case.
 """
 from __future__ import annotations
 
