@@ -195,7 +195,8 @@ int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_byte
  *   "qsplit"  queries per workgroup (0 = automatic)
  *   "selector"          0 = automatic, 1 = threshold filter with growing row groups (many
  *                       queries), 2 = histogram selection (few queries; Section 4.1)
- *   "hist_max_queries"  automatic choice: histogram selection up to this many queries
+ *   "hist_max_queries"  automatic choice: histogram selection up to this many queries (default
+ *                       16), twice as many for k > 128, three times for k > 512
  *   "refine_growth"     the same bound for the bounded candidate search of xbq_search_refine and
  *                       xbq_k_select (default 1.5: safe when the lists reach their bound of 2048 rows;
  *                       2.0 is a few percent faster when they stay well below it and up to

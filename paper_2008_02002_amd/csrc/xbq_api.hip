@@ -129,7 +129,11 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false
     p.total = off;
 
     // histogram selection: eligible for plain top-K when the stored distances stay moderate
-    const bool want = g_opt.selector == 2 || (g_opt.selector == 0 && m <= g_opt.hist_max_queries);
+    // the threshold schedule pays per query for sorting O(k) keys in every row group, the histogram
+    // path does not: its range grows with k (measured on C2: even at 40 queries for k = 100, beyond
+    // 64 for k = 1000)
+    const int64_t hist_limit = static_cast<int64_t>(g_opt.hist_max_queries) * (k > 512 ? 3 : k > 128 ? 2 : 1);
+    const bool want = g_opt.selector == 2 || (g_opt.selector == 0 && m <= hist_limit);
     const int hq = static_cast<int>(m < kHistMaxQueries ? m : kHistMaxQueries);
     if (!refine && !p.dot && !p.mfma && want && m <= p.batch && n * int64_t(4) * hq <= kHistMaxDistBytes) {
         p.hist = true;

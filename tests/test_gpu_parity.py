@@ -409,6 +409,10 @@ def test_automatic_selector_switches_with_query_count():
     gu.assert_same(gu.gpu_search(Xdb, _rand(9, 128, seed=44), 4, 10, 2.0), want_few, "auto, 9 queries")
     Xq = _rand(700, 128, seed=45)
     gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 10, 2.0), gu.oracle_search(Xdb, Xq, 4, 10, 2.0), "auto, 700 queries")
+    # with a large k the histogram selection serves more queries (40 here), and the workspace says so
+    Xq = _rand(40, 128, seed=46)
+    gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 1000, 2.0), gu.oracle_search(Xdb, Xq, 4, 1000, 2.0), "auto, k = 1000")
+    assert xbq.xbq_search_workspace_bytes(40_000, 40, 128, 4, 1000) >= 8 * 40_000 * 4      # stored distances
 
 
 def test_many_queries_cross_the_internal_batch():
