@@ -34,6 +34,8 @@ extern "C" {
 #define XBQ_EUNSUPPORTED (-2)  /* bits, d or layout outside what the kernels cover       */
 #define XBQ_EWORKSPACE   (-3)  /* workspace smaller than xbq_search_workspace_bytes()    */
 #define XBQ_EHIP         (-4)  /* a HIP launch or query failed; see xbq_last_hip_error() */
+#define XBQ_ESTATIC      (-5)  /* xbq_search_static: the request needs more scratch than
+                                  XBQ_STATIC_SCRATCH_BYTES                                */
 
 /* Code layouts (both hold uint32 plane words, W = ceil(d/32) per plane, plane b =
  * bit b of every coordinate's code, coordinate 32w+t at bit t of word w, pad bits 0;
@@ -111,6 +113,23 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
 int xbq_search_asym(const uint32_t* db_codes, int64_t n, int db_bits, const uint32_t* q_codes,
                     int64_t m, int q_bits, int d, int k, int32_t* idx, int32_t* score,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * xbq_search for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and order as xbq_search, without the workspace: the scratch memory is a buffer of
+ * XBQ_STATIC_SCRATCH_BYTES that is part of the library image (every GPU the library runs on
+ * holds one until the process ends).  The call allocates and frees nothing.
+ *   - A request whose xbq_search_workspace_bytes(n, m, d, bits, k) exceeds
+ *     XBQ_STATIC_SCRATCH_BYTES returns XBQ_ESTATIC before anything is enqueued (32 MiB serves,
+ *     e.g., 1 query x 4 M rows, 8 queries x 1 M rows, or 2 000 queries at k = 10 whatever n).
+ *   - All calls on one GPU share that GPU's buffer, which keeps the previous call's contents
+ *     (the kernels clear what they need zeroed): two calls that overlap in time on one GPU --
+ *     different streams, or different threads -- race.  Serialise them on one stream.
+ */
+#define XBQ_STATIC_SCRATCH_BYTES (32u << 20)
+int xbq_search_static(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int64_t m, int d,
+                      int bits, int k, int32_t* idx, int32_t* score, void* stream);
 
 /*
  * Search with the extra-distance candidate list and the exact refine of Algorithm 1

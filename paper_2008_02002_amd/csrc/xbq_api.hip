@@ -13,6 +13,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "xbq_internal.h"
@@ -42,10 +43,39 @@ struct Trace {
 } g_trace;
 constexpr int kTraceMaxLaunches = 4096;
 
+// Scratch of xbq_search_static: the workspace a caller of xbq_search would pass, held by the
+// library instead.  Each device that loads the library holds its own copy of the array at its
+// own address until the process ends.  In host code the name below is only a handle for
+// hipGetSymbolAddress; the address kernels use is looked up once per device (scratch_address).
+static __device__ __align__(256) unsigned char scratch[XBQ_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
 int fail_hip(hipError_t e)
 {
     g_last_hip_error = static_cast<int>(e);
     return XBQ_EHIP;
+}
+
+// Device address of `scratch` on the current device; looked up on the first call per device.
+hipError_t scratch_address(char** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr || reinterpret_cast<uintptr_t>(p) % 256) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<char*>(g_scratch_ptr[dev]);
+    return hipSuccess;
 }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -689,6 +719,7 @@ const char* xbq_strerror(int code)
     case XBQ_EUNSUPPORTED: return "unsupported bits, dimension or layout";
     case XBQ_EWORKSPACE: return "workspace too small";
     case XBQ_EHIP: return "HIP runtime error";
+    case XBQ_ESTATIC: return "request needs more scratch than the built-in buffer of xbq_search_static holds";
     default: return "unknown error code";
     }
 }
@@ -750,6 +781,21 @@ int xbq_search_asym(const uint32_t* db_codes, int64_t n, int db_bits, const uint
     job.d = d; job.k = k; job.extra = -1;
     job.idx = idx; job.score = score;
     return run_search(job, p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+int xbq_search_static(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int64_t m, int d, int bits, int k,
+                      int32_t* idx, int32_t* score, void* stream)
+{
+    if (d < 1 || bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
+    if (!valid_shape(d, bits)) return XBQ_EUNSUPPORTED;
+    if (!valid_search_sizes(n, m, d, bits, k)) return XBQ_EINVAL;
+    if (n == 0 || m == 0) return XBQ_OK;
+    // the size check comes first: a request that cannot fit is refused without any HIP call
+    if (make_plan(n, m, d, bits, k, false).total > static_cast<size_t>(XBQ_STATIC_SCRATCH_BYTES)) return XBQ_ESTATIC;
+    char* ws = nullptr;
+    const hipError_t e = scratch_address(&ws);
+    if (e != hipSuccess) return fail_hip(e);
+    return xbq_search_asym(db_codes, n, bits, q_codes, m, bits, d, k, idx, score, ws, XBQ_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t xbq_search_refine_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int k)

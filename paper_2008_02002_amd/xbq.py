@@ -12,14 +12,15 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libxbq.so")
 
-OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ESTATIC = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 32 << 20
 ROWS, BUNDLE64 = 0, 1
 MAX_BITS, MAX_DIM, MAX_K = 4, 2048, 1024
 REFINE_MAX_CANDIDATES = 2048
 
 EXPORTS = (
     "xbq_version", "xbq_strerror", "xbq_last_hip_error", "xbq_code_bytes", "xbq_encode",
-    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_k_select_workspace_bytes", "xbq_k_select", "xbq_trace_enable", "xbq_trace_read",
+    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_static", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_k_select_workspace_bytes", "xbq_k_select", "xbq_trace_enable", "xbq_trace_read",
     "xbq_probe_out_bytes", "xbq_probe_valu", "xbq_probe_read", "xbq_set_option",
 )
 
@@ -66,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.xbq_search.restype = i32
         L.xbq_search_asym.argtypes = [vp, i64, i32, vp, i64, i32, i32, i32, vp, vp, vp, sz, vp]
         L.xbq_search_asym.restype = i32
+        L.xbq_search_static.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
+        L.xbq_search_static.restype = i32
         L.xbq_search_refine_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
         L.xbq_search_refine_workspace_bytes.restype = sz
         L.xbq_search_refine.argtypes = [vp, vp, i64, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -155,6 +158,16 @@ def xbq_search(db_codes, n: int, q_codes, m: int, d: int, bits: int, k: int, wor
                           ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                           _stream())
     _check(rc, "xbq_search")
+    return idx, score
+
+
+def xbq_search_static(db_codes, n: int, q_codes, m: int, d: int, bits: int, k: int, idx, score):
+    """xbq_search without a workspace and without any allocation: idx and score ([m, k] int32
+    CUDA tensors) come from the caller, the scratch memory is the library's built-in buffer."""
+    rc = lib().xbq_search_static(ctypes.c_void_p(db_codes.data_ptr()), n, ctypes.c_void_p(q_codes.data_ptr()), m,
+                                 d, bits, k, ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(score.data_ptr()),
+                                 _stream())
+    _check(rc, "xbq_search_static")
     return idx, score
 
 
