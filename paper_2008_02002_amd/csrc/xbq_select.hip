@@ -12,6 +12,7 @@
 //                   rows with a running threshold and a bounded LDS buffer (slow, always
 //                   exact, and only ever taken when the row order is adversarial)
 
+#include "xbq_cut.h"
 #include "xbq_device.h"
 
 namespace xbq {
@@ -26,31 +27,40 @@ __device__ __forceinline__ void write_result(const SelectArgs& a, int q, const u
     }
 }
 
+// Number of keys with D <= bound among `have` ascending keys in LDS (a single step in a sorted
+// array).  All threads call this; `scratch` is one LDS word; ends with a barrier.
+__device__ int count_within(const uint64_t* keys, int have, uint32_t bound, int* scratch)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) *scratch = static_cast<uint32_t>(keys[have - 1] >> 32) <= bound ? have : 0;
+    __syncthreads();
+    for (int t = threadIdx.x; t + 1 < have; t += blockDim.x)
+        if (static_cast<uint32_t>(keys[t] >> 32) <= bound && static_cast<uint32_t>(keys[t + 1] >> 32) > bound)
+            *scratch = t + 1;
+    __syncthreads();
+    const int within = *scratch;
+    __syncthreads();
+    return within;
+}
+
 // Store the head of the sorted keys as the query's new list and derive its threshold.
 // Plain top-K: the first k keys; later rows matter only if D < D_k (an equal D loses the tie
 // to the rows already held, which all have lower numbers).  Candidate mode (extra >= 0):
-// every key with D <= D_k + extra, at most keep_max (the best by key); later rows matter if
-// D <= D_k + extra and, once the list is cut, only if they beat its last key.
+// every key with D <= D_k + extra, at most keep_max (the best by key); see candidate_list_cut.
 // `have` sorted keys are in LDS; all threads call this, with a barrier before it.
-__device__ void write_topk(const SelectArgs& a, int q, const uint64_t* keys, int have, int* scratch)
+// thr_before: the threshold the keys were collected under (0xffffffff for the first group).
+__device__ void write_topk(const SelectArgs& a, int q, const uint64_t* keys, int have, int* scratch, uint32_t thr_before)
 {
     const uint32_t dk = static_cast<uint32_t>(keys[a.k - 1] >> 32);
     int keep = a.k;
     if (a.extra >= 0) {
         const uint32_t bound = dk + static_cast<uint32_t>(a.extra);
-        if (threadIdx.x == 0) *scratch = have;                       // all keys within the bound
-        __syncthreads();
-        for (int t = threadIdx.x; t + 1 < have; t += blockDim.x)     // sorted: find the single step
-            if (static_cast<uint32_t>(keys[t] >> 32) <= bound && static_cast<uint32_t>(keys[t + 1] >> 32) > bound)
-                *scratch = t + 1;
-        __syncthreads();
-        const bool cut = *scratch > a.keep_max;                      // more candidates than may be kept
-        keep = cut ? a.keep_max : *scratch;
+        const int within = count_within(keys, have, bound, scratch);
+        const ListCut cut = candidate_list_cut(keys, within, a.keep_max, bound, thr_before);
+        keep = cut.keep;
         if (threadIdx.x == 0) {
             a.len[q] = static_cast<uint32_t>(keep);
-            // a cut list holds the keep_max best keys: a later row gets in only with a smaller
-            // D than the last one kept (an equal D has a higher row number and stays out)
-            a.thr[q] = cut ? static_cast<uint32_t>(keys[keep - 1] >> 32) : bound + 1;
+            a.thr[q] = cut.thr;
             a.cnt[q] = 0;
         }
     } else if (threadIdx.x == 0) {
@@ -75,7 +85,7 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
         keys[t] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
     __syncthreads();
     bitonic_sort_lds(keys, P);
-    write_topk(a, q, keys, a.rows, &scratch);
+    write_topk(a, q, keys, a.rows, &scratch, 0xffffffffu);
 }
 
 // Exact re-score of rows [row_begin, row_end) for one query, starting from its current
@@ -105,23 +115,15 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int capac
             bitonic_sort_lds(keys, P);
             // cut back to what is still of interest; the threshold can only tighten
             const uint32_t dk = static_cast<uint32_t>(keys[a.k - 1] >> 32);
-            const uint32_t now = a.extra >= 0 ? dk + static_cast<uint32_t>(a.extra) + 1 : dk;
-            thr = now < thr ? now : thr;
             int keep = a.k;
             if (a.extra >= 0) {
-                __syncthreads();
-                if (threadIdx.x == 0) *fill = have;
-                __syncthreads();
-                for (int t = threadIdx.x; t + 1 < have; t += blockDim.x)
-                    if (static_cast<uint32_t>(keys[t] >> 32) < thr && static_cast<uint32_t>(keys[t + 1] >> 32) >= thr)
-                        *fill = t + 1;
-                __syncthreads();
-                keep = *fill < a.keep_max ? *fill : a.keep_max;
-                if (*fill > a.keep_max) {
-                    const uint32_t last = static_cast<uint32_t>(keys[keep - 1] >> 32);
-                    thr = last < thr ? last : thr;
-                }
-                __syncthreads();
+                const uint32_t bound = dk + static_cast<uint32_t>(a.extra);
+                const int within = count_within(keys, have, bound, fill);
+                const ListCut cut = candidate_list_cut(keys, within, a.keep_max, bound, thr);
+                keep = cut.keep;
+                thr = cut.thr;
+            } else {
+                thr = dk < thr ? dk : thr;
             }
             if (threadIdx.x == 0) *fill = keep;
         }
@@ -132,7 +134,7 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int capac
     for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
     __syncthreads();
     bitonic_sort_lds(keys, P);
-    write_topk(a, q, keys, have, fill);
+    write_topk(a, q, keys, have, fill, thr);
 }
 
 __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int capacity)
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int ca
         __syncthreads();
         if (c != 0) bitonic_sort_lds(keys, P);
     }
-    write_topk(a, q, keys, total, &fill);
+    write_topk(a, q, keys, total, &fill, a.extra >= 0 ? a.thr[q] : 0xffffffffu);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -237,6 +237,68 @@ def test_refine_on_clustered_rows_and_sorted_rows():
     gu.assert_refined_matches(got, Xs, Xq[:4], D, 10, 50, xbq.REFINE_MAX_CANDIDATES)
 
 
+def _one_bit_rows_at_distances(D, d, rng):
+    """Rows of +-1/sqrt(d) whose one-bit code differs from the all-positive query in exactly
+    D[r] coordinates (Eq. 6 with one plane on each side is the Hamming distance)."""
+    n = len(D)
+    X = np.full((n, d), 1.0, dtype=np.float32)
+    for r in range(n):
+        X[r, rng.choice(d, size=int(D[r]), replace=False)] = -1.0
+    return X / np.float32(np.sqrt(d))
+
+
+def test_cut_candidate_list_keeps_its_ties_through_the_exact_rescan():
+    # One-bit codes, rows ever closer to query 0, massive ties.  With the default schedule the
+    # group of rows 13 824 .. 20 735 overflows the survivor list of query 0 and is rescanned
+    # exactly, starting from a list that was cut at 2048 rows of distance 50.  The rows at 48
+    # and 49 then arrive in an order in which the rescan compacts its buffer while it holds rows
+    # at the threshold distance: the 55 lowest-numbered rows at 49 belong to the first 2048
+    # candidates, and xbq_k_select has to see that the bounded list is not the whole list.
+    rng = np.random.default_rng(41)
+    d, k, extra = 64, 100, 1
+    D0 = np.concatenate([np.full(13_824, 50), np.full(200, 48), np.full(3896, 49), np.full(1793, 48),
+                         np.full(20_736 - 13_824 - 5889, 60)])
+    Xdb = _one_bit_rows_at_distances(D0, d, rng)
+    Xq = np.concatenate([np.full((1, d), 1.0, dtype=np.float32),
+                         rng.choice([-1.0, 1.0], size=(5, d)).astype(np.float32)]) / np.float32(np.sqrt(d))
+    D = gu.oracle_distances(Xdb, Xq, 1, 1, 1.0)
+    assert np.array_equal(D[0], D0)
+    _say("one-bit sorted rows: xbq_search_refine")
+    got = gu.gpu_search_refine(Xdb, Xq, 1, 1, k, extra, 1.0)
+    assert got[2][0] == xbq.REFINE_MAX_CANDIDATES
+    gu.assert_refined_matches(got, Xdb, Xq, D, k, extra, xbq.REFINE_MAX_CANDIDATES, tol=4e-6)
+    try:
+        xbq.xbq_set_option("kselect_lists_min", 0)           # first stage = the bounded candidate search
+        _say("one-bit sorted rows: xbq_k_select")
+        got = gu.gpu_k_select(Xdb, Xq, 1, 1, k, extra, len(Xdb), 1.0)
+    finally:
+        xbq.xbq_set_option("kselect_lists_min", 128)
+    assert got[2][0] == 1993 + 3896
+    gu.assert_refined_matches(got, Xdb, Xq, D, k, extra, len(Xdb), tol=4e-6, by_levels=True)
+
+
+def test_candidate_search_on_sorted_tie_heavy_rows():
+    rng = np.random.default_rng(43)
+    d = 48
+    for trial, (k, extra) in enumerate(((10, 0), (100, 2), (1000, 1))):
+        D0 = np.sort(rng.integers(0, d + 1, size=30_000))[::-1]
+        if trial == 1:
+            D0 = np.concatenate([np.sort(c)[::-1] for c in np.array_split(rng.permutation(D0), 5)])
+        Xdb = _one_bit_rows_at_distances(D0, d, rng)
+        Xq = np.concatenate([np.full((1, d), 1.0, dtype=np.float32),
+                             rng.choice([-1.0, 1.0], size=(3, d)).astype(np.float32)]) / np.float32(np.sqrt(d))
+        D = gu.oracle_distances(Xdb, Xq, 1, 1, 1.0)
+        _say(f"sorted tie-heavy rows k={k} extra={extra}")
+        got = gu.gpu_search_refine(Xdb, Xq, 1, 1, k, extra, 1.0)
+        gu.assert_refined_matches(got, Xdb, Xq, D, k, extra, xbq.REFINE_MAX_CANDIDATES, tol=4e-6)
+        try:
+            xbq.xbq_set_option("kselect_lists_min", 0)
+            got = gu.gpu_k_select(Xdb, Xq, 1, 1, k, extra, 20_000, 1.0)
+        finally:
+            xbq.xbq_set_option("kselect_lists_min", 128)
+        gu.assert_refined_matches(got, Xdb, Xq, D, k, extra, 20_000, tol=4e-6, by_levels=True)
+
+
 KSELECT = [
     # n, d, m, q_bits, db_bits, k, extra, max_candidates
     (6000, 128, 20, 4, 4, 10, 0, 6000),            # nothing cut: Algorithm 1 as printed
