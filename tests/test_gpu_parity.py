@@ -58,6 +58,22 @@ def test_encode_matches_oracle(bits, n, d):
         assert (got_b[n:] == 0).all()                      # rows past n in the last bundle are zero words
 
 
+def test_encode_bit_order_against_hand_typed_words(golden_dir):
+    """Both code layouts of the library against the plane words typed by hand in the golden file
+    (coordinate 0 at the least significant end of a plane; Section 3.3)."""
+    from tests.test_oracle_pins import _read_bit_order_golden
+    d, B, row, want, _ = _read_bit_order_golden(golden_dir)
+    x = ((7 - 2 * row.astype(np.int64)) / 8.0).astype(np.float32)
+    X = np.stack([x, x[::-1], x])                      # the hand-typed row first and last, another one between
+    W = (d + 31) // 32
+    rows = gu.gpu_encode(X, B, 1.0, xbq.ROWS).reshape(3, B, W)
+    assert np.array_equal(rows[0], want) and np.array_equal(rows[2], want)
+    assert not np.array_equal(rows[1], want)
+    bundle = gu.gpu_encode(X, B, 1.0, xbq.BUNDLE64).reshape(1, B, W, 64)
+    assert np.array_equal(bundle[0, :, :, 0], want) and np.array_equal(bundle[0, :, :, 2], want)
+    assert np.array_equal(bundle[0, :, :, 1], rows[1]) and not bundle[0, :, :, 3:].any()
+
+
 @pytest.mark.parametrize("bits", [1, 2, 3, 4])
 def test_encode_cell_boundaries_denormals_and_saturation(bits):
     pts = []

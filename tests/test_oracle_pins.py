@@ -312,6 +312,51 @@ def test_precision_at_k():
     assert np.allclose(sim[:, 0], 1.0, atol=1e-6)
 
 
+def _read_bit_order_golden(golden_dir):
+    d = B = None
+    codes, words, ints = {}, {}, {}
+    for line in open(os.path.join(golden_dir, "plane_bit_order.txt")):
+        f = line.split()
+        if not f or f[0].startswith("#"):
+            continue
+        if f[0] == "dimension":
+            d = int(f[1])
+        elif f[0] == "bits":
+            B = int(f[1])
+        elif f[0] == "code":
+            codes[int(f[1])] = int(f[2])
+        elif f[0] == "word":
+            words[(int(f[1]), int(f[2]))] = int(f[3], 16)
+        elif f[0] == "plane_integer":
+            ints[int(f[1])] = int(f[2], 16)
+    row = np.zeros(d, dtype=np.uint8)
+    for k, c in codes.items():
+        row[k] = c
+    W = (d + 31) // 32
+    want = np.array([[words[(b, w)] for w in range(W)] for b in range(B)], dtype=np.uint32)
+    return d, B, row, want, [ints[b] for b in range(B)]
+
+
+def test_plane_bit_order_against_hand_typed_words(golden_dir):
+    """Coordinate 0 sits at the least significant end of a plane (Section 3.3, the equation that
+    defines xhat_b); the words are typed by hand in the golden file, so a reversed or permuted
+    bit order in any of the three packers fails here."""
+    from oracle import scale as oc
+    d, B, row, want, ints = _read_bit_order_golden(golden_dir)
+    assert od.plane_ints(row, B) == ints
+    assert np.array_equal(od.pack_planes(row[None, :], B)[0], want)
+    assert np.array_equal(oc.planes_as_u32(oc.pack(row[None, :], B), d)[0], want)
+    # through the quantizer as well: cell centres give back the codes
+    x = ((7 - 2 * row.astype(np.int64)) / 8.0).astype(np.float32)
+    assert np.array_equal(od.encode(x[None, :], B), row[None, :])
+    assert np.array_equal(oc.planes_as_u32(oc.encode(x[None, :], B, 1.0), d)[0], want)
+    # a second row in the same call must not disturb the first (row stride of the packers)
+    two = np.stack([row, row[::-1]])
+    assert np.array_equal(od.pack_planes(two, B)[0], want)
+    assert np.array_equal(oc.planes_as_u32(oc.pack(two, B), d)[0], want)
+    assert od.plane_ints(row[::-1], B) != ints                                # the case is not symmetric
+
+
 # ------------------------------------------------------------- Algorithm 1 (K-Select)
 def _kselect_case(seed, n=400, d=24, m=5, Bq=4, Bd=3):
     rng = np.random.default_rng(seed)
@@ -339,7 +384,20 @@ def test_candidates_are_exactly_rows_within_the_bound():
             assert sorted(L.tolist()) == [i for i in range(D.shape[1]) if D[0, i] <= bound]
             keys = [(int(D[0, i]), int(i)) for i in L]
             assert keys == sorted(keys) and len(L) >= K
-            assert od.k_select_candidates(D[0], K, extra, limit=K).tolist() == L[:K].tolist()
+
+
+def test_candidates_with_a_limit_hand_case():
+    # 10 rows, K = 3.  By hand: sorted (D, row) = (1,r4) (2,r0) (2,r7) (3,r2) (3,r5) (3,r9) (5,r1) (6,r3) (6,r8) (9,r6);
+    # the 3rd smallest distance is 2; with extra 1 the boundary is 3 and six rows lie within it
+    D = np.array([2, 5, 3, 6, 1, 3, 9, 2, 6, 3])
+    f = od.k_select_candidates
+    assert f(D, 3, 1).tolist() == [4, 0, 7, 2, 5, 9]
+    assert f(D, 3, 1, limit=6).tolist() == [4, 0, 7, 2, 5, 9]
+    assert f(D, 3, 1, limit=5).tolist() == [4, 0, 7, 2, 5]        # cut inside the level D = 3: lower rows stay
+    assert f(D, 3, 1, limit=4).tolist() == [4, 0, 7, 2]
+    assert f(D, 3, 1, limit=3).tolist() == [4, 0, 7]
+    assert f(D, 3, 4, limit=8).tolist() == [4, 0, 7, 2, 5, 9, 1, 3]   # boundary 6: nine rows, the first eight kept
+    assert f(D, 1, 0, limit=1).tolist() == [4]
 
 
 def test_k_select_with_unbounded_extra_is_exact_search():
