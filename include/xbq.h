@@ -79,10 +79,12 @@ int xbq_encode(const float* X, int64_t n, int d, int bits, float scale, int layo
                uint32_t* codes, void* stream);
 
 /* Bytes of scratch xbq_search needs for these sizes; 0 if arguments are invalid.  Depends on
- * the options in force (xbq_set_option).  With more than a handful of queries it depends on
- * n only through min(n, small constant) and on m only up to an internal query batch (below
- * ~0.3 GiB); with few queries (histogram selection) it holds 4 bytes per (query, row) for up
- * to 8 queries, at most 1 GiB; the cross-check kernel adds a copy of the database codes. */
+ * the process-wide options in force (xbq_set_option; xbq_search_workspace_bytes_ex takes them as
+ * an argument instead).  With more than a handful of queries it depends on n only through
+ * min(n, small constant) and on m only up to an internal query batch (below ~0.3 GiB); with few
+ * queries it holds per-workgroup candidate lists (at most ~25 MB), or for k > 256 four bytes per
+ * (query, row) for up to 8 queries, at most 1 GiB; the cross-check kernels add a copy of the
+ * database codes. */
 size_t xbq_search_workspace_bytes(int64_t n, int64_t m, int d, int bits, int k);
 
 /*
@@ -113,6 +115,33 @@ int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int
 int xbq_search_asym(const uint32_t* db_codes, int64_t n, int db_bits, const uint32_t* q_codes,
                     int64_t m, int q_bits, int d, int k, int32_t* idx, int32_t* score,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same search with its schedule options passed per call instead of taken from the
+ * process-wide defaults (xbq_set_option): two callers with different options can coexist, and
+ * the workspace a call needs is a function of its arguments alone.  Code widths as for
+ * xbq_search_asym.  options == NULL means the process-wide defaults in force when the call
+ * starts (every entry point takes one snapshot of them).  A field out of its range, or a
+ * struct_bytes that is not sizeof(xbq_options), gives XBQ_EINVAL (workspace query: 0).
+ * Fields: see xbq_set_option below; xbq_options_default fills in the built-in defaults.
+ */
+typedef struct xbq_options {
+    uint32_t struct_bytes;       /* sizeof(xbq_options) */
+    int32_t selector;
+    int32_t kernel;
+    int32_t first;
+    int32_t qsplit;
+    int32_t hist_max_queries;
+    int32_t kselect_lists_min;
+    int32_t local_groups;
+    double growth;
+    double refine_growth;
+} xbq_options;
+void xbq_options_default(xbq_options* options);
+size_t xbq_search_workspace_bytes_ex(int64_t n, int64_t m, int d, int q_bits, int k, const xbq_options* options);
+int xbq_search_ex(const uint32_t* db_codes, int64_t n, int db_bits, const uint32_t* q_codes, int64_t m,
+                  int q_bits, int d, int k, int32_t* idx, int32_t* score, void* workspace,
+                  size_t workspace_bytes, const xbq_options* options, void* stream);
 
 /*
  * xbq_search for callers that cannot allocate device memory or pass a workspace: code under
@@ -181,7 +210,8 @@ int xbq_k_select(const float* X_db, const uint32_t* db_codes, int64_t n, int db_
  * kernel (the XOR + population-count loop) with HIP events on the caller's stream.
  * xbq_trace_read waits for those events, returns the summed kernel time, the number of
  * launches and the number of (query, row) pairs they scored, and clears the record.
- * Not thread safe; at most 4096 launches are recorded between reads.
+ * The record belongs to the calling thread: enable, search and read on the same thread; other
+ * threads are not traced and not disturbed.  At most 4096 launches are recorded between reads.
  */
 int xbq_trace_enable(int on);
 int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
@@ -207,15 +237,19 @@ int xbq_probe_valu(uint32_t* out, size_t out_bytes, uint32_t seed, int iters, do
 int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_bytes, void* stream);
 
 /*
- * Tuning knobs (process-wide, host side only):
+ * Tuning knobs, host side only.  xbq_set_option changes the process-wide defaults (thread
+ * safe; a call already running keeps the snapshot it took); xbq_search_ex takes them per call.
  *   "growth"  upper bound on rows-after-a-group / rows-before-it (default 4.0; lowered
  *             automatically for large k so the survivor lists stay short)
  *   "first"   rows scored densely before any threshold exists (default 1024)
  *   "qsplit"  queries per workgroup (0 = automatic)
  *   "selector"          0 = automatic, 1 = threshold filter with growing row groups (many
- *                       queries), 2 = histogram selection (few queries; Section 4.1)
- *   "hist_max_queries"  automatic choice: histogram selection up to this many queries (default
+ *                       queries), 2 = histogram selection over stored distances (Section 4.1),
+ *                       3 = the same selection done per workgroup while the rows stream, nothing
+ *                       stored (k <= 256; the automatic choice for few queries)
+ *   "hist_max_queries"  automatic choice: few-query selection up to this many queries (default
  *                       16), twice as many for k > 128, three times for k > 512
+ *   "local_groups"      selector 3: most pieces the rows are split into (1..1024, default 256: one per compute unit)
  *   "refine_growth"     the same bound for the bounded candidate search of xbq_search_refine and
  *                       xbq_k_select (default 1.5: safe when the lists reach their bound of 2048 rows;
  *                       2.0 is a few percent faster when they stay well below it and up to

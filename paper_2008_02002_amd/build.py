@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libxbq.so")
 SOURCES = ["xbq_api.hip", "xbq_scan.hip", "xbq_select.hip", "xbq_encode.hip", "xbq_hist.hip", "xbq_dot.hip", "xbq_mfma.hip",
-           "xbq_probe.hip", "xbq_kselect.hip"]
+           "xbq_probe.hip", "xbq_kselect.hip", "xbq_local.hip"]
 # Denormals are kept (a flushed negative denormal would land in the wrong sign cell) and
 # floating-point contraction is off so the scaling multiply rounds exactly once.
 FLAGS = [

@@ -24,23 +24,65 @@ using namespace xbq;
 
 thread_local int g_last_hip_error = 0;
 
+// The schedule knobs of one call.  Every entry point takes a snapshot when it starts (of the
+// caller's xbq_options, or of the process-wide defaults behind xbq_set_option) and passes it
+// down: nothing below reads shared mutable state.
 struct Options {
     double growth = 4.0;
     int first = 1024;
     int qsplit = 0;
-    int selector = 0;                // 0 automatic, 1 threshold filter, 2 histogram
-    int hist_max_queries = 16;       // automatic choice: histogram selection up to this many queries
+    int selector = 0;                // 0 automatic, 1 threshold filter, 2 histogram (distances stored), 3 local selection
+    int hist_max_queries = 16;       // automatic choice: few-query selection up to this many queries
     int kernel = 0;                  // 0 XOR + population count; cross-checks: 1 packed 4-bit dots, 2 int8 MFMA
     double refine_growth = 1.5;      // growth bound of the bounded candidate search
     int kselect_lists_min = 128;     // xbq_k_select: batches of at least this many queries start from bounded lists
-} g_opt;
+    int local_groups = 256;          // local selection: most pieces (workgroups) the rows are split into
+};
 
+std::mutex g_opt_mutex;
+Options g_opt;                       // process-wide defaults, guarded by g_opt_mutex
+
+Options default_options()
+{
+    std::lock_guard<std::mutex> lock(g_opt_mutex);
+    return g_opt;
+}
+
+// Range check of one knob; shared by xbq_set_option and the xbq_options of the _ex calls.
+bool set_knob(Options& o, const char* name, double value)
+{
+    if (!std::strcmp(name, "growth")) { if (!(value >= 1.25 && value <= 64.0)) return false; o.growth = value; return true; }
+    if (!std::strcmp(name, "first")) { if (!(value >= 64 && value <= kSortCap)) return false; o.first = static_cast<int>(value); return true; }
+    if (!std::strcmp(name, "kernel")) { if (!(value == 0 || value == 1 || value == 2)) return false; o.kernel = static_cast<int>(value); return true; }
+    if (!std::strcmp(name, "selector")) { if (!(value == 0 || value == 1 || value == 2 || value == 3)) return false; o.selector = static_cast<int>(value); return true; }
+    if (!std::strcmp(name, "hist_max_queries")) { if (!(value >= 0 && value <= (1 << 20))) return false; o.hist_max_queries = static_cast<int>(value); return true; }
+    if (!std::strcmp(name, "refine_growth")) { if (!(value >= 1.25 && value <= 64.0)) return false; o.refine_growth = value; return true; }
+    if (!std::strcmp(name, "kselect_lists_min")) { if (!(value >= 0 && value <= (1 << 20))) return false; o.kselect_lists_min = static_cast<int>(value); return true; }
+    if (!std::strcmp(name, "qsplit")) { if (!(value >= 0 && value <= 65536)) return false; o.qsplit = static_cast<int>(value); return true; }
+    if (!std::strcmp(name, "local_groups")) { if (!(value >= 1 && value <= kLocalMaxGroups)) return false; o.local_groups = static_cast<int>(value); return true; }
+    return false;
+}
+
+// The options of an _ex call: nullptr = the process-wide defaults.  False if a field is out of range.
+bool options_from(const xbq_options* in, Options& o)
+{
+    if (in == nullptr) { o = default_options(); return true; }
+    if (in->struct_bytes != sizeof(xbq_options)) return false;
+    o = Options();
+    return set_knob(o, "growth", in->growth) && set_knob(o, "first", in->first) && set_knob(o, "qsplit", in->qsplit) &&
+           set_knob(o, "selector", in->selector) && set_knob(o, "hist_max_queries", in->hist_max_queries) &&
+           set_knob(o, "kernel", in->kernel) && set_knob(o, "refine_growth", in->refine_growth) &&
+           set_knob(o, "kselect_lists_min", in->kselect_lists_min) && set_knob(o, "local_groups", in->local_groups);
+}
+
+// Scan timing record of xbq_trace_*: one per calling thread.
 struct Trace {
     bool on = false;
     std::vector<hipEvent_t> ev;      // pairs: start, stop
     int used = 0;                    // events used
     double pairs = 0;
-} g_trace;
+};
+thread_local Trace g_trace;
 constexpr int kTraceMaxLaunches = 4096;
 
 // Scratch of xbq_search_static: the workspace a caller of xbq_search would pass, held by the
@@ -108,15 +150,24 @@ struct Plan {
     int hist_wc = 0, hist_nchunks = 0, hist_shift = 0;
     size_t hoff_q = 0, hoff_zero = 0, hoff_dist = 0, hoff_cand = 0;
     size_t zero_words = 0;               // hist + cand_cnt, cleared in one go
+    // local selection (few queries, nothing stored; aliases the regions above as well)
+    bool local = false;
+    int local_cap = 0, local_mq = 0, local_groups = 0, local_shift2 = 0;
+    int64_t local_bpg = 0;               // bundles per piece
+    size_t loff_q = 0, loff_counts = 0, loff_lists = 0;
     size_t total = 0;
 };
 
 constexpr int64_t kHistMaxDistBytes = int64_t(1) << 30;   // stored distances of one pass
+constexpr int kLocalMaxK = 256;      // local selection keeps lists of 8 k keys per query in LDS
 
 constexpr int kRefineKeep = 2048;    // candidate bound of the refine path
 constexpr int kRefineCap = 2048;     // survivor list of the refine path (keep + cap <= kSortCap)
 
-Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false)
+// keep_dist: the caller reads the stored distances of the histogram selection afterwards
+// (xbq_k_select with few queries), so the few-query path must be the one that stores them.
+Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, bool refine = false,
+               bool keep_dist = false)
 {
     Plan p;
     p.W = words32(d);
@@ -125,7 +176,7 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false
         p.nchunks = (p.W + p.wc - 1) / p.wc;
     }
     const int kpad = next_pow2(k);
-    int first = g_opt.first > 4 * kpad ? g_opt.first : 4 * kpad;
+    int first = o.first > 4 * kpad ? o.first : 4 * kpad;
     if (first > kSortCap) first = kSortCap;
     first = first / kLanes * kLanes;
     p.first = static_cast<int>(n < first ? n : first);
@@ -143,14 +194,14 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false
     p.off_dense = off; off = align_up(off + b * static_cast<size_t>(p.first) * sizeof(uint32_t), 256);
     p.off_q = off;
     if (p.wc) off = align_up(off + b * p.nchunks * bits * p.wc * sizeof(uint32_t), 256);
-    if (g_opt.kernel == 1 && p.wc == 0) {
+    if (o.kernel == 1 && p.wc == 0) {
         p.dot = true;
         const size_t wd = 4u * p.W;
         p.off_qn = off;   off = align_up(off + b * wd * sizeof(uint32_t), 256);
         p.off_qsum = off; off = align_up(off + b * sizeof(int32_t), 256);
         p.off_dbn = off;  off = align_up(off + static_cast<size_t>((n + kLanes - 1) / kLanes) * kLanes * wd * sizeof(uint32_t), 256);
     }
-    if (g_opt.kernel == 2 && p.wc == 0) {
+    if (o.kernel == 2 && p.wc == 0) {
         p.mfma = true;
         const size_t row_bytes = 32u * p.W;
         p.off_qb = off;  off = align_up(off + (b + 31) / 32 * 32 * row_bytes, 256);
@@ -162,14 +213,40 @@ Plan make_plan(int64_t n, int64_t m, int d, int bits, int k, bool refine = false
     // the threshold schedule pays per query for sorting O(k) keys in every row group, the histogram
     // path does not: its range grows with k (measured on C2: even at 40 queries for k = 100, beyond
     // 64 for k = 1000)
-    const int64_t hist_limit = static_cast<int64_t>(g_opt.hist_max_queries) * (k > 512 ? 3 : k > 128 ? 2 : 1);
-    const bool want = g_opt.selector == 2 || (g_opt.selector == 0 && m <= hist_limit);
+    const int64_t hist_limit = static_cast<int64_t>(o.hist_max_queries) * (k > 512 ? 3 : k > 128 ? 2 : 1);
+    const bool few = o.selector == 0 && m <= hist_limit;
+    const int64_t dmax = static_cast<int64_t>(d) * ((1 << bits) - 1) * ((1 << bits) - 1);
+    // local selection: the default for few queries; its lists live in LDS, which bounds k
+    const bool want_local = (o.selector == 3 || (few && !keep_dist)) && k <= kLocalMaxK;
+    if (!refine && !p.dot && !p.mfma && want_local && m <= p.batch) {
+        p.local = true;
+        p.local_cap = next_pow2(8 * k > 1024 ? 8 * k : 1024);
+        p.local_mq = kLocalMaxQueries;
+        while (p.local_mq > 1 && local_lds_bytes(p.local_mq, p.local_cap) > 64 * 1024) --p.local_mq;
+        if (m < p.local_mq) p.local_mq = static_cast<int>(m);
+        const int64_t nbundles = (n + kLanes - 1) / kLanes;
+        int64_t bpg = (nbundles + o.local_groups - 1) / o.local_groups;
+        bpg = (bpg + 15) / 16 * 16;                      // whole steps of 16 wavefronts
+        p.local_bpg = bpg;
+        p.local_groups = static_cast<int>((nbundles + bpg - 1) / bpg);
+        p.hist_wc = p.wc ? p.wc : p.W;
+        p.hist_nchunks = p.wc ? p.nchunks : 1;
+        while ((dmax >> p.hist_shift) >= kHistBins) ++p.hist_shift;
+        while ((dmax >> p.local_shift2) >= 4096) ++p.local_shift2;
+        size_t h = 0;
+        p.loff_q = h;
+        if (p.wc) h = align_up(h + b * p.nchunks * bits * p.wc * sizeof(uint32_t), 256);
+        p.loff_counts = h; h = align_up(h + static_cast<size_t>(p.local_mq) * p.local_groups * sizeof(uint32_t), 256);
+        p.loff_lists = h;  h = align_up(h + static_cast<size_t>(p.local_mq) * p.local_groups * p.local_cap * sizeof(uint64_t), 256);
+        if (h > p.total) p.total = h;
+        return p;
+    }
+    const bool want = o.selector == 2 || (o.selector == 3 && k > kLocalMaxK) || few;
     const int hq = static_cast<int>(m < kHistMaxQueries ? m : kHistMaxQueries);
     if (!refine && !p.dot && !p.mfma && want && m <= p.batch && n * int64_t(4) * hq <= kHistMaxDistBytes) {
         p.hist = true;
         p.hist_wc = p.wc ? p.wc : p.W;
         p.hist_nchunks = p.wc ? p.nchunks : 1;
-        const int64_t dmax = static_cast<int64_t>(d) * ((1 << bits) - 1) * ((1 << bits) - 1);
         while ((dmax >> p.hist_shift) >= kHistBins) ++p.hist_shift;
         size_t h = 0;
         p.hoff_q = h;
@@ -194,9 +271,9 @@ bool valid_search_sizes(int64_t n, int64_t m, int d, int bits, int k)
 }
 
 // Queries per workgroup for a group of `bundles` bundles.
-int choose_qsplit(int64_t bundles, int rows_per_lane, int m, int tile)
+int choose_qsplit(const Options& o, int64_t bundles, int rows_per_lane, int m, int tile)
 {
-    if (g_opt.qsplit > 0) return (g_opt.qsplit + tile - 1) / tile * tile;
+    if (o.qsplit > 0) return (o.qsplit + tile - 1) / tile * tile;
     const int64_t waves = (bundles + rows_per_lane - 1) / rows_per_lane;
     int64_t ranges = (32768 + waves - 1) / waves;            // aim for >= 32k wavefronts
     const int64_t min_ranges = (m + 127) / 128;               // at most 128 queries per workgroup
@@ -336,7 +413,57 @@ int run_hist_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s
     return XBQ_OK;
 }
 
-int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
+// Local selection: queries in passes of p.local_mq, two launches per pass, nothing cleared.
+int run_local_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
+{
+    const int64_t m = job.m;
+    const uint32_t* q_all = job.q_codes;
+    if (p.wc) {                                          // long codes: chunk-major padded query copy
+        uint32_t* qc = reinterpret_cast<uint32_t*>(ws + p.loff_q);
+        const hipError_t e = launch_repack_queries(job.q_codes, static_cast<int>(m), job.q_bits, p.W, p.wc, p.nchunks, qc, s);
+        if (e != hipSuccess) return fail_hip(e);
+        q_all = qc;
+    }
+    const int64_t q_stride = static_cast<int64_t>(p.hist_nchunks) * job.q_bits * p.hist_wc;
+    for (int64_t qb = 0; qb < m; qb += p.local_mq) {
+        LocalArgs la{};
+        la.db = job.db_codes;
+        la.n = job.n;
+        la.q = q_all + qb * q_stride;
+        la.m = static_cast<int>(m - qb < p.local_mq ? m - qb : p.local_mq);
+        la.q_bits = job.q_bits;
+        la.db_bits = job.db_bits;
+        la.W = p.W;
+        la.wc = p.hist_wc;
+        la.nchunks = p.hist_nchunks;
+        la.k = job.k;
+        la.d = job.d;
+        la.shift = p.hist_shift;
+        la.shift2 = p.local_shift2;
+        la.cap = p.local_cap;
+        la.groups = p.local_groups;
+        la.bundles_per_group = p.local_bpg;
+        la.lists = reinterpret_cast<uint64_t*>(ws + p.loff_lists);
+        la.counts = reinterpret_cast<uint32_t*>(ws + p.loff_counts);
+        la.idx = job.idx + qb * job.k;
+        la.score = job.score + qb * job.k;
+        const bool rec = g_trace.on && g_trace.used + 2 <= static_cast<int>(g_trace.ev.size());
+        hipError_t e;
+        if (rec && (e = hipEventRecord(g_trace.ev[g_trace.used], s)) != hipSuccess) return fail_hip(e);
+        e = launch_scan_local(la, s);
+        if (e != hipSuccess) return fail_hip(e);
+        if (rec) {
+            if ((e = hipEventRecord(g_trace.ev[g_trace.used + 1], s)) != hipSuccess) return fail_hip(e);
+            g_trace.used += 2;
+            g_trace.pairs += static_cast<double>(job.n) * la.m;
+        }
+        e = launch_local_finish(la, s);
+        if (e != hipSuccess) return fail_hip(e);
+    }
+    return XBQ_OK;
+}
+
+int run_search(const Options& o, const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
 {
     const uint32_t* db_codes = job.db_codes;
     const uint32_t* q_codes = job.q_codes;
@@ -346,6 +473,7 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
     const int rpl_max = (p.wc == 0 && db_bits * p.W <= 16) ? 2 : 1;
     const int tile = p.wc ? kTileQ : 1;
 
+    if (p.local && !refine) return run_local_search(job, p, ws, s);
     if (p.hist && !refine) return run_hist_search(job, p, ws, s);
     if (p.dot) {
         const hipError_t e = launch_nibbles_db(db_codes, n, d, db_bits, reinterpret_cast<uint32_t*>(ws + p.off_dbn), s);
@@ -453,7 +581,7 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             sa.row_end = seen;
             const int64_t bundles = (seen + kLanes - 1) / kLanes;
             sa.rows_per_lane = 1;
-            sa.qsplit = choose_qsplit(bundles, 1, mb, tile);
+            sa.qsplit = choose_qsplit(o, bundles, 1, mb, tile);
             da.row_begin = sa.row_begin; da.row_end = sa.row_end; da.rows_per_lane = 1; da.qsplit = sa.qsplit;
             fa.row_begin = sa.row_begin; fa.row_end = sa.row_end;
             hipError_t e = p.mfma ? traced_scan_mfma(fa, true, s) : p.dot ? traced_scan_dot(da, true, s) : traced_scan(sa, true, s);
@@ -469,8 +597,8 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             // expected survivors per query in a group are about k * (growth - 1): keep them
             // at a third of the list capacity at most
             double growth = 1.0 + static_cast<double>(p.cap) / (3.0 * k);
-            if (growth > g_opt.growth) growth = g_opt.growth;
-            if (refine && growth > g_opt.refine_growth) growth = g_opt.refine_growth;   // the kept list may be as long as the survivor list
+            if (growth > o.growth) growth = o.growth;
+            if (refine && growth > o.refine_growth) growth = o.refine_growth;   // the kept list may be as long as the survivor list
             int64_t size = static_cast<int64_t>(std::ceil(static_cast<double>(seen) * (growth - 1.0)));
             size = (size + 511) / 512 * 512;
             int64_t end = seen + size;
@@ -479,7 +607,7 @@ int run_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
             sa.row_end = end;
             const int64_t bundles = (end - seen + kLanes - 1) / kLanes;
             sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
-            sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, tile);
+            sa.qsplit = choose_qsplit(o, bundles, sa.rows_per_lane, mb, tile);
             da.row_begin = seen; da.row_end = end; da.rows_per_lane = sa.rows_per_lane; da.qsplit = sa.qsplit;
             fa.row_begin = seen; fa.row_end = end;
             hipError_t e = p.mfma ? traced_scan_mfma(fa, false, s) : p.dot ? traced_scan_dot(da, false, s) : traced_scan(sa, false, s);
@@ -535,14 +663,14 @@ struct KPlan {
 // The first stage of a batch of mb queries and its workspace: the plain search (few = true) for
 // few queries, where the longer schedule of the bounded candidate search costs more than the
 // collecting scan it may save; else the bounded candidate search.
-Plan first_stage_plan(int64_t n, int64_t mb, int d, int q_bits, int k, bool& few)
+Plan first_stage_plan(const Options& o, int64_t n, int64_t mb, int d, int q_bits, int k, bool& few)
 {
-    const Plan plain = make_plan(n, mb, d, q_bits, k, false);
-    few = plain.hist || mb < g_opt.kselect_lists_min;
-    return few ? plain : make_plan(n, mb, d, q_bits, k, true);
+    const Plan plain = make_plan(o, n, mb, d, q_bits, k, false, true);
+    few = plain.hist || plain.local || mb < o.kselect_lists_min;
+    return few ? plain : make_plan(o, n, mb, d, q_bits, k, true);
 }
 
-KPlan make_kplan(int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_candidates, int extra)
+KPlan make_kplan(const Options& o, int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_candidates, int extra)
 {
     KPlan kp;
     kp.cap = static_cast<int>(max_candidates < n ? max_candidates : n);
@@ -551,10 +679,10 @@ KPlan make_kplan(int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_can
     if (batch > 8192) batch = 8192;
     kp.batch = m < batch ? m : batch;
     bool few = false;
-    const Plan whole = first_stage_plan(n, kp.batch, d, q_bits, k, few);
+    const Plan whole = first_stage_plan(o, n, kp.batch, d, q_bits, k, few);
     kp.inner = whole.total;
     if (m % kp.batch) {                                   // a short last batch may take the few-query path
-        const size_t t = first_stage_plan(n, m % kp.batch, d, q_bits, k, few).total;
+        const size_t t = first_stage_plan(o, n, m % kp.batch, d, q_bits, k, few).total;
         if (t > kp.inner) kp.inner = t;
     }
     int parts = kp.batch >= 1024 ? 1 : static_cast<int>((1024 + kp.batch - 1) / kp.batch);
@@ -581,7 +709,7 @@ KPlan make_kplan(int64_t n, int64_t m, int d, int q_bits, int k, int64_t max_can
     return kp;
 }
 
-int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
+int run_k_select(const Options& o, const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
 {
     const int64_t n = job.n, m = job.m;
     const int d = job.d, k = job.k, W = words32(d);
@@ -589,7 +717,7 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
         const int mb = static_cast<int>(m - qb < kp.batch ? m - qb : kp.batch);
         const uint32_t* q_rows = job.q_codes + qb * (static_cast<int64_t>(job.q_bits) * W);
         bool few = false;
-        const Plan p = first_stage_plan(n, mb, d, job.q_bits, k, few);
+        const Plan p = first_stage_plan(o, n, mb, d, job.q_bits, k, few);
         if (p.total > kp.inner) return XBQ_EWORKSPACE;    // cannot happen: make_kplan took the larger of the two
 
         KSelectArgs ka{};
@@ -610,7 +738,7 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
             ka.len1 = reinterpret_cast<const uint32_t*>(ws + p.off_len);
             ka.keep1 = p.keep_max;
         }
-        const int rc = run_search(first, p, ws, s);
+        const int rc = run_search(o, first, p, ws, s);
         if (rc != XBQ_OK) return rc;
 
         ka.db = job.db_codes;
@@ -685,7 +813,7 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
         const int64_t bundles = (n + kLanes - 1) / kLanes;
         const int rpl_max = (p.wc == 0 && job.db_bits * W <= 16) ? 2 : 1;
         sa.rows_per_lane = (rpl_max == 2 && bundles >= 4096) ? 2 : 1;
-        sa.qsplit = choose_qsplit(bundles, sa.rows_per_lane, mb, p.wc ? kTileQ : 1);
+        sa.qsplit = choose_qsplit(o, bundles, sa.rows_per_lane, mb, p.wc ? kTileQ : 1);
         sa.levels = ka.levels;
         sa.level_base = ka.dk;
         sa.level_stride = job.extra + 2;
@@ -703,6 +831,31 @@ int run_k_select(const SearchJob& job, const KPlan& kp, char* ws, hipStream_t s)
         if (e != hipSuccess) return fail_hip(e);
     }
     return XBQ_OK;
+}
+
+// xbq_search, xbq_search_asym, xbq_search_ex and xbq_search_static after their options are fixed.
+int search_with(const Options& o, const uint32_t* db_codes, int64_t n, int db_bits, const uint32_t* q_codes, int64_t m,
+                int q_bits, int d, int k, int32_t* idx, int32_t* score, void* workspace, size_t workspace_bytes,
+                void* stream)
+{
+    if (d < 1 || db_bits < 1 || q_bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
+    if (!valid_shape(d, db_bits) || !valid_shape(d, q_bits) || !scan_supports_bits(q_bits, db_bits))
+        return XBQ_EUNSUPPORTED;
+    if (!valid_search_sizes(n, m, d, q_bits, k)) return XBQ_EINVAL;
+    if (n == 0 || m == 0) return XBQ_OK;
+    if (!db_codes || !q_codes || !idx || !score || !workspace) return XBQ_EINVAL;
+    if (reinterpret_cast<uintptr_t>(db_codes) % 4 || reinterpret_cast<uintptr_t>(q_codes) % 4 ||
+        reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(score) % 4 ||
+        reinterpret_cast<uintptr_t>(workspace) % 256)
+        return XBQ_EINVAL;
+    const Plan p = make_plan(o, n, m, d, q_bits, k, false);
+    if (workspace_bytes < p.total) return XBQ_EWORKSPACE;
+    SearchJob job{};
+    job.db_codes = db_codes; job.n = n; job.db_bits = db_bits;
+    job.q_codes = q_codes; job.m = m; job.q_bits = q_bits;
+    job.d = d; job.k = k; job.extra = -1;
+    job.idx = idx; job.score = score;
+    return run_search(o, job, p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -749,38 +902,54 @@ int xbq_encode(const float* X, int64_t n, int d, int bits, float scale, int layo
 
 size_t xbq_search_workspace_bytes(int64_t n, int64_t m, int d, int bits, int k)
 {
-    if (!valid_search_sizes(n, m, d, bits, k)) return 0;
+    return xbq_search_workspace_bytes_ex(n, m, d, bits, k, nullptr);
+}
+
+size_t xbq_search_workspace_bytes_ex(int64_t n, int64_t m, int d, int q_bits, int k, const xbq_options* options)
+{
+    Options o;
+    if (!options_from(options, o)) return 0;
+    if (!valid_search_sizes(n, m, d, q_bits, k)) return 0;
     if (n == 0 || m == 0) return 256;
-    return make_plan(n, m, d, bits, k).total;
+    return make_plan(o, n, m, d, q_bits, k).total;
+}
+
+void xbq_options_default(xbq_options* options)
+{
+    if (options == nullptr) return;
+    const Options o;
+    options->struct_bytes = sizeof(xbq_options);
+    options->selector = o.selector;
+    options->kernel = o.kernel;
+    options->first = o.first;
+    options->qsplit = o.qsplit;
+    options->hist_max_queries = o.hist_max_queries;
+    options->kselect_lists_min = o.kselect_lists_min;
+    options->local_groups = o.local_groups;
+    options->growth = o.growth;
+    options->refine_growth = o.refine_growth;
 }
 
 int xbq_search(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int64_t m, int d, int bits, int k,
                int32_t* idx, int32_t* score, void* workspace, size_t workspace_bytes, void* stream)
 {
-    return xbq_search_asym(db_codes, n, bits, q_codes, m, bits, d, k, idx, score, workspace, workspace_bytes, stream);
+    return xbq_search_ex(db_codes, n, bits, q_codes, m, bits, d, k, idx, score, workspace, workspace_bytes, nullptr, stream);
 }
 
 int xbq_search_asym(const uint32_t* db_codes, int64_t n, int db_bits, const uint32_t* q_codes, int64_t m, int q_bits,
                     int d, int k, int32_t* idx, int32_t* score, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (d < 1 || db_bits < 1 || q_bits < 1 || n < 0 || m < 0) return XBQ_EINVAL;
-    if (!valid_shape(d, db_bits) || !valid_shape(d, q_bits) || !scan_supports_bits(q_bits, db_bits))
-        return XBQ_EUNSUPPORTED;
-    if (!valid_search_sizes(n, m, d, q_bits, k)) return XBQ_EINVAL;
-    if (n == 0 || m == 0) return XBQ_OK;
-    if (!db_codes || !q_codes || !idx || !score || !workspace) return XBQ_EINVAL;
-    if (reinterpret_cast<uintptr_t>(db_codes) % 4 || reinterpret_cast<uintptr_t>(q_codes) % 4 ||
-        reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(score) % 4 ||
-        reinterpret_cast<uintptr_t>(workspace) % 256)
-        return XBQ_EINVAL;
-    const Plan p = make_plan(n, m, d, q_bits, k, false);
-    if (workspace_bytes < p.total) return XBQ_EWORKSPACE;
-    SearchJob job{};
-    job.db_codes = db_codes; job.n = n; job.db_bits = db_bits;
-    job.q_codes = q_codes; job.m = m; job.q_bits = q_bits;
-    job.d = d; job.k = k; job.extra = -1;
-    job.idx = idx; job.score = score;
-    return run_search(job, p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+    return xbq_search_ex(db_codes, n, db_bits, q_codes, m, q_bits, d, k, idx, score, workspace, workspace_bytes, nullptr,
+                         stream);
+}
+
+int xbq_search_ex(const uint32_t* db_codes, int64_t n, int db_bits, const uint32_t* q_codes, int64_t m, int q_bits,
+                  int d, int k, int32_t* idx, int32_t* score, void* workspace, size_t workspace_bytes,
+                  const xbq_options* options, void* stream)
+{
+    Options o;
+    if (!options_from(options, o)) return XBQ_EINVAL;
+    return search_with(o, db_codes, n, db_bits, q_codes, m, q_bits, d, k, idx, score, workspace, workspace_bytes, stream);
 }
 
 int xbq_search_static(const uint32_t* db_codes, int64_t n, const uint32_t* q_codes, int64_t m, int d, int bits, int k,
@@ -790,19 +959,20 @@ int xbq_search_static(const uint32_t* db_codes, int64_t n, const uint32_t* q_cod
     if (!valid_shape(d, bits)) return XBQ_EUNSUPPORTED;
     if (!valid_search_sizes(n, m, d, bits, k)) return XBQ_EINVAL;
     if (n == 0 || m == 0) return XBQ_OK;
+    const Options o = default_options();
     // the size check comes first: a request that cannot fit is refused without any HIP call
-    if (make_plan(n, m, d, bits, k, false).total > static_cast<size_t>(XBQ_STATIC_SCRATCH_BYTES)) return XBQ_ESTATIC;
+    if (make_plan(o, n, m, d, bits, k, false).total > static_cast<size_t>(XBQ_STATIC_SCRATCH_BYTES)) return XBQ_ESTATIC;
     char* ws = nullptr;
     const hipError_t e = scratch_address(&ws);
     if (e != hipSuccess) return fail_hip(e);
-    return xbq_search_asym(db_codes, n, bits, q_codes, m, bits, d, k, idx, score, ws, XBQ_STATIC_SCRATCH_BYTES, stream);
+    return search_with(o, db_codes, n, bits, q_codes, m, bits, d, k, idx, score, ws, XBQ_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t xbq_search_refine_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int k)
 {
     if (!valid_search_sizes(n, m, d, q_bits, k)) return 0;
     if (n == 0 || m == 0) return 256;
-    return make_plan(n, m, d, q_bits, k, true).total;
+    return make_plan(default_options(), n, m, d, q_bits, k, true).total;
 }
 
 int xbq_search_refine(const float* X_db, const uint32_t* db_codes, int64_t n, int db_bits, const float* X_q,
@@ -821,14 +991,15 @@ int xbq_search_refine(const float* X_db, const uint32_t* db_codes, int64_t n, in
         reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(similarity) % 4 ||
         reinterpret_cast<uintptr_t>(candidates) % 4 || reinterpret_cast<uintptr_t>(workspace) % 256)
         return XBQ_EINVAL;
-    const Plan p = make_plan(n, m, d, q_bits, k, true);
+    const Options o = default_options();
+    const Plan p = make_plan(o, n, m, d, q_bits, k, true);
     if (workspace_bytes < p.total) return XBQ_EWORKSPACE;
     SearchJob job{};
     job.db_codes = db_codes; job.n = n; job.db_bits = db_bits;
     job.q_codes = q_codes; job.m = m; job.q_bits = q_bits;
     job.d = d; job.k = k; job.extra = extra_distance;
     job.idx = idx; job.X_db = X_db; job.X_q = X_q; job.similarity = similarity; job.candidates = candidates;
-    return run_search(job, p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+    return run_search(o, job, p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 size_t xbq_k_select_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int k, int extra_distance,
@@ -838,7 +1009,7 @@ size_t xbq_k_select_workspace_bytes(int64_t n, int64_t m, int d, int q_bits, int
     if (extra_distance < 0 || extra_distance > XBQ_MAX_EXTRA) return 0;
     if (max_candidates < k || max_candidates > XBQ_MAX_CANDIDATES) return 0;
     if (n == 0 || m == 0) return 256;
-    return make_kplan(n, m, d, q_bits, k, max_candidates, extra_distance).total;
+    return make_kplan(default_options(), n, m, d, q_bits, k, max_candidates, extra_distance).total;
 }
 
 int xbq_k_select(const float* X_db, const uint32_t* db_codes, int64_t n, int db_bits, const float* X_q,
@@ -859,14 +1030,15 @@ int xbq_k_select(const float* X_db, const uint32_t* db_codes, int64_t n, int db_
         reinterpret_cast<uintptr_t>(idx) % 4 || reinterpret_cast<uintptr_t>(similarity) % 4 ||
         reinterpret_cast<uintptr_t>(candidates) % 4 || reinterpret_cast<uintptr_t>(workspace) % 256)
         return XBQ_EINVAL;
-    const KPlan kp = make_kplan(n, m, d, q_bits, k, max_candidates, extra_distance);
+    const Options o = default_options();
+    const KPlan kp = make_kplan(o, n, m, d, q_bits, k, max_candidates, extra_distance);
     if (workspace_bytes < kp.total) return XBQ_EWORKSPACE;
     SearchJob job{};
     job.db_codes = db_codes; job.n = n; job.db_bits = db_bits;
     job.q_codes = q_codes; job.m = m; job.q_bits = q_bits;
     job.d = d; job.k = k; job.extra = extra_distance;
     job.idx = idx; job.X_db = X_db; job.X_q = X_q; job.similarity = similarity; job.candidates = candidates;
-    return run_k_select(job, kp, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+    return run_k_select(o, job, kp, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 int xbq_trace_enable(int on)
@@ -927,47 +1099,11 @@ int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_byte
 int xbq_set_option(const char* name, double value)
 {
     if (!name) return XBQ_EINVAL;
-    if (!std::strcmp(name, "growth")) {
-        if (!(value >= 1.25 && value <= 64.0)) return XBQ_EINVAL;
-        g_opt.growth = value;
-        return XBQ_OK;
-    }
-    if (!std::strcmp(name, "first")) {
-        if (!(value >= 64 && value <= kSortCap)) return XBQ_EINVAL;
-        g_opt.first = static_cast<int>(value);
-        return XBQ_OK;
-    }
-    if (!std::strcmp(name, "kernel")) {
-        if (!(value == 0 || value == 1 || value == 2)) return XBQ_EINVAL;
-        g_opt.kernel = static_cast<int>(value);
-        return XBQ_OK;
-    }
-    if (!std::strcmp(name, "selector")) {
-        if (!(value == 0 || value == 1 || value == 2)) return XBQ_EINVAL;
-        g_opt.selector = static_cast<int>(value);
-        return XBQ_OK;
-    }
-    if (!std::strcmp(name, "hist_max_queries")) {
-        if (!(value >= 0 && value <= (1 << 20))) return XBQ_EINVAL;
-        g_opt.hist_max_queries = static_cast<int>(value);
-        return XBQ_OK;
-    }
-    if (!std::strcmp(name, "refine_growth")) {
-        if (!(value >= 1.25 && value <= 64.0)) return XBQ_EINVAL;
-        g_opt.refine_growth = value;
-        return XBQ_OK;
-    }
-    if (!std::strcmp(name, "kselect_lists_min")) {
-        if (!(value >= 0 && value <= (1 << 20))) return XBQ_EINVAL;
-        g_opt.kselect_lists_min = static_cast<int>(value);
-        return XBQ_OK;
-    }
-    if (!std::strcmp(name, "qsplit")) {
-        if (!(value >= 0 && value <= 65536)) return XBQ_EINVAL;
-        g_opt.qsplit = static_cast<int>(value);
-        return XBQ_OK;
-    }
-    return XBQ_EINVAL;
+    std::lock_guard<std::mutex> lock(g_opt_mutex);
+    Options o = g_opt;
+    if (!set_knob(o, name, value)) return XBQ_EINVAL;
+    g_opt = o;
+    return XBQ_OK;
 }
 
 }  // extern "C"

@@ -15,6 +15,8 @@ constexpr int kSortCap = 4096;    // most 64-bit keys one workgroup sorts in LDS
 constexpr int kTileQ = 16;        // queries per register tile of the word-chunked scan
 constexpr int kHistBins = 1024;   // histogram bins per query (histogram selection)
 constexpr int kHistMaxQueries = 8;  // queries per pass of the histogram selection
+constexpr int kLocalMaxQueries = 4; // queries per pass of the local selection (few queries, nothing stored)
+constexpr int kLocalMaxGroups = 1024;   // most pieces (workgroups) of the local selection
 
 // A candidate is ordered by the 64-bit key (D << 32) | row: smaller key = better
 // (smaller distance D, then lower row number).  D is the Eq. 6 distance.
@@ -187,6 +189,29 @@ struct CollectArgs {
 hipError_t launch_clear(uint32_t* p, int64_t count, hipStream_t s);
 hipError_t launch_scan_hist(const HistArgs& a, hipStream_t s);
 hipError_t launch_hist_collect(const CollectArgs& a, hipStream_t s);
+
+// Local selection (few queries, no stored distances): see xbq_local.hip.
+struct LocalArgs {
+    const uint32_t* db;      // XBQ_BUNDLE64 codes
+    int64_t n;
+    const uint32_t* q;       // [m][nchunks][q_bits][wc]
+    int m;                   // 1..kLocalMaxQueries
+    int q_bits, db_bits;
+    int W, wc, nchunks;
+    int k, d;
+    int shift;               // piece histogram: bin = D >> shift  (< kHistBins for every possible D)
+    int shift2;              // merge histogram: bin = D >> shift2 (< 4096 for every possible D)
+    int cap;                 // keys per (piece, query) list: power of two, >= 8 k, 1024..4096
+    int groups;              // pieces = workgroups of scan_local
+    int64_t bundles_per_group;
+    uint64_t* lists;         // [m][groups][cap], written by scan_local
+    uint32_t* counts;        // [m][groups]
+    int32_t* idx;            // [m][k]
+    int32_t* score;          // [m][k]
+};
+size_t local_lds_bytes(int m, int cap);
+hipError_t launch_scan_local(const LocalArgs& a, hipStream_t s);
+hipError_t launch_local_finish(const LocalArgs& a, hipStream_t s);
 
 // Algorithm 1 with the whole candidate list (xbq_kselect.hip), one batch of queries.
 struct KSelectArgs {

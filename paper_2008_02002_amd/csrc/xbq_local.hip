@@ -1,0 +1,622 @@
+// Few queries (the single-request mode the paper measures, Section 5), two launches, no
+// distance ever stored: the scan selects while it streams.
+//
+// With one or two queries the scan is bound by the HBM stream of the database codes, so the
+// path moves those bytes once and nothing else of size n.  Algorithm 1's selector (Section 4.1
+// "Histogram and Select": histogram of the integer distances, boundary at the K-th smallest)
+// is applied per workgroup, on the rows that workgroup streams:
+//
+//   scan_local    Each workgroup owns one contiguous piece of the database.  It keeps, per
+//                 query, a histogram of D >> shift of the rows it let through and a list of
+//                 their keys, both in LDS.  A row of the global top-K is also in the top-K of
+//                 its own piece, so a row may be dropped as soon as K rows of the same piece
+//                 lie in lower bins.  After 1024 rows, and then every time the rows seen have
+//                 doubled, the workgroup recomputes that boundary from its histogram, lowers
+//                 its threshold and compacts its list; for rows in random order about K rows
+//                 pass between two such points.  At the end the list (a superset of the
+//                 piece's K best, typically K plus the ties of one bin) is written to the
+//                 workgroup's own slot: no global atomics, nothing to clear beforehand.
+//                 If a list overflows (rows sorted towards the query, or massive ties) the
+//                 workgroup re-selects its piece exactly for that query: bounded buffer, sorted
+//                 and cut to K whenever it fills (slow, always exact).
+//   local_finish  One workgroup per query merges the lists: histogram of D >> shift2 (4096
+//                 bins) over all listed keys, boundary bin, the keys at or below it sorted by
+//                 (D, row), first K written.  Massive ties at the boundary are streamed with a
+//                 running threshold on the whole key instead.
+//
+// Ties go to the lower row: keys are (D << 32) | row and every cut is made on whole keys or
+// keeps whole bins.
+
+#include "xbq_device.h"
+
+namespace xbq {
+
+namespace {
+
+constexpr int kLocalBlock = 1024;                     // threads per workgroup
+constexpr int kLocalWaves = kLocalBlock / kLanes;
+constexpr int kFinishBins = 4096;
+
+__device__ __forceinline__ uint32_t load_stream(const uint32_t* p) { return __builtin_nontemporal_load(p); }
+
+// LDS of scan_local, carved from one dynamic allocation.
+struct LocalLds {
+    uint64_t* buf;        // [m][cap] keys let through
+    uint32_t* hist;       // [m][kHistBins]
+    uint32_t* cnt;        // [kLocalMaxQueries] keys in buf[t]
+    uint32_t* thr;        // [kLocalMaxQueries] a row passes when D < thr[t]
+    uint32_t* ovf;        // [kLocalMaxQueries] set when a key did not fit
+    uint32_t* wave_sum;   // [kLocalWaves]
+    int* pick;            // [2]
+};
+
+__device__ __forceinline__ LocalLds carve(uint64_t* base, int m, int cap)
+{
+    LocalLds s;
+    s.buf = base;
+    s.hist = reinterpret_cast<uint32_t*>(base + static_cast<size_t>(m) * cap);
+    s.cnt = s.hist + m * kHistBins;
+    s.thr = s.cnt + kLocalMaxQueries;
+    s.ovf = s.thr + kLocalMaxQueries;
+    s.wave_sum = s.ovf + kLocalMaxQueries;
+    s.pick = reinterpret_cast<int*>(s.wave_sum + kLocalWaves);
+    return s;
+}
+
+// Append the keys of the passing lanes to an LDS list: one LDS atomic per wavefront reserves
+// the slots.  Keys that do not fit raise *ovf.  Passing rows are also counted in hist.
+__device__ __forceinline__ void append_lds(bool pass, uint32_t D, uint32_t row, uint64_t* list, uint32_t* counter,
+                                           uint32_t cap, uint32_t* ovf, uint32_t* hist, int shift)
+{
+    const uint64_t mask = __ballot(pass);
+    if (mask == 0) return;
+    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
+    uint32_t base = 0;
+    if (lane_id() == leader) base = atomicAdd(counter, static_cast<uint32_t>(__popcll(mask)));
+    base = __shfl(base, leader);
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+    if (pass) {
+        const uint32_t pos = base + rank;
+        if (pos < cap) list[pos] = make_key(D, row);
+        else *ovf = 1u;
+        if (hist != nullptr) atomicAdd(&hist[D >> shift], 1u);
+    }
+}
+
+// Smallest bin b such that bins 0..b of h[0 .. PER * blockDim) hold at least k rows; the last
+// bin if all of them hold fewer.  *within = rows in bins 0..b.  Called by every thread of the
+// workgroup (1024 threads); contains barriers.
+template <int PER>
+__device__ int boundary_of(const uint32_t* h, int k, uint32_t* wave_sum, int* pick, int* within)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t mine[PER];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) { mine[i] = h[threadIdx.x * PER + i]; sum += mine[i]; }
+    uint32_t incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    if (threadIdx.x == 0) { pick[0] = PER * kLocalBlock - 1; pick[1] = -1; }
+    __syncthreads();
+    uint32_t before = incl - sum, all = 0;
+    for (int w = 0; w < kLocalWaves; ++w) {
+        const uint32_t v = wave_sum[w];
+        if (w < wave) before += v;
+        all += v;
+    }
+    const uint32_t kk = static_cast<uint32_t>(k);
+    if (before < kk && before + sum >= kk) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            if (before < kk && before + mine[i] >= kk) {
+                pick[0] = threadIdx.x * PER + i;
+                pick[1] = static_cast<int>(before + mine[i]);
+            }
+            before += mine[i];
+        }
+    }
+    __syncthreads();
+    const int bin = pick[0];
+    *within = pick[1] < 0 ? static_cast<int>(all) : pick[1];
+    __syncthreads();                                     // pick and wave_sum may be reused at once
+    return bin;
+}
+
+// Eq. 10 (Section 3.3, the POPCNT form) for one row against query t of the chunk-major query
+// layout, run-time sizes: the slow path of the exact re-selection.
+__device__ uint32_t distance_chunked(const LocalArgs& a, int64_t row, int t)
+{
+    const uint32_t* xb = a.db + (row / kLanes) * (static_cast<int64_t>(a.db_bits) * a.W * kLanes) + (row % kLanes);
+    const uint32_t* yq = a.q + static_cast<size_t>(t) * a.nchunks * a.q_bits * a.wc;
+    uint32_t D = 0;
+    for (int w = 0; w < a.W; ++w) {
+        const int c = w / a.wc, o = w - c * a.wc;
+        uint32_t x[XBQ_MAX_BITS], y[XBQ_MAX_BITS];
+        for (int b = 0; b < a.db_bits; ++b) x[b] = xb[(b * a.W + w) * kLanes];
+        for (int b = 0; b < a.q_bits; ++b) y[b] = yq[(c * a.q_bits + b) * a.wc + o];
+        for (int i = 0; i < a.db_bits; ++i)
+            for (int j = 0; j < a.q_bits; ++j) D += static_cast<uint32_t>(__builtin_popcount(x[i] ^ y[j])) << (i + j);
+    }
+    return D;
+}
+
+// Exact K best rows of the piece [row_begin, row_end) for query t into buf (at most cap keys),
+// rows in ascending order: a later row gets in only with a smaller D than the K-th best so far.
+__device__ void reselect_piece(const LocalArgs& a, const LocalLds& s, int t, int64_t row_begin, int64_t row_end)
+{
+    uint64_t* buf = s.buf + static_cast<size_t>(t) * a.cap;
+    const int chunk = a.cap / 2 < kLocalBlock ? a.cap / 2 : kLocalBlock;     // k <= cap / 8, so k + chunk fits
+    if (threadIdx.x == 0) s.cnt[t] = 0;
+    __syncthreads();
+    uint32_t thr = 0xffffffffu;
+    for (int64_t r0 = row_begin; r0 < row_end; r0 += chunk) {
+        const int64_t row = r0 + threadIdx.x;
+        if (static_cast<int>(threadIdx.x) < chunk && row < row_end) {
+            const uint32_t D = distance_chunked(a, row, t);
+            if (D < thr) buf[atomicAdd(&s.cnt[t], 1u)] = make_key(D, static_cast<uint32_t>(row));
+        }
+        __syncthreads();
+        const int have = static_cast<int>(s.cnt[t]);     // <= cap: at most cap - chunk before this round
+        if (have > a.cap - chunk) {
+            const int P = next_pow2(have);
+            for (int i = have + threadIdx.x; i < P; i += kLocalBlock) buf[i] = kPadKey;
+            __syncthreads();
+            bitonic_sort_lds(buf, P);
+            if (have > a.k) {
+                thr = static_cast<uint32_t>(buf[a.k - 1] >> 32);
+                __syncthreads();
+                if (threadIdx.x == 0) s.cnt[t] = static_cast<uint32_t>(a.k);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// New boundary of query `t` from its piece histogram, by one wavefront: the smallest bin b such
+// that bins 0..b hold at least k rows (the last bin if there are fewer rows).  Returns the
+// threshold (b + 1) << shift in every lane.
+__device__ __forceinline__ uint32_t wave_boundary(const uint32_t* h, int k, int shift)
+{
+    constexpr int kPer = kHistBins / kLanes;             // 16 consecutive bins per lane
+    const int lane = lane_id();
+    uint32_t mine[kPer];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) { mine[i] = h[lane * kPer + i]; sum += mine[i]; }
+    uint32_t incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    uint32_t before = incl - sum;
+    const uint32_t kk = static_cast<uint32_t>(k);
+    int bin = -1;
+    if (before < kk && incl >= kk) {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            if (bin < 0 && before + mine[i] >= kk) bin = lane * kPer + i;
+            before += mine[i];
+        }
+    }
+    const uint64_t found = __ballot(bin >= 0);
+    if (found == 0) return static_cast<uint32_t>(kHistBins) << shift;      // fewer than k rows so far
+    bin = __shfl(bin, __ffsll(static_cast<long long>(found)) - 1);
+    return (static_cast<uint32_t>(bin) + 1u) << shift;
+}
+
+// Rows of one step of one wavefront: bundle j of the wavefront is b_begin + j * 16 + wave; step 0
+// is bundle 0 alone (it only has to give K rows), step s >= 1 is bundles 1 + (s-1) R .. s R.
+template <int R>
+__device__ __forceinline__ int64_t step_bundle(int step, int r, int64_t b_begin, int wave)
+{
+    if (step == 0) return r == 0 ? b_begin + wave : -1;
+    return b_begin + (1 + static_cast<int64_t>(step - 1) * R + r) * kLocalWaves + wave;
+}
+
+}  // namespace
+
+// One workgroup per piece of a.bundles_per_group bundles.  PREFETCH (whole row in registers,
+// nchunks == 1): the rows of the next step are requested before the current step is scored, so
+// the stream keeps flowing while the workgroup sits in the barriers of a threshold update.
+template <int BQ, int BD, int WC, int R, bool PREFETCH>
+__global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
+{
+    extern __shared__ uint64_t local_lds[];
+    const LocalLds s = carve(local_lds, a.m, a.cap);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < a.m * kHistBins; i += kLocalBlock) s.hist[i] = 0;
+    if (threadIdx.x < kLocalMaxQueries) {
+        s.cnt[threadIdx.x] = 0;
+        s.thr[threadIdx.x] = 0xffffffffu;
+        s.ovf[threadIdx.x] = 0;
+    }
+
+    const int64_t nbundles = (a.n + kLanes - 1) / kLanes;
+    const int64_t b_begin = static_cast<int64_t>(blockIdx.x) * a.bundles_per_group;
+    const int64_t b_end = b_begin + a.bundles_per_group < nbundles ? b_begin + a.bundles_per_group : nbundles;
+    const int rounds = static_cast<int>((b_end - b_begin + kLocalWaves - 1) / kLocalWaves);   // bundles per wavefront
+    const int steps = 1 + (rounds - 1 + R - 1) / R;
+    const int64_t row_stride = static_cast<int64_t>(BD) * a.W * kLanes;
+
+    uint32_t thr[kLocalMaxQueries];
+#pragma unroll
+    for (int t = 0; t < kLocalMaxQueries; ++t) thr[t] = 0xffffffffu;
+
+    uint32_t xn[R][BD][WC];                              // PREFETCH: rows of the step to come
+    if (PREFETCH) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t bundle = step_bundle<R>(0, r, b_begin, wave);
+            if (bundle >= 0 && bundle < b_end) {
+                const uint32_t* xb = a.db + bundle * row_stride + lane;
+#pragma unroll
+                for (int b = 0; b < BD; ++b)
+#pragma unroll
+                    for (int w = 0; w < WC; ++w) xn[r][b][w] = load_stream(xb + (b * WC + w) * kLanes);
+            }
+        }
+    }
+    __syncthreads();
+
+    int64_t seen = 0, seen_at_refresh = 0;
+    for (int step = 0; step < steps; ++step) {
+        uint32_t acc[R][kLocalMaxQueries];
+        uint32_t row[R];
+        bool live[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t bundle = step_bundle<R>(step, r, b_begin, wave);
+            live[r] = bundle >= 0 && bundle < b_end;     // same in every lane
+            row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
+#pragma unroll
+            for (int t = 0; t < kLocalMaxQueries; ++t) acc[r][t] = 0;
+        }
+        if (PREFETCH) {
+            uint32_t x[R][BD][WC];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int b = 0; b < BD; ++b)
+#pragma unroll
+                    for (int w = 0; w < WC; ++w) x[r][b][w] = xn[r][b][w];
+            if (step + 1 < steps) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int64_t bundle = step_bundle<R>(step + 1, r, b_begin, wave);
+                    if (bundle >= 0 && bundle < b_end) {
+                        const uint32_t* xb = a.db + bundle * row_stride + lane;
+#pragma unroll
+                        for (int b = 0; b < BD; ++b)
+#pragma unroll
+                            for (int w = 0; w < WC; ++w) xn[r][b][w] = load_stream(xb + (b * WC + w) * kLanes);
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kLocalMaxQueries; ++t) {
+                if (t < a.m) {
+                    uniform_ptr yq = (uniform_ptr)(a.q + static_cast<size_t>(t) * (BQ * WC));
+                    uint32_t y[BQ][WC];
+#pragma unroll
+                    for (int b = 0; b < BQ; ++b)
+#pragma unroll
+                        for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        if (live[r]) acc[r][t] = xor_popcount<BQ, BD, WC>(x[r], y);
+                }
+            }
+        } else {
+            for (int c = 0; c < a.nchunks; ++c) {
+                uint32_t x[R][BD][WC];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (!live[r]) continue;
+                    const uint32_t* xb = a.db + step_bundle<R>(step, r, b_begin, wave) * row_stride + lane;
+#pragma unroll
+                    for (int b = 0; b < BD; ++b)
+#pragma unroll
+                        for (int w = 0; w < WC; ++w) {
+                            const int ww = c * WC + w;
+                            x[r][b][w] = ww < a.W ? load_stream(xb + (b * a.W + ww) * kLanes) : 0u;
+                        }
+                }
+#pragma unroll
+                for (int t = 0; t < kLocalMaxQueries; ++t) {
+                    if (t < a.m) {
+                        uniform_ptr yq = (uniform_ptr)(a.q + (static_cast<size_t>(t) * a.nchunks + c) * (BQ * WC));
+                        uint32_t y[BQ][WC];
+#pragma unroll
+                        for (int b = 0; b < BQ; ++b)
+#pragma unroll
+                            for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+                            if (live[r]) acc[r][t] += xor_popcount<BQ, BD, WC>(x[r], y);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (!live[r]) continue;
+            const bool valid = row[r] < a.n;
+#pragma unroll
+            for (int t = 0; t < kLocalMaxQueries; ++t) {
+                if (t < a.m)
+                    append_lds(valid && acc[r][t] < thr[t], acc[r][t], row[r], s.buf + static_cast<size_t>(t) * a.cap,
+                               &s.cnt[t], static_cast<uint32_t>(a.cap), &s.ovf[t], s.hist + t * kHistBins, a.shift);
+            }
+        }
+        seen += static_cast<int64_t>(step == 0 ? 1 : R) * kLocalBlock;
+        if (seen < 4 * seen_at_refresh && step + 1 < steps) continue;
+
+        // Threshold update, all queries at once: wavefront t finds the new boundary of query t,
+        // then the whole workgroup compacts the lists (keys held in registers across the reset).
+        seen_at_refresh = seen;
+        __syncthreads();
+        if (wave < a.m) {
+            const uint32_t edge = wave_boundary(s.hist + wave * kHistBins, a.k, a.shift);
+            if (lane == 0 && edge < s.thr[wave]) s.thr[wave] = edge;
+        }
+        constexpr int kHeld = 4;                         // cap <= kHeld * kLocalBlock
+        uint64_t held[kLocalMaxQueries][kHeld];
+#pragma unroll
+        for (int t = 0; t < kLocalMaxQueries; ++t) {
+            const int have = t < a.m ? static_cast<int>(s.cnt[t] < static_cast<uint32_t>(a.cap) ? s.cnt[t] : a.cap) : 0;
+#pragma unroll
+            for (int u = 0; u < kHeld; ++u) {
+                const int i = u * kLocalBlock + threadIdx.x;
+                held[t][u] = i < have ? s.buf[static_cast<size_t>(t) * a.cap + i] : kPadKey;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < kLocalMaxQueries) s.cnt[threadIdx.x] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < kLocalMaxQueries; ++t) {
+            if (t < a.m) {
+                thr[t] = s.thr[t];
+#pragma unroll
+                for (int u = 0; u < kHeld; ++u) {
+                    if (u * kLocalBlock < a.cap) {
+                        const uint32_t D = static_cast<uint32_t>(held[t][u] >> 32);
+                        append_lds(held[t][u] != kPadKey && D < thr[t], D, static_cast<uint32_t>(held[t][u]),
+                                   s.buf + static_cast<size_t>(t) * a.cap, &s.cnt[t], static_cast<uint32_t>(a.cap),
+                                   &s.ovf[t], nullptr, 0);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    const int64_t row_begin = b_begin * kLanes;
+    const int64_t row_end = b_end * kLanes < a.n ? b_end * kLanes : a.n;
+    for (int t = 0; t < a.m; ++t) {
+        if (s.ovf[t] != 0) reselect_piece(a, s, t, row_begin, row_end);          // same value in every thread
+        __syncthreads();
+        const uint32_t have = s.cnt[t];
+        const size_t slot = static_cast<size_t>(t) * a.groups + blockIdx.x;
+        for (uint32_t i = threadIdx.x; i < have; i += kLocalBlock) a.lists[slot * a.cap + i] = s.buf[static_cast<size_t>(t) * a.cap + i];
+        if (threadIdx.x == 0) a.counts[slot] = have;
+    }
+}
+
+// One workgroup per query: merge of the pieces' lists, see the head of this file.  The lists
+// are read as one rectangle [groups][longest list rounded up to a power of two], one slot per
+// thread and round, every load of a pass issued before the first key is looked at; if the
+// rectangle fits 32 slots per thread the keys stay in registers for the second pass.
+constexpr int kFinishHeld = 32;
+constexpr int kFinishBatch = 8;
+
+__device__ __forceinline__ uint64_t finish_slot(const LocalArgs& a, const uint64_t* lists, const uint32_t* cnt_s,
+                                                int64_t slot, int64_t nslots, int sh)
+{
+    if (slot >= nslots) return kPadKey;
+    const int g = static_cast<int>(slot >> sh);
+    const uint32_t i = static_cast<uint32_t>(slot & ((int64_t(1) << sh) - 1));
+    return i < cnt_s[g] ? lists[static_cast<size_t>(g) * a.cap + i] : kPadKey;
+}
+
+__device__ __forceinline__ void finish_collect(uint64_t key, uint32_t bin, int shift2, uint64_t* keys, uint32_t* fill)
+{
+    const bool pass = key != kPadKey && (static_cast<uint32_t>(key >> 32) >> shift2) <= bin;
+    const uint64_t mask = __ballot(pass);
+    if (mask == 0) return;
+    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
+    uint32_t base = 0;
+    if (lane_id() == leader) base = atomicAdd(fill, static_cast<uint32_t>(__popcll(mask)));
+    base = __shfl(base, leader);
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+    if (pass) keys[base + rank] = key;
+}
+
+__global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
+{
+    __shared__ uint64_t keys[kSortCap];
+    __shared__ uint32_t hist[kFinishBins];
+    __shared__ uint32_t cnt_s[kLocalMaxGroups];
+    __shared__ uint32_t wave_sum[kLocalWaves];
+    __shared__ int pick[2];
+    __shared__ uint32_t fill, longest;
+    const int q = blockIdx.x;
+    const uint64_t* lists = a.lists + static_cast<size_t>(q) * a.groups * a.cap;
+    const uint32_t* counts = a.counts + static_cast<size_t>(q) * a.groups;
+    for (int i = threadIdx.x; i < kFinishBins; i += kLocalBlock) hist[i] = 0;
+    if (threadIdx.x == 0) { fill = 0; longest = 0; }
+    __syncthreads();
+    for (int g = threadIdx.x; g < a.groups; g += kLocalBlock) {
+        const uint32_t c = counts[g];
+        cnt_s[g] = c;
+        atomicMax(&longest, c);
+    }
+    __syncthreads();
+    const int sh = 31 - __builtin_clz(static_cast<uint32_t>(next_pow2(static_cast<int>(longest < 64 ? 64 : longest))));
+    const int64_t nslots = static_cast<int64_t>(a.groups) << sh;
+    const bool in_registers = nslots <= static_cast<int64_t>(kFinishHeld) * kLocalBlock;
+
+    uint64_t held[kFinishHeld];
+    if (in_registers) {
+#pragma unroll
+        for (int u = 0; u < kFinishHeld; ++u)
+            held[u] = finish_slot(a, lists, cnt_s, static_cast<int64_t>(u) * kLocalBlock + threadIdx.x, nslots, sh);
+#pragma unroll
+        for (int u = 0; u < kFinishHeld; ++u)
+            if (held[u] != kPadKey) atomicAdd(&hist[static_cast<uint32_t>(held[u] >> 32) >> a.shift2], 1u);
+    } else {
+        for (int64_t s0 = 0; s0 < nslots; s0 += static_cast<int64_t>(kFinishBatch) * kLocalBlock) {
+            uint64_t k8[kFinishBatch];
+#pragma unroll
+            for (int u = 0; u < kFinishBatch; ++u)
+                k8[u] = finish_slot(a, lists, cnt_s, s0 + static_cast<int64_t>(u) * kLocalBlock + threadIdx.x, nslots, sh);
+#pragma unroll
+            for (int u = 0; u < kFinishBatch; ++u)
+                if (k8[u] != kPadKey) atomicAdd(&hist[static_cast<uint32_t>(k8[u] >> 32) >> a.shift2], 1u);
+        }
+    }
+    __syncthreads();
+    int within;
+    const uint32_t bin = static_cast<uint32_t>(boundary_of<kFinishBins / kLocalBlock>(hist, a.k, wave_sum, pick, &within));
+
+    if (within <= kSortCap) {
+        if (in_registers) {
+#pragma unroll
+            for (int u = 0; u < kFinishHeld; ++u) finish_collect(held[u], bin, a.shift2, keys, &fill);
+        } else {
+            for (int64_t s0 = 0; s0 < nslots; s0 += static_cast<int64_t>(kFinishBatch) * kLocalBlock) {
+                uint64_t k8[kFinishBatch];
+#pragma unroll
+                for (int u = 0; u < kFinishBatch; ++u)
+                    k8[u] = finish_slot(a, lists, cnt_s, s0 + static_cast<int64_t>(u) * kLocalBlock + threadIdx.x, nslots, sh);
+#pragma unroll
+                for (int u = 0; u < kFinishBatch; ++u) finish_collect(k8[u], bin, a.shift2, keys, &fill);
+            }
+        }
+        __syncthreads();
+        const int have = static_cast<int>(fill);         // == within
+        const int P = next_pow2(have);
+        for (int i = have + threadIdx.x; i < P; i += kLocalBlock) keys[i] = kPadKey;
+        __syncthreads();
+        bitonic_sort_lds(keys, P);
+    } else {
+        // massive ties at the boundary: every listed key in turn against the K-th best key so far
+        uint64_t thr = kPadKey;
+        for (int g = 0; g < a.groups; ++g) {
+            const uint32_t c = cnt_s[g];
+            const uint64_t* list = lists + static_cast<size_t>(g) * a.cap;
+            for (uint32_t i0 = 0; i0 < c; i0 += kLocalBlock) {
+                const uint32_t i = i0 + threadIdx.x;
+                if (i < c) {
+                    const uint64_t key = list[i];
+                    if (key < thr) keys[atomicAdd(&fill, 1u)] = key;
+                }
+                __syncthreads();
+                const int have = static_cast<int>(fill);
+                if (have > kSortCap - kLocalBlock) {
+                    const int P = next_pow2(have);
+                    for (int j = have + threadIdx.x; j < P; j += kLocalBlock) keys[j] = kPadKey;
+                    __syncthreads();
+                    bitonic_sort_lds(keys, P);
+                    thr = keys[a.k - 1];                 // have > k here: k <= 1024 < have
+                    __syncthreads();
+                    if (threadIdx.x == 0) fill = static_cast<uint32_t>(a.k);
+                }
+                __syncthreads();
+            }
+        }
+        const int have = static_cast<int>(fill);
+        const int P = next_pow2(have);
+        for (int i = have + threadIdx.x; i < P; i += kLocalBlock) keys[i] = kPadKey;
+        __syncthreads();
+        bitonic_sort_lds(keys, P);
+    }
+    const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
+    for (int i = threadIdx.x; i < a.k; i += kLocalBlock) {
+        const uint64_t key = keys[i];
+        a.idx[static_cast<size_t>(q) * a.k + i] = static_cast<int32_t>(key & 0xffffffffu);
+        a.score[static_cast<size_t>(q) * a.k + i] = full - 2 * static_cast<int32_t>(key >> 32);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+size_t local_lds_bytes(int m, int cap)
+{
+    return static_cast<size_t>(m) * cap * sizeof(uint64_t) + static_cast<size_t>(m) * kHistBins * sizeof(uint32_t) +
+           (3 * kLocalMaxQueries + kLocalWaves + 2) * sizeof(uint32_t);
+}
+
+template <int BQ, int BD, int WC>
+static hipError_t launch_scan_local_w(const LocalArgs& a, hipStream_t s)
+{
+    const dim3 grid(static_cast<unsigned>(a.groups)), block(kLocalBlock);
+    const size_t lds = local_lds_bytes(a.m, a.cap);
+    // whole row in registers (one chunk, exactly W words): next step's rows are prefetched
+    if (a.nchunks == 1 && a.W == WC) {
+        if (BD * WC <= 16) hipLaunchKernelGGL((scan_local<BQ, BD, WC, 2, true>), grid, block, lds, s, a);
+        else               hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, true>), grid, block, lds, s, a);
+    } else {
+        hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, false>), grid, block, lds, s, a);
+    }
+    return hipGetLastError();
+}
+
+template <int BQ, int BD>
+static hipError_t launch_scan_local_b(const LocalArgs& a, hipStream_t s)
+{
+    switch (a.wc) {
+    case 1: return launch_scan_local_w<BQ, BD, 1>(a, s);
+    case 2: return launch_scan_local_w<BQ, BD, 2>(a, s);
+    case 3: return launch_scan_local_w<BQ, BD, 3>(a, s);
+    case 4: return launch_scan_local_w<BQ, BD, 4>(a, s);
+    case 5: return launch_scan_local_w<BQ, BD, 5>(a, s);
+    case 6: return launch_scan_local_w<BQ, BD, 6>(a, s);
+    case 7: return launch_scan_local_w<BQ, BD, 7>(a, s);
+    case 8: return launch_scan_local_w<BQ, BD, 8>(a, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_scan_local(const LocalArgs& a, hipStream_t s)
+{
+    if (a.m < 1 || a.m > kLocalMaxQueries || a.n < 1 || a.wc < 1 || a.wc > 8 || a.nchunks < 1 ||
+        a.nchunks * a.wc < a.W) return hipErrorInvalidValue;
+    if (a.k < 1 || a.cap < 8 * a.k || a.cap < kLocalBlock || a.cap > 4 * kLocalBlock || (a.cap & (a.cap - 1)) != 0)
+        return hipErrorInvalidValue;
+    if (local_lds_bytes(a.m, a.cap) > 64 * 1024) return hipErrorInvalidValue;
+    const int64_t nbundles = (a.n + kLanes - 1) / kLanes;
+    if (a.groups > kLocalMaxGroups) return hipErrorInvalidValue;
+    if (a.groups < 1 || a.bundles_per_group < 1 || a.groups * a.bundles_per_group < nbundles ||
+        (a.groups - 1) * a.bundles_per_group >= nbundles) return hipErrorInvalidValue;
+    const int64_t dmax = static_cast<int64_t>(a.d) * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
+    if ((dmax >> a.shift) >= kHistBins || (dmax >> a.shift2) >= kFinishBins) return hipErrorInvalidValue;
+    switch (a.q_bits * 10 + a.db_bits) {
+    case 11: return launch_scan_local_b<1, 1>(a, s);
+    case 22: return launch_scan_local_b<2, 2>(a, s);
+    case 33: return launch_scan_local_b<3, 3>(a, s);
+    case 44: return launch_scan_local_b<4, 4>(a, s);
+    case 21: return launch_scan_local_b<2, 1>(a, s);
+    case 32: return launch_scan_local_b<3, 2>(a, s);
+    case 43: return launch_scan_local_b<4, 3>(a, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// After launch_scan_local with the same arguments on the same stream.
+hipError_t launch_local_finish(const LocalArgs& a, hipStream_t s)
+{
+    if (a.m < 1 || a.m > kLocalMaxQueries || a.groups < 1 || a.groups > kLocalMaxGroups || a.k < 1 || a.k > kSortCap / 4)
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(local_finish, dim3(static_cast<unsigned>(a.m)), dim3(kLocalBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace xbq

@@ -20,11 +20,19 @@ REFINE_MAX_CANDIDATES = 2048
 
 EXPORTS = (
     "xbq_version", "xbq_strerror", "xbq_last_hip_error", "xbq_code_bytes", "xbq_encode",
-    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_static", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_k_select_workspace_bytes", "xbq_k_select", "xbq_trace_enable", "xbq_trace_read",
+    "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_static", "xbq_search_ex", "xbq_search_workspace_bytes_ex", "xbq_options_default", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_k_select_workspace_bytes", "xbq_k_select", "xbq_trace_enable", "xbq_trace_read",
     "xbq_probe_out_bytes", "xbq_probe_valu", "xbq_probe_read", "xbq_set_option",
 )
 
 _lib = None
+
+
+class XbqOptions(ctypes.Structure):
+    """struct xbq_options of the C ABI."""
+    _fields_ = [("struct_bytes", ctypes.c_uint32), ("selector", ctypes.c_int32), ("kernel", ctypes.c_int32),
+                ("first", ctypes.c_int32), ("qsplit", ctypes.c_int32), ("hist_max_queries", ctypes.c_int32),
+                ("kselect_lists_min", ctypes.c_int32), ("local_groups", ctypes.c_int32),
+                ("growth", ctypes.c_double), ("refine_growth", ctypes.c_double)]
 
 
 class XbqError(RuntimeError):
@@ -67,6 +75,12 @@ def lib() -> ctypes.CDLL:
         L.xbq_search.restype = i32
         L.xbq_search_asym.argtypes = [vp, i64, i32, vp, i64, i32, i32, i32, vp, vp, vp, sz, vp]
         L.xbq_search_asym.restype = i32
+        L.xbq_options_default.argtypes = [ctypes.POINTER(XbqOptions)]
+        L.xbq_options_default.restype = None
+        L.xbq_search_workspace_bytes_ex.argtypes = [i64, i64, i32, i32, i32, ctypes.POINTER(XbqOptions)]
+        L.xbq_search_workspace_bytes_ex.restype = sz
+        L.xbq_search_ex.argtypes = [vp, i64, i32, vp, i64, i32, i32, i32, vp, vp, vp, sz, ctypes.POINTER(XbqOptions), vp]
+        L.xbq_search_ex.restype = i32
         L.xbq_search_static.argtypes = [vp, i64, vp, i64, i32, i32, i32, vp, vp, vp]
         L.xbq_search_static.restype = i32
         L.xbq_search_refine_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
@@ -158,6 +172,43 @@ def xbq_search(db_codes, n: int, q_codes, m: int, d: int, bits: int, k: int, wor
                           ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                           _stream())
     _check(rc, "xbq_search")
+    return idx, score
+
+
+def xbq_options_default(**fields) -> XbqOptions:
+    """The built-in defaults, with the given fields replaced."""
+    o = XbqOptions()
+    lib().xbq_options_default(ctypes.byref(o))
+    for name, value in fields.items():
+        if name not in dict(XbqOptions._fields_):
+            raise ValueError(f"no such option: {name}")
+        setattr(o, name, value)
+    return o
+
+
+def xbq_search_workspace_bytes_ex(n: int, m: int, d: int, q_bits: int, k: int, options=None) -> int:
+    return lib().xbq_search_workspace_bytes_ex(n, m, d, q_bits, k, ctypes.byref(options) if options is not None else None)
+
+
+def xbq_search_ex(db_codes, n: int, db_bits: int, q_codes, m: int, q_bits: int, d: int, k: int, options=None,
+                  workspace=None, idx=None, score=None):
+    """xbq_search_asym with the schedule options passed per call (an XbqOptions or None)."""
+    import torch
+    dev = db_codes.device
+    need = xbq_search_workspace_bytes_ex(n, m, d, q_bits, k, options)
+    if need == 0:
+        raise XbqError(EINVAL, "xbq_search_workspace_bytes_ex")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    if idx is None:
+        idx = torch.empty((m, k), dtype=torch.int32, device=dev)
+    if score is None:
+        score = torch.empty((m, k), dtype=torch.int32, device=dev)
+    rc = lib().xbq_search_ex(ctypes.c_void_p(db_codes.data_ptr()), n, db_bits, ctypes.c_void_p(q_codes.data_ptr()), m,
+                             q_bits, d, k, ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(score.data_ptr()),
+                             ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                             ctypes.byref(options) if options is not None else None, _stream())
+    _check(rc, "xbq_search_ex")
     return idx, score
 
 

@@ -180,7 +180,8 @@ def test_workspace_bytes(L):
     assert a == b and 0 < a < (1 << 30)             # independent of n once n is large
     assert f(1_000_000, 1_000_000, 128, 4, 100) < (1 << 30)      # bounded in m (internal batches)
     assert f(1_000_000, 1000, 960, 4, 10) > f(1_000_000, 1000, 128, 4, 10)   # repacked queries
-    assert f(1_000_000, 4, 128, 4, 10) >= 4 * 1_000_000 * 4                     # stored distances, few queries
+    assert f(8_000_000, 4, 128, 4, 10) < 32 << 20                              # few queries: per-piece lists only
+    assert f(1_000_000, 4, 128, 4, 1000) >= 4 * 1_000_000 * 4                   # k > 256: stored distances
 
 
 def test_options(L):
@@ -190,8 +191,8 @@ def test_options(L):
     assert L.xbq_set_option(None, 1.0) == xbq.EINVAL
     assert L.xbq_set_option(b"first", 1024) == xbq.OK
     assert L.xbq_set_option(b"qsplit", 0) == xbq.OK
-    assert L.xbq_set_option(b"selector", 3) == xbq.EINVAL
-    for sel in (1, 2, 0):
+    assert L.xbq_set_option(b"selector", 4) == xbq.EINVAL
+    for sel in (1, 2, 3, 0):
         assert L.xbq_set_option(b"selector", sel) == xbq.OK
     assert L.xbq_set_option(b"hist_max_queries", 16) == xbq.OK
     assert L.xbq_set_option(b"kernel", 3) == xbq.EINVAL
@@ -203,6 +204,70 @@ def test_options(L):
     assert L.xbq_set_option(b"kernel", 1) == xbq.OK
     assert L.xbq_search_workspace_bytes(100_000, 1000, 128, 4, 10) >= base + 100_000 * 64   # nibble copy of the rows
     assert L.xbq_set_option(b"kernel", 0) == xbq.OK
+
+
+def test_options_per_call_do_not_touch_the_process_defaults(L):
+    n, m, d, bits, k = 8_000_000, 4, 128, 4, 10
+    stored = xbq.xbq_options_default(selector=2)          # histogram selection over stored distances
+    local = xbq.xbq_options_default(selector=3)           # selection while the rows stream
+    before = L.xbq_search_workspace_bytes(n, m, d, bits, k)
+    a = xbq.xbq_search_workspace_bytes_ex(n, m, d, bits, k, stored)
+    b = xbq.xbq_search_workspace_bytes_ex(n, m, d, bits, k, local)
+    assert a >= m * n * 4 and b < a // 4                  # two option sets, two workspace sizes
+    assert L.xbq_search_workspace_bytes(n, m, d, bits, k) == before           # the defaults did not move
+    assert xbq.xbq_search_workspace_bytes_ex(n, m, d, bits, k, None) == before
+    # and the other way round: changing the process defaults does not reach a call with its own options
+    assert L.xbq_set_option(b"selector", 2) == xbq.OK
+    try:
+        assert L.xbq_search_workspace_bytes(n, m, d, bits, k) == a
+        assert xbq.xbq_search_workspace_bytes_ex(n, m, d, bits, k, local) == b
+    finally:
+        assert L.xbq_set_option(b"selector", 0) == xbq.OK
+
+
+def test_options_struct_is_validated(L):
+    o = xbq.xbq_options_default()
+    assert o.struct_bytes == ctypes.sizeof(xbq.XbqOptions) and o.growth == 4.0 and o.first == 1024
+    assert o.selector == 0 and o.kernel == 0 and o.local_groups == 256 and o.refine_growth == 1.5
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+
+    def search(opt):
+        return L.xbq_search_ex(fake, 1000, 4, fake, 10, 4, 128, 10, fake, fake, fake, 1 << 40,
+                               ctypes.byref(opt) if opt is not None else None, null)
+
+    for field, bad in (("growth", 1.0), ("selector", 7), ("kernel", -1), ("first", 5), ("qsplit", -2),
+                       ("local_groups", 0), ("hist_max_queries", -1), ("refine_growth", 100.0), ("struct_bytes", 8)):
+        opt = xbq.xbq_options_default(**{field: bad})
+        assert xbq.xbq_search_workspace_bytes_ex(1000, 10, 128, 4, 10, opt) == 0, field
+        assert search(opt) == xbq.EINVAL, field
+    # argument checks come before any GPU work for the _ex call as well
+    assert L.xbq_search_ex(null, 1000, 4, fake, 10, 4, 128, 10, fake, fake, fake, 1 << 40, None, null) == xbq.EINVAL
+    assert L.xbq_search_ex(fake, 1000, 4, fake, 10, 4, 128, 10, fake, fake, fake, 16, None, null) == xbq.EWORKSPACE
+    assert L.xbq_search_ex(fake, 1000, 2, fake, 10, 4, 128, 10, fake, fake, fake, 1 << 40, None, null) == xbq.EUNSUPPORTED
+
+
+def test_set_option_from_two_threads_keeps_a_consistent_default(L):
+    import threading
+    errors = []
+
+    def worker(value):
+        for _ in range(2000):
+            if L.xbq_set_option(b"first", value) != xbq.OK:
+                errors.append(value)
+            w = L.xbq_search_workspace_bytes(100_000, 1000, 128, 4, 10)
+            if w not in sizes:
+                errors.append(w)
+
+    sizes = set()
+    for v in (512, 2048):
+        assert L.xbq_set_option(b"first", v) == xbq.OK
+        sizes.add(L.xbq_search_workspace_bytes(100_000, 1000, 128, 4, 10))
+    assert len(sizes) == 2
+    ts = [threading.Thread(target=worker, args=(v,)) for v in (512, 2048)]
+    [t.start() for t in ts]
+    [t.join() for t in ts]
+    assert L.xbq_set_option(b"first", 1024) == xbq.OK
+    assert not errors
 
 
 def test_missing_library_is_loud(monkeypatch):

@@ -29,7 +29,7 @@ def _gpu():
     yield
 
 
-@pytest.fixture(params=[1, 2], ids=["threshold", "histogram"])
+@pytest.fixture(params=[1, 2, 3], ids=["threshold", "histogram", "local"])
 def selector(request):
     """Run a test once with each top-K selector forced."""
     xbq.xbq_set_option("selector", request.param)
@@ -479,6 +479,63 @@ def test_massive_ties_take_the_streaming_path_of_the_histogram_selector():
             gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 1.5), gu.oracle_search(Xdb, Xq, bits, k, 1.5), "ties")
     finally:
         xbq.xbq_set_option("selector", 0)
+
+
+def test_local_selection_on_massive_ties_and_odd_piece_sizes():
+    # one or two bits, low dimension: every piece's boundary bin holds far more rows than its list,
+    # so every workgroup re-selects its piece exactly and the merge streams over tied keys
+    Xdb = _rand(300_000, 8, seed=41)
+    Xq = _rand(5, 8, seed=42)
+    want = {(bits, k): gu.oracle_search(Xdb, Xq, bits, k, 1.5) for bits, k in ((1, 100), (2, 256), (4, 7))}
+    try:
+        xbq.xbq_set_option("selector", 3)
+        for groups in (256, 1, 37, 1024):
+            xbq.xbq_set_option("local_groups", groups)
+            for (bits, k), w in want.items():
+                _say(f"local selection, ties: groups={groups} bits={bits} k={k}")
+                gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 1.5), w, f"ties groups={groups} bits={bits} k={k}")
+    finally:
+        xbq.xbq_set_option("local_groups", 256)
+        xbq.xbq_set_option("selector", 0)
+
+
+def test_local_selection_piece_sizes_and_query_passes():
+    # random rows: piece sizes from one step of 1024 rows to the whole database, 1 .. 9 queries
+    # (more than one pass of four), every supported list size (k <= 128: 1024 keys, k <= 256: 2048)
+    rng = np.random.default_rng(47)
+    for n, d, bits in ((70_001, 128, 4), (5_000, 200, 3), (200_000, 96, 4), (33_000, 960, 3)):
+        Xdb = _rand(n, d, seed=n)
+        for m, k in ((1, 100), (9, 10), (3, 256), (4, 129), (2, 1)):
+            Xq = _rand(m, d, seed=n + m)
+            want = gu.oracle_search(Xdb, Xq, bits, k, 2.0)
+            for groups in (256, 3, 64, 1000):
+                _say(f"local selection n={n} d={d} bits={bits} m={m} k={k} groups={groups}")
+                try:
+                    xbq.xbq_set_option("selector", 3)
+                    xbq.xbq_set_option("local_groups", groups)
+                    got = gu.gpu_search(Xdb, Xq, bits, k, 2.0)
+                finally:
+                    xbq.xbq_set_option("local_groups", 256)
+                    xbq.xbq_set_option("selector", 0)
+                gu.assert_same(got, want, f"local n={n} m={m} k={k} groups={groups}")
+
+
+def test_search_ex_takes_its_options_per_call():
+    import torch
+    Xdb = _rand(60_000, 128, seed=51)
+    Xq = _rand(6, 128, seed=52)
+    want = gu.oracle_search(Xdb, Xq, 4, 20, 2.0)
+    db = xbq.xbq_encode(gu.to_dev(Xdb), 4, 2.0, xbq.BUNDLE64)
+    q = xbq.xbq_encode(gu.to_dev(Xq), 4, 2.0, xbq.ROWS)
+    for fields in ({"selector": 1}, {"selector": 2}, {"selector": 3}, {"selector": 3, "local_groups": 5},
+                   {"selector": 1, "growth": 2.0, "first": 256, "qsplit": 3}, {"kernel": 1, "selector": 1}, {}):
+        _say(f"xbq_search_ex options {fields}")
+        idx, score = xbq.xbq_search_ex(db, 60_000, 4, q, 6, 4, 128, 20, xbq.xbq_options_default(**fields))
+        torch.cuda.synchronize()
+        gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), want, f"options {fields}")
+    idx, score = xbq.xbq_search_ex(db, 60_000, 4, q, 6, 4, 128, 20, None)          # process-wide defaults
+    torch.cuda.synchronize()
+    gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), want, "default options")
 
 
 def test_automatic_selector_switches_with_query_count():
