@@ -1,17 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the whole hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2] [--no-cpu] [--no-all]
 
 One step = encode the database rows (bundle layout) + encode the queries + exhaustive
 top-K search, all through the C-ABI library, with the fp32 inputs already resident in
-HBM.  Prints ONE JSON line: queries/s of the whole step, the roofline position of the
-dominant kernel (the XOR + population-count scan, timed with HIP events inside the
-library on the stream it runs on), and the CPU oracle timed on the host cores.
+HBM.  Prints ONE JSON line: queries/s of the whole step on the headline workload, the
+roofline position of the dominant kernel (the XOR + population-count scan, timed with HIP
+events inside the library on the stream it runs on), the few-query regime the paper
+measures, the same step on the other workloads (``all_workloads``), and the CPU oracle
+timed on the host cores.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -22,11 +25,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def source_sha16() -> str:
+    """Fingerprint of the kernel sources and the ABI header: the profile summaries under
+    profiles/ carry the fingerprint of the sources they were taken from, so a figure that
+    comes from a stale profile shows."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2008_02002_amd", "csrc")
+    names = sorted(f for f in os.listdir(csrc) if f.endswith((".hip", ".h")))
+    for path in [os.path.join(csrc, f) for f in names] + [os.path.join(ROOT, "include", "xbq.h")]:
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def cpu_baseline(w, bits, db_bits, k, scale, budget_s=15.0):
     """The oracle as it stands, on the host cores, on a bounded sample of the same
     workload: the whole database is encoded and the first q queries are searched, q
     sized from a short probe so the search takes about budget_s seconds."""
-    import numpy as np
     from oracle import scale as oc
     from paper_2008_02002_amd import workloads as wl
 
@@ -116,6 +130,173 @@ def recall_by_scale(xbq, wl, w, Xdb, Xq, bits, db_bits, k, nq=256):
     return out
 
 
+def resident_inputs(wl, w):
+    """fp32 database and queries of a workload in HBM (generated in slabs of 2^20 rows)."""
+    import torch
+    Xq = torch.from_numpy(wl.queries(w)).cuda()
+    Xdb = torch.empty((w.n, w.d), dtype=torch.float32, device="cuda")
+    slab = 1 << 20
+    for lo in range(0, w.n, slab):
+        hi = min(w.n, lo + slab)
+        Xdb[lo:hi] = torch.from_numpy(wl.database(w, lo, hi)).cuda()
+    return Xdb, Xq
+
+
+def timed_steps(xbq, Xdb, Xq, db, q, w, bits, db_bits, scale, search, steps, warmup):
+    """W untimed and K timed steps (encode database, encode queries, search); returns the
+    step time, the summed scan-kernel time of the timed steps (HIP events inside the library,
+    on the stream the kernels run on) and the database-encode time."""
+    import torch
+
+    def step():
+        xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)
+        xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
+        search()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    xbq.xbq_trace_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    enc_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        enc_ev[i][0].record()
+        xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)
+        enc_ev[i][1].record()
+        xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
+        search()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    scan_ms, launches, pairs = xbq.xbq_trace_read()
+    xbq.xbq_trace_enable(False)
+    enc_ms = sum(a.elapsed_time(b) for a, b in enc_ev) / steps
+    return {"ms_per_step": max(wall_ms, gpu_ms) / steps, "scan_ms": scan_ms, "launches": launches, "pairs": pairs,
+            "enc_ms": enc_ms}
+
+
+def few_queries_leg(xbq, cm, w, Xdb, Xq, db, q, bits, db_bits, k, mq, reps=30):
+    """The regime the paper measured (Section 5: single-query requests): mq queries against the
+    resident codes.  One query is bound by the HBM stream of the database codes; from about three
+    queries on the vector ALUs bind (both fractions are reported)."""
+    import torch
+    idx1 = torch.empty((mq, k), dtype=torch.int32, device="cuda")
+    sc1 = torch.empty((mq, k), dtype=torch.int32, device="cuda")
+    wsb = xbq.xbq_search_workspace_bytes(w.n, mq, w.d, bits, k)
+    ws1 = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+
+    def one():
+        xbq.xbq_search_asym(db, w.n, db_bits, q, mq, bits, w.d, k, workspace=ws1, idx=idx1, score=sc1)
+
+    for _ in range(3):
+        one()
+    torch.cuda.synchronize()
+    xbq.xbq_trace_enable(True)
+    a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a0.record()
+    for _ in range(reps):
+        one()
+    a1.record()
+    torch.cuda.synchronize()
+    sms, sl, _ = xbq.xbq_trace_read()
+    xbq.xbq_trace_enable(False)
+    lat_ms = a0.elapsed_time(a1) / reps
+    # the same search captured once in a HIP graph and replayed (no launch gaps from the host)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one()
+    graph.replay()
+    torch.cuda.synchronize()
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record()
+    for _ in range(reps):
+        graph.replay()
+    g1.record()
+    torch.cuda.synchronize()
+    graph_ms = g0.elapsed_time(g1) / reps
+    del graph
+    # Algorithm 1 in full for the same queries (extra distance 100, fp32 refine), the request
+    # the paper times: xbq_k_select on resident codes and resident fp32 rows
+    ks_cap = min(w.n, 8192)
+    ks_ws = torch.empty(xbq.lib().xbq_k_select_workspace_bytes(w.n, mq, w.d, bits, k, 100, ks_cap),
+                        dtype=torch.uint8, device="cuda")
+    ks_sim = torch.empty((mq, k), dtype=torch.float32, device="cuda")
+    ks_cnt = torch.empty((mq,), dtype=torch.int32, device="cuda")
+
+    def ksel():
+        xbq.xbq_k_select(Xdb, db, db_bits, Xq[:mq], q, bits, k, 100, ks_cap, workspace=ks_ws, idx=idx1, sim=ks_sim,
+                         cand=ks_cnt)
+
+    for _ in range(3):
+        ksel()
+    torch.cuda.synchronize()
+    k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    k0.record()
+    for _ in range(reps):
+        ksel()
+    k1.record()
+    torch.cuda.synchronize()
+    ks_ms = k0.elapsed_time(k1) / reps
+    scan_s = sms / reps * 1e-3
+    code_bytes = w.n * cm.code_bytes_per_row(w.d, db_bits) * (sl / reps)          # one pass over the codes per scan launch
+    stored = wsb >= 4 * w.n * mq                       # the selection over stored distances also writes 4 bytes per pair
+    stream_bytes = code_bytes + (4 * w.n * mq if stored else 0)
+    lane_ops = cm.credited_lane_ops_per_pair(w.d, bits, db_bits) * w.n * mq
+    return {
+        "queries": mq, "search_ms": lat_ms, "queries_per_s": mq / (lat_ms * 1e-3),
+        "graph_replay_ms": graph_ms, "graph_queries_per_s": mq / (graph_ms * 1e-3),
+        "k_select_extra100_ms": ks_ms, "k_select_mean_candidates": float(ks_cnt.float().mean()),
+        "scan_kernel_ms": sms / reps, "scan_launches": sl / reps,
+        "scan_GBps": stream_bytes / 1e9 / scan_s,
+        "scan_hbm_frac": stream_bytes / scan_s / cm.HBM_BYTES_PER_S,
+        "scan_alu_frac": lane_ops / scan_s / cm.VALU_INT_LANE_OPS_PER_S,
+        "hbm_floor_ms": code_bytes / cm.HBM_BYTES_PER_S * 1e3,
+        "alu_floor_ms": lane_ops / cm.VALU_INT_LANE_OPS_PER_S * 1e3,
+        "path": "selection over stored distances" if stored else "selection while the rows stream (nothing stored)",
+        "note": "codes resident, encode not included; scan time from HIP events around the scan launch"}
+
+
+def workload_summary(xbq, cm, wl, name, bits, k, steps, warmup):
+    """One line of all_workloads: the same step as the headline on another workload."""
+    import torch
+    w = wl.WORKLOADS[name]
+    scale = wl.workload_scale(w)
+    Xdb, Xq = resident_inputs(wl, w)
+    db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
+    q = torch.empty(xbq.xbq_code_bytes(w.m, w.d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
+    ws = torch.empty(xbq.xbq_search_workspace_bytes(w.n, w.m, w.d, bits, k), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
+    score = torch.empty((w.m, k), dtype=torch.int32, device="cuda")
+
+    def search():
+        xbq.xbq_search_asym(db, w.n, bits, q, w.m, bits, w.d, k, workspace=ws, idx=idx, score=score)
+
+    t = timed_steps(xbq, Xdb, Xq, db, q, w, bits, bits, scale, search, steps, warmup)
+    ops = cm.credited_lane_ops_per_pair(w.d, bits, bits) * t["pairs"]
+    enc_bytes = w.n * cm.encode_bytes_per_row(w.d, bits)
+    out = {"workload": f"{w.name}: n={w.n} d={w.d} m={w.m} bits={bits} K={k}", "steps": steps, "warmup": warmup,
+           "queries_per_s": w.m / (t["ms_per_step"] * 1e-3), "ms_per_step": t["ms_per_step"],
+           "scan_ms_per_step": t["scan_ms"] / steps, "scan_launches_per_step": t["launches"] / steps,
+           "scan_alu_frac": ops / (t["scan_ms"] * 1e-3) / cm.VALU_INT_LANE_OPS_PER_S,
+           "encode_db_ms": t["enc_ms"], "encode_hbm_frac": enc_bytes / (t["enc_ms"] * 1e-3) / cm.HBM_BYTES_PER_S}
+    if w.n * w.d <= 1 << 31:                             # the large ones would double the run for one more figure
+        out["recall_at_k"] = recall_at_k(Xdb, Xq, idx, k)[0]
+    one = few_queries_leg(xbq, cm, w, Xdb, Xq, db, q, bits, bits, k, 1, reps=10)
+    out["one_query"] = {key: one[key] for key in ("search_ms", "graph_replay_ms", "scan_kernel_ms", "scan_hbm_frac",
+                                                   "k_select_extra100_ms")}
+    del Xdb, Xq, db, q, ws, idx, score
+    torch.cuda.empty_cache()
+    return out
+
+
+ALL_WORKLOADS = (("C1", 4, 10, 20), ("C3", 3, 10, 3), ("C3", 4, 10, 3), ("C4", 3, 10, 3), ("C4", 3, 100, 3),
+                 ("C5", 4, 100, 3))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +309,8 @@ def main():
     ap.add_argument("--queries", type=int, default=0, help="use only the first N queries")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-recall", action="store_true")
+    ap.add_argument("--no-all", action="store_true", help="skip the all_workloads leg (the other workloads)")
+    ap.add_argument("--no-few", action="store_true", help="skip the few-query and cross-check legs")
     ap.add_argument("--refine", type=int, default=-1, metavar="EXTRA",
                     help="time the candidate search + fp32 refine (xbq_search_refine) with this extra distance")
     ap.add_argument("--k-select", type=int, default=-1, metavar="EXTRA",
@@ -143,7 +326,6 @@ def main():
               "run it with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
 
     from paper_2008_02002_amd import costmodel as cm
@@ -163,12 +345,7 @@ def main():
         xbq.xbq_set_option(name, float(value))
 
     scale = wl.workload_scale(w)
-    Xq = torch.from_numpy(wl.queries(w)).cuda()
-    Xdb = torch.empty((w.n, w.d), dtype=torch.float32, device="cuda")
-    slab = 1 << 20
-    for lo in range(0, w.n, slab):
-        hi = min(w.n, lo + slab)
-        Xdb[lo:hi] = torch.from_numpy(wl.database(w, lo, hi)).cuda()
+    Xdb, Xq = resident_inputs(wl, w)
     db = torch.empty(xbq.xbq_code_bytes(w.n, w.d, db_bits, xbq.BUNDLE64) // 4, dtype=torch.int32, device="cuda")
     q = torch.empty(xbq.xbq_code_bytes(w.m, w.d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
     if args.k_select >= 0 and args.refine >= 0:
@@ -197,54 +374,33 @@ def main():
         else:
             xbq.xbq_search_asym(db, w.n, db_bits, q, w.m, bits, w.d, k, workspace=ws, idx=idx, score=score)
 
-    def step():
-        xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)
-        xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
-        search()
-
     if args.calib_copy:
         src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device="cuda")      # 256 MiB
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    xbq.xbq_trace_enable(True)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    enc_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record()
-    for i in range(args.steps):
-        enc_ev[i][0].record()
-        xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)
-        enc_ev[i][1].record()
-        xbq.xbq_encode(Xq, bits, scale, xbq.ROWS, out=q)
-        search()
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    gpu_ms = e0.elapsed_time(e1)
-    scan_ms, launches, pairs = xbq.xbq_trace_read()
-    xbq.xbq_trace_enable(False)
-    enc_ms = sum(a.elapsed_time(b) for a, b in enc_ev) / args.steps
-    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    t = timed_steps(xbq, Xdb, Xq, db, q, w, bits, db_bits, scale, search, args.steps, args.warmup)
+    ms_per_step, scan_ms, launches, pairs, enc_ms = t["ms_per_step"], t["scan_ms"], t["launches"], t["pairs"], t["enc_ms"]
 
     ops = cm.credited_lane_ops_per_pair(w.d, bits, db_bits) * pairs          # credited XOR + popcount lane-ops
     achieved = ops / (scan_ms * 1e-3) / 1e12
     peak = cm.VALU_INT_LANE_OPS_PER_S / 1e12
     # HBM-side bytes per scan launch come from the committed rocprofv3 --pmc summary of this
-    # same command (they cannot be read from inside the process)
-    traffic = None
+    # same command (they cannot be read from inside the process); the summary carries the
+    # fingerprint of the sources it was taken from, reported beside the figure
+    here = source_sha16()
+    traffic, traffic_sha = None, None
     tpath = os.path.join(ROOT, "profiles", f"bench_{w.name}.md")
     if os.path.exists(tpath) and not args.queries:
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_scan_launch:"):
                 traffic = float(line.split(":")[1])
-    # what the chip sustains on the two streams the rooflines are about (register-only XOR +
-    # population count; a streaming read of the fp32 database), beside the published peaks
+            if line.startswith("source_sha16:"):
+                traffic_sha = line.split(":")[1].strip()
+    # what the chip sustains on the streams the rooflines are about (register-only XOR +
+    # population count; a streaming read of the fp32 database; a bare kernel with the encoder's
+    # traffic mix), beside the published peaks
     pe0, pe1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     pout, pops = xbq.xbq_probe_valu(20000)
     torch.cuda.synchronize()
@@ -261,6 +417,19 @@ def main():
     pe1.record()
     torch.cuda.synchronize()
     read_measured = 5 * Xdb.numel() * 4 / (pe0.elapsed_time(pe1) * 1e-3)
+    enc_bytes = w.n * cm.encode_bytes_per_row(w.d, db_bits)
+    mix_measured = None
+    if w.d % 4 == 0:
+        xbq.xbq_probe_encode_traffic(Xdb, db_bits, db)
+        torch.cuda.synchronize()
+        pe0.record()
+        for _ in range(5):
+            xbq.xbq_probe_encode_traffic(Xdb, db_bits, db)
+        pe1.record()
+        torch.cuda.synchronize()
+        mix_measured = 5 * enc_bytes / (pe0.elapsed_time(pe1) * 1e-3)
+        xbq.xbq_encode(Xdb, db_bits, scale, xbq.BUNDLE64, out=db)          # the probe overwrote the codes
+        torch.cuda.synchronize()
     del pout
 
     out = {
@@ -277,6 +446,7 @@ def main():
         "vs_baseline": None,
         "dtype": "u32",
         "data": "synthetic",
+        "source_sha16": here,
         "config": {"workload": f"{w.name}: n={w.n} d={w.d} m={w.m} bits={bits}" +
                                (f"x{db_bits}" if db_bits != bits else "") + f" K={k} ({w.kind}, seed {w.seed})",
                    "scale": scale, "options": args.set,
@@ -291,6 +461,9 @@ def main():
             "unit": "T lane-op/s (32-bit integer)",
             "frac": achieved / peak,
             "traffic": traffic,
+            "traffic_from": None if traffic is None else {
+                "file": f"profiles/bench_{w.name}.md", "source_sha16": traffic_sha,
+                "sources_unchanged_since": traffic_sha == here},
             "measured_peak": valu_measured,
             "frac_of_measured_peak": achieved / valu_measured,
             "scan_ms_per_step": scan_ms / args.steps,
@@ -301,83 +474,23 @@ def main():
             "traffic_GBps": (traffic / 1e9 / (scan_ms / max(launches, 1) * 1e-3)) if traffic else None,
         },
         "encode": {"db_ms": enc_ms,
-                   "GBps": w.n * cm.encode_bytes_per_row(w.d, db_bits) / 1e9 / (enc_ms * 1e-3),
-                   "hbm_frac": w.n * cm.encode_bytes_per_row(w.d, db_bits) / (enc_ms * 1e-3) / cm.HBM_BYTES_PER_S,
+                   "GBps": enc_bytes / 1e9 / (enc_ms * 1e-3),
+                   "hbm_frac": enc_bytes / (enc_ms * 1e-3) / cm.HBM_BYTES_PER_S,
                    "measured_streaming_read_GBps": read_measured / 1e9,
-                   "frac_of_measured_read": w.n * cm.encode_bytes_per_row(w.d, db_bits) / (enc_ms * 1e-3) / read_measured},
+                   "frac_of_measured_read": enc_bytes / (enc_ms * 1e-3) / read_measured,
+                   "measured_same_traffic_no_arithmetic_GBps": None if mix_measured is None else mix_measured / 1e9,
+                   "frac_of_same_traffic_no_arithmetic": None if mix_measured is None
+                   else enc_bytes / (enc_ms * 1e-3) / mix_measured},
     }
-    # the regime the paper measured (Section 5: single-query requests): one query against the
-    # resident codes, bound by the HBM stream of the database codes
     plain = args.refine < 0 and args.k_select < 0
-    if plain:
-        for mq in (1, 8):
-            if mq > w.m:
-                continue
-            idx1 = torch.empty((mq, k), dtype=torch.int32, device="cuda")
-            sc1 = torch.empty((mq, k), dtype=torch.int32, device="cuda")
-            ws1 = torch.empty(xbq.xbq_search_workspace_bytes(w.n, mq, w.d, bits, k), dtype=torch.uint8, device="cuda")
-            reps = 30
-            for _ in range(3):
-                xbq.xbq_search_asym(db, w.n, db_bits, q, mq, bits, w.d, k, workspace=ws1, idx=idx1, score=sc1)
-            torch.cuda.synchronize()
-            xbq.xbq_trace_enable(True)
-            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a0.record()
-            for _ in range(reps):
-                xbq.xbq_search_asym(db, w.n, db_bits, q, mq, bits, w.d, k, workspace=ws1, idx=idx1, score=sc1)
-            a1.record()
-            torch.cuda.synchronize()
-            sms, sl, _ = xbq.xbq_trace_read()
-            xbq.xbq_trace_enable(False)
-            lat_ms = a0.elapsed_time(a1) / reps
-            # the same search captured once in a HIP graph and replayed (no launch gaps from the host)
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                xbq.xbq_search_asym(db, w.n, db_bits, q, mq, bits, w.d, k, workspace=ws1, idx=idx1, score=sc1)
-            graph.replay()
-            torch.cuda.synchronize()
-            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            g0.record()
-            for _ in range(reps):
-                graph.replay()
-            g1.record()
-            torch.cuda.synchronize()
-            graph_ms = g0.elapsed_time(g1) / reps
-            del graph
-            # Algorithm 1 in full for the same queries (extra distance 100, fp32 refine), the request
-            # the paper times: xbq_k_select on resident codes and resident fp32 rows
-            ks_cap = min(w.n, 8192)
-            ks_ws = torch.empty(xbq.lib().xbq_k_select_workspace_bytes(w.n, mq, w.d, bits, k, 100, ks_cap),
-                                dtype=torch.uint8, device="cuda")
-            ks_sim = torch.empty((mq, k), dtype=torch.float32, device="cuda")
-            ks_cnt = torch.empty((mq,), dtype=torch.int32, device="cuda")
-            for _ in range(3):
-                xbq.xbq_k_select(Xdb, db, db_bits, Xq[:mq], q, bits, k, 100, ks_cap, workspace=ks_ws, idx=idx1,
-                                 sim=ks_sim, cand=ks_cnt)
-            torch.cuda.synchronize()
-            k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            k0.record()
-            for _ in range(reps):
-                xbq.xbq_k_select(Xdb, db, db_bits, Xq[:mq], q, bits, k, 100, ks_cap, workspace=ks_ws, idx=idx1,
-                                 sim=ks_sim, cand=ks_cnt)
-            k1.record()
-            torch.cuda.synchronize()
-            ks_ms = k0.elapsed_time(k1) / reps
-            ks_mean = float(ks_cnt.float().mean())
-            del ks_ws, ks_sim, ks_cnt
-            stream_bytes = w.n * (cm.code_bytes_per_row(w.d, db_bits) + 4 * mq)     # codes in, distances out
-            out.setdefault("few_queries", []).append({
-                "queries": mq, "search_ms": lat_ms, "queries_per_s": mq / (lat_ms * 1e-3),
-                "graph_replay_ms": graph_ms, "graph_queries_per_s": mq / (graph_ms * 1e-3),
-                "k_select_extra100_ms": ks_ms, "k_select_mean_candidates": ks_mean,
-                "scan_kernel_ms": sms / reps, "scan_launches": sl / reps,
-                "scan_GBps": stream_bytes / 1e9 / (sms / reps * 1e-3),
-                "scan_hbm_frac": stream_bytes / (sms / reps * 1e-3) / cm.HBM_BYTES_PER_S,
-                "note": "codes resident, encode not included; scan bytes = database codes + stored distances"})
-            del idx1, sc1, ws1
+    if plain and not args.no_few:
+        for mq in (1, 4, 8):
+            if mq <= w.m:
+                out.setdefault("few_queries", []).append(
+                    few_queries_leg(xbq, cm, w, Xdb, Xq, db, q, bits, db_bits, k, mq))
     # the cross-check scan (same integers from packed 4-bit dot products, d <= 256): what the
     # other formulation costs on this chip.  Reported beside the headline, never instead of it.
-    if plain and w.d <= 256 and not any(kv.startswith("kernel=") for kv in args.set):
+    if plain and not args.no_few and w.d <= 256 and not any(kv.startswith("kernel=") for kv in args.set):
         for kernel, label, note in ((1, "cross_check_dot8", "v_dot8_i32_i4 on nibble-packed codes"),
                                     (2, "cross_check_mfma", "v_mfma_i32_32x32x32_i8 on int8-decoded codes")):
             xbq.xbq_set_option("kernel", kernel)
@@ -414,8 +527,11 @@ def main():
             out["recall_at_k"]["max_candidates"] = int(ncand.max())
         else:
             out["recall_at_k"]["by_scale"] = recall_by_scale(xbq, wl, w, Xdb, Xq, bits, db_bits, k)
-    del Xdb
+    del Xdb, Xq, db, q, ws, idx, score
     torch.cuda.empty_cache()
+    # the same step on the other workloads (fewer steps each; the headline fields above stay C2)
+    if plain and w.name == "C2" and not args.no_all and not args.queries and not args.set:
+        out["all_workloads"] = [workload_summary(xbq, cm, wl, name, b, kk, st, 1) for name, b, kk, st in ALL_WORKLOADS]
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, bits, db_bits, k, scale)
     else:

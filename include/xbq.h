@@ -217,9 +217,9 @@ int xbq_trace_enable(int on);
 int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
 
 /*
- * Measurement aids: the rates this chip sustains on the two streams the search is bound by,
- * for quoting a kernel against a measured ceiling beside the published one.  Both are
- * asynchronous on `stream` and timed by the caller; `out` is device memory of at least
+ * Measurement aids: the rates this chip sustains on the streams the path is bound by,
+ * for quoting a kernel against a measured ceiling beside the published one.  All are
+ * asynchronous on `stream` and timed by the caller; `out` (first two) is device memory of at least
  * xbq_probe_out_bytes() bytes (XBQ_EWORKSPACE otherwise) that receives a checkable result.
  *   xbq_probe_valu  the credited instruction pair of the scan (Section 3.3, Eq. 6: XOR with a
  *                   scalar operand, population count with accumulate) from registers only, 8
@@ -231,10 +231,19 @@ int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
  *   xbq_probe_read  reads `bytes` bytes (multiple of 16, 16-byte aligned, device) once with
  *                   16-byte loads; out[w], w < 2048, is the sum (mod 2^32) of the 32-bit words
  *                   read by workgroup w, so the sum of out[] is the sum of all words.
+ *   xbq_probe_encode_traffic  the memory traffic of xbq_encode (XBQ_BUNDLE64) without its
+ *                   arithmetic: reads X [n][d] once the way the encoder does (one workgroup per
+ *                   bundle of 64 rows, 16-byte loads) and overwrites all xbq_code_bytes(n, d, bits,
+ *                   XBQ_BUNDLE64) bytes of `codes`: thread t (0 <= t < 256) of bundle b stores the
+ *                   sum (mod 2^32) of the 32-bit words of the 16-byte groups t, t + 256, ... of the
+ *                   bundle's rows into code words t, t + 256, ... of the bundle.  d a multiple of
+ *                   4 and X 16-byte aligned, else XBQ_EUNSUPPORTED / XBQ_EINVAL.  The rate it
+ *                   reaches is the ceiling of the encoder's access pattern on this chip.
  */
 size_t xbq_probe_out_bytes(void);
 int xbq_probe_valu(uint32_t* out, size_t out_bytes, uint32_t seed, int iters, double* lane_ops, void* stream);
 int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_bytes, void* stream);
+int xbq_probe_encode_traffic(const float* X, int64_t n, int d, int bits, uint32_t* codes, void* stream);
 
 /*
  * Tuning knobs, host side only.  xbq_set_option changes the process-wide defaults (thread
@@ -246,7 +255,8 @@ int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_byte
  *   "selector"          0 = automatic, 1 = threshold filter with growing row groups (many
  *                       queries), 2 = histogram selection over stored distances (Section 4.1),
  *                       3 = the same selection done per workgroup while the rows stream, nothing
- *                       stored (k <= 256; the automatic choice for few queries)
+ *                       stored (k <= 256, four queries per pass; the automatic choice for up to
+ *                       four queries; a larger k falls back to 2)
  *   "hist_max_queries"  automatic choice: few-query selection up to this many queries (default
  *                       16), twice as many for k > 128, three times for k > 512
  *   "local_groups"      selector 3: most pieces the rows are split into (1..1024, default 256: one per compute unit)

@@ -152,9 +152,9 @@ struct Plan {
     size_t zero_words = 0;               // hist + cand_cnt, cleared in one go
     // local selection (few queries, nothing stored; aliases the regions above as well)
     bool local = false;
-    int local_cap = 0, local_mq = 0, local_groups = 0, local_shift2 = 0;
+    int local_cap = 0, local_mq = 0, local_groups = 0, local_shift2 = 0, local_stride = 0, local_prefix = 0;
     int64_t local_bpg = 0;               // bundles per piece
-    size_t loff_q = 0, loff_counts = 0, loff_lists = 0;
+    size_t loff_q = 0, loff_lists = 0;
     size_t total = 0;
 };
 
@@ -217,7 +217,9 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
     const bool few = o.selector == 0 && m <= hist_limit;
     const int64_t dmax = static_cast<int64_t>(d) * ((1 << bits) - 1) * ((1 << bits) - 1);
     // local selection: the default for few queries; its lists live in LDS, which bounds k
-    const bool want_local = (o.selector == 3 || (few && !keep_dist)) && k <= kLocalMaxK;
+    // automatic: one pass of it (up to kLocalMaxQueries queries); more queries are served faster by the
+    // histogram selection over stored distances, which scores eight queries per pass
+    const bool want_local = (o.selector == 3 || (few && !keep_dist && m <= kLocalMaxQueries)) && k <= kLocalMaxK;
     if (!refine && !p.dot && !p.mfma && want_local && m <= p.batch) {
         p.local = true;
         p.local_cap = next_pow2(8 * k > 1024 ? 8 * k : 1024);
@@ -236,8 +238,12 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
         size_t h = 0;
         p.loff_q = h;
         if (p.wc) h = align_up(h + b * p.nchunks * bits * p.wc * sizeof(uint32_t), 256);
-        p.loff_counts = h; h = align_up(h + static_cast<size_t>(p.local_mq) * p.local_groups * sizeof(uint32_t), 256);
-        p.loff_lists = h;  h = align_up(h + static_cast<size_t>(p.local_mq) * p.local_groups * p.local_cap * sizeof(uint64_t), 256);
+        p.local_stride = (k + 15) / 16 * 16;             // lists start on 128-byte boundaries
+        // a list contributes about k / groups keys to the result: read four times that, at least 16
+        p.local_prefix = next_pow2((4 * k + p.local_groups - 1) / p.local_groups);
+        if (p.local_prefix < 16) p.local_prefix = 16;
+        if (p.local_prefix > next_pow2(k) && next_pow2(k) >= 16) p.local_prefix = next_pow2(k);
+        p.loff_lists = h;  h = align_up(h + static_cast<size_t>(p.local_mq) * p.local_groups * p.local_stride * sizeof(uint64_t), 256);
         if (h > p.total) p.total = h;
         return p;
     }
@@ -444,7 +450,14 @@ int run_local_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t 
         la.groups = p.local_groups;
         la.bundles_per_group = p.local_bpg;
         la.lists = reinterpret_cast<uint64_t*>(ws + p.loff_lists);
-        la.counts = reinterpret_cast<uint32_t*>(ws + p.loff_counts);
+        la.list_stride = p.local_stride;
+        la.prefix = p.local_prefix;
+        {
+            const int64_t piece = p.local_bpg * kLanes;
+            const int64_t last = job.n - (p.local_groups - 1) * piece;
+            la.len_full = static_cast<int>(piece < job.k ? piece : job.k);
+            la.len_last = static_cast<int>(last < job.k ? last : job.k);
+        }
         la.idx = job.idx + qb * job.k;
         la.score = job.score + qb * job.k;
         const bool rec = g_trace.on && g_trace.used + 2 <= static_cast<int>(g_trace.ev.size());
@@ -1093,6 +1106,16 @@ int xbq_probe_read(const void* buf, size_t bytes, uint32_t* out, size_t out_byte
         return XBQ_EINVAL;
     if (out_bytes < probe_out_bytes()) return XBQ_EWORKSPACE;
     const hipError_t e = launch_probe_read(buf, bytes, out, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? XBQ_OK : fail_hip(e);
+}
+
+int xbq_probe_encode_traffic(const float* X, int64_t n, int d, int bits, uint32_t* codes, void* stream)
+{
+    if (d < 1 || bits < 1 || n < 0 || n >= (int64_t(1) << 31)) return XBQ_EINVAL;
+    if (!valid_shape(d, bits) || d % 4 != 0) return XBQ_EUNSUPPORTED;
+    if (n == 0) return XBQ_OK;
+    if (!X || !codes || reinterpret_cast<uintptr_t>(X) % 16 || reinterpret_cast<uintptr_t>(codes) % 4) return XBQ_EINVAL;
+    const hipError_t e = launch_probe_encode_traffic(X, n, d, bits, codes, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? XBQ_OK : fail_hip(e);
 }
 

@@ -21,6 +21,15 @@ __device__ __forceinline__ int next_pow2(int v)
     return p;
 }
 
+// Workgroup barrier for data exchanged through LDS only: orders LDS accesses around the barrier
+// and leaves global loads in flight (__syncthreads() also waits for those).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // acc + POPCNT(v) in one instruction.  Written as an instruction so the compiler keeps one
 // running sum per weight class; left to itself it re-associates the sums into trees of
 // three-input adds, which costs a fifth more vector instructions.

@@ -204,8 +204,11 @@ struct LocalArgs {
     int cap;                 // keys per (piece, query) list: power of two, >= 8 k, 1024..4096
     int groups;              // pieces = workgroups of scan_local
     int64_t bundles_per_group;
-    uint64_t* lists;         // [m][groups][cap], written by scan_local
-    uint32_t* counts;        // [m][groups]
+    uint64_t* lists;         // [m][groups][list_stride]: the min(k, rows of the piece) best keys of every
+                             // piece, ascending, written by scan_local
+    int list_stride;         // >= k
+    int len_full, len_last;  // list lengths: min(k, rows of a full piece), min(k, rows of the last piece)
+    int prefix;              // keys of every list local_finish reads first: power of two, groups * prefix <= 32768
     int32_t* idx;            // [m][k]
     int32_t* score;          // [m][k]
 };
@@ -255,5 +258,6 @@ size_t probe_out_bytes();
 double probe_valu_lane_ops(int iters);
 hipError_t launch_probe_valu(uint32_t* out, uint32_t seed, int iters, hipStream_t s);
 hipError_t launch_probe_read(const void* buf, size_t bytes, uint32_t* out, hipStream_t s);
+hipError_t launch_probe_encode_traffic(const float* X, int64_t n, int d, int bits, uint32_t* codes, hipStream_t s);
 
 }  // namespace xbq

@@ -14,15 +14,17 @@
 //                 doubled, the workgroup recomputes that boundary from its histogram, lowers
 //                 its threshold and compacts its list; for rows in random order about K rows
 //                 pass between two such points.  At the end the list (a superset of the
-//                 piece's K best, typically K plus the ties of one bin) is written to the
+//                 piece's K best, typically K plus the ties of one bin) goes to the
 //                 workgroup's own slot: no global atomics, nothing to clear beforehand.
 //                 If a list overflows (rows sorted towards the query, or massive ties) the
 //                 workgroup re-selects its piece exactly for that query: bounded buffer, sorted
 //                 and cut to K whenever it fills (slow, always exact).
-//   local_finish  One workgroup per query merges the lists: histogram of D >> shift2 (4096
-//                 bins) over all listed keys, boundary bin, the keys at or below it sorted by
-//                 (D, row), first K written.  Massive ties at the boundary are streamed with a
-//                 running threshold on the whole key instead.
+//                 The list leaves sorted and cut to the piece's K best keys.
+//   local_finish  One workgroup per query merges the lists, reading only their heads: histogram
+//                 of D >> shift2 (4096 bins), boundary bin, the keys at or below it sorted by
+//                 (D, row), first K written; whole lists only when a head turns out too short,
+//                 and massive ties at the boundary are streamed with a running threshold on
+//                 the whole key.
 //
 // Ties go to the lower row: keys are (D << 32) | row and every cut is made on whole keys or
 // keeps whole bins.
@@ -36,6 +38,8 @@ namespace {
 constexpr int kLocalBlock = 1024;                     // threads per workgroup
 constexpr int kLocalWaves = kLocalBlock / kLanes;
 constexpr int kFinishBins = 4096;
+constexpr int kLocalMaxCap = 2048;                    // longest per-piece list (keys); bounds k to 256
+constexpr int kRankSortMax = 512;                     // most keys sorted by ranking instead of the bitonic network
 
 __device__ __forceinline__ uint32_t load_stream(const uint32_t* p) { return __builtin_nontemporal_load(p); }
 
@@ -178,6 +182,28 @@ __device__ void reselect_piece(const LocalArgs& a, const LocalLds& s, int t, int
     }
 }
 
+// Rank of every one of `have` distinct keys in LDS (have <= kRankSortMax): rank[i] = number of
+// keys smaller than keys[i].  The comparisons of one key are split over 1024 / P threads
+// (P = have rounded up to a power of two), which add their counts into rank[].  rank[] is an LDS
+// array of at least `have` words; all threads of the workgroup call this; ends with a barrier.
+__device__ void rank_keys(const uint64_t* keys, int have, uint32_t* rank)
+{
+    const int P = next_pow2(have);
+    const int parts = kLocalBlock / P;                   // >= 2
+    const int i = threadIdx.x & (P - 1), part = threadIdx.x / P;
+    if (static_cast<int>(threadIdx.x) < have) rank[threadIdx.x] = 0;
+    __syncthreads();
+    if (i < have) {
+        const uint64_t key = keys[i];
+        const int per = (have + parts - 1) / parts;
+        const int j0 = part * per, j1 = j0 + per < have ? j0 + per : have;
+        uint32_t r = 0;
+        for (int j = j0; j < j1; ++j) r += keys[j] < key ? 1u : 0u;
+        if (r != 0) atomicAdd(&rank[i], r);
+    }
+    __syncthreads();
+}
+
 // New boundary of query `t` from its piece histogram, by one wavefront: the smallest bin b such
 // that bins 0..b hold at least k rows (the last bin if there are fewer rows).  Returns the
 // threshold (b + 1) << shift in every lane.
@@ -222,10 +248,11 @@ __device__ __forceinline__ int64_t step_bundle(int step, int r, int64_t b_begin,
 
 }  // namespace
 
-// One workgroup per piece of a.bundles_per_group bundles.  PREFETCH (whole row in registers,
+// One workgroup per piece of a.bundles_per_group bundles; MQ >= a.m is the number of queries the
+// register arrays are sized for (1 or kLocalMaxQueries).  PREFETCH (whole row in registers,
 // nchunks == 1): the rows of the next step are requested before the current step is scored, so
 // the stream keeps flowing while the workgroup sits in the barriers of a threshold update.
-template <int BQ, int BD, int WC, int R, bool PREFETCH>
+template <int BQ, int BD, int WC, int R, bool PREFETCH, int MQ>
 __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
 {
     extern __shared__ uint64_t local_lds[];
@@ -245,9 +272,9 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
     const int steps = 1 + (rounds - 1 + R - 1) / R;
     const int64_t row_stride = static_cast<int64_t>(BD) * a.W * kLanes;
 
-    uint32_t thr[kLocalMaxQueries];
+    uint32_t thr[MQ];
 #pragma unroll
-    for (int t = 0; t < kLocalMaxQueries; ++t) thr[t] = 0xffffffffu;
+    for (int t = 0; t < MQ; ++t) thr[t] = 0xffffffffu;
 
     uint32_t xn[R][BD][WC];                              // PREFETCH: rows of the step to come
     if (PREFETCH) {
@@ -267,7 +294,7 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
 
     int64_t seen = 0, seen_at_refresh = 0;
     for (int step = 0; step < steps; ++step) {
-        uint32_t acc[R][kLocalMaxQueries];
+        uint32_t acc[R][MQ];
         uint32_t row[R];
         bool live[R];
 #pragma unroll
@@ -276,7 +303,7 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
             live[r] = bundle >= 0 && bundle < b_end;     // same in every lane
             row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
 #pragma unroll
-            for (int t = 0; t < kLocalMaxQueries; ++t) acc[r][t] = 0;
+            for (int t = 0; t < MQ; ++t) acc[r][t] = 0;
         }
         if (PREFETCH) {
             uint32_t x[R][BD][WC];
@@ -300,7 +327,7 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
                 }
             }
 #pragma unroll
-            for (int t = 0; t < kLocalMaxQueries; ++t) {
+            for (int t = 0; t < MQ; ++t) {
                 if (t < a.m) {
                     uniform_ptr yq = (uniform_ptr)(a.q + static_cast<size_t>(t) * (BQ * WC));
                     uint32_t y[BQ][WC];
@@ -329,7 +356,7 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
                         }
                 }
 #pragma unroll
-                for (int t = 0; t < kLocalMaxQueries; ++t) {
+                for (int t = 0; t < MQ; ++t) {
                     if (t < a.m) {
                         uniform_ptr yq = (uniform_ptr)(a.q + (static_cast<size_t>(t) * a.nchunks + c) * (BQ * WC));
                         uint32_t y[BQ][WC];
@@ -349,7 +376,7 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
             if (!live[r]) continue;
             const bool valid = row[r] < a.n;
 #pragma unroll
-            for (int t = 0; t < kLocalMaxQueries; ++t) {
+            for (int t = 0; t < MQ; ++t) {
                 if (t < a.m)
                     append_lds(valid && acc[r][t] < thr[t], acc[r][t], row[r], s.buf + static_cast<size_t>(t) * a.cap,
                                &s.cnt[t], static_cast<uint32_t>(a.cap), &s.ovf[t], s.hist + t * kHistBins, a.shift);
@@ -360,16 +387,17 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
 
         // Threshold update, all queries at once: wavefront t finds the new boundary of query t,
         // then the whole workgroup compacts the lists (keys held in registers across the reset).
+        // Only LDS is exchanged, so the barriers leave the prefetched rows in flight.
         seen_at_refresh = seen;
-        __syncthreads();
+        lds_barrier();
         if (wave < a.m) {
             const uint32_t edge = wave_boundary(s.hist + wave * kHistBins, a.k, a.shift);
             if (lane == 0 && edge < s.thr[wave]) s.thr[wave] = edge;
         }
-        constexpr int kHeld = 4;                         // cap <= kHeld * kLocalBlock
-        uint64_t held[kLocalMaxQueries][kHeld];
+        constexpr int kHeld = kLocalMaxCap / kLocalBlock;
+        uint64_t held[MQ][kHeld];
 #pragma unroll
-        for (int t = 0; t < kLocalMaxQueries; ++t) {
+        for (int t = 0; t < MQ; ++t) {
             const int have = t < a.m ? static_cast<int>(s.cnt[t] < static_cast<uint32_t>(a.cap) ? s.cnt[t] : a.cap) : 0;
 #pragma unroll
             for (int u = 0; u < kHeld; ++u) {
@@ -377,11 +405,11 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
                 held[t][u] = i < have ? s.buf[static_cast<size_t>(t) * a.cap + i] : kPadKey;
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (threadIdx.x < kLocalMaxQueries) s.cnt[threadIdx.x] = 0;
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
-        for (int t = 0; t < kLocalMaxQueries; ++t) {
+        for (int t = 0; t < MQ; ++t) {
             if (t < a.m) {
                 thr[t] = s.thr[t];
 #pragma unroll
@@ -395,35 +423,52 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
                 }
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
 
+    // The piece's list leaves sorted and cut to its K best keys: the merge then needs only the
+    // head of each list.  Short lists are ranked (every key counts the keys before it), long
+    // ones (after an overflow, or with many ties in the boundary bin) take the LDS sort.
     const int64_t row_begin = b_begin * kLanes;
     const int64_t row_end = b_end * kLanes < a.n ? b_end * kLanes : a.n;
     for (int t = 0; t < a.m; ++t) {
         if (s.ovf[t] != 0) reselect_piece(a, s, t, row_begin, row_end);          // same value in every thread
         __syncthreads();
-        const uint32_t have = s.cnt[t];
-        const size_t slot = static_cast<size_t>(t) * a.groups + blockIdx.x;
-        for (uint32_t i = threadIdx.x; i < have; i += kLocalBlock) a.lists[slot * a.cap + i] = s.buf[static_cast<size_t>(t) * a.cap + i];
-        if (threadIdx.x == 0) a.counts[slot] = have;
+        const int have = static_cast<int>(s.cnt[t]);
+        uint64_t* buf = s.buf + static_cast<size_t>(t) * a.cap;
+        uint64_t* out = a.lists + (static_cast<size_t>(t) * a.groups + blockIdx.x) * a.list_stride;
+        if (have <= kRankSortMax) {
+            uint32_t* rank = s.hist + t * kHistBins;     // the histogram has done its work
+            rank_keys(buf, have, rank);
+            if (static_cast<int>(threadIdx.x) < have && rank[threadIdx.x] < static_cast<uint32_t>(a.k))
+                out[rank[threadIdx.x]] = buf[threadIdx.x];
+        } else {
+            const int P = next_pow2(have);
+            for (int i = have + threadIdx.x; i < P; i += kLocalBlock) buf[i] = kPadKey;
+            __syncthreads();
+            bitonic_sort_lds(buf, P);
+            const int keep = have < a.k ? have : a.k;
+            for (int i = threadIdx.x; i < keep; i += kLocalBlock) out[i] = buf[i];
+        }
     }
 }
 
-// One workgroup per query: merge of the pieces' lists, see the head of this file.  The lists
-// are read as one rectangle [groups][longest list rounded up to a power of two], one slot per
-// thread and round, every load of a pass issued before the first key is looked at; if the
-// rectangle fits 32 slots per thread the keys stay in registers for the second pass.
-constexpr int kFinishHeld = 32;
+// One workgroup per query: merge of the pieces' lists, see the head of this file.
+//
+// List g of a query holds the min(k, rows of piece g) best keys of its piece in ascending
+// order.  A list contributes about k / groups keys to the result, so only the first a.prefix
+// keys of every list are read (one round trip, keys stay in registers): histogram of
+// D >> shift2 over them, boundary bin, the keys at or below it sorted, K-th key.  If the last
+// key read of some longer list is not beyond that K-th key, unread keys of that list could
+// belong to the result: then (and when ties overfill the sort buffer) the whole lists are
+// merged instead, slowly.
+constexpr int kFinishHeld = 32;                          // prefix slots per thread, at most
 constexpr int kFinishBatch = 8;
 
-__device__ __forceinline__ uint64_t finish_slot(const LocalArgs& a, const uint64_t* lists, const uint32_t* cnt_s,
-                                                int64_t slot, int64_t nslots, int sh)
+// Every piece but the last is full; a.len_full and a.len_last are min(k, rows of the piece).
+__device__ __forceinline__ int list_length(const LocalArgs& a, int g)
 {
-    if (slot >= nslots) return kPadKey;
-    const int g = static_cast<int>(slot >> sh);
-    const uint32_t i = static_cast<uint32_t>(slot & ((int64_t(1) << sh) - 1));
-    return i < cnt_s[g] ? lists[static_cast<size_t>(g) * a.cap + i] : kPadKey;
+    return g == a.groups - 1 ? a.len_last : a.len_full;
 }
 
 __device__ __forceinline__ void finish_collect(uint64_t key, uint32_t bin, int shift2, uint64_t* keys, uint32_t* fill)
@@ -440,108 +485,168 @@ __device__ __forceinline__ void finish_collect(uint64_t key, uint32_t bin, int s
     if (pass) keys[base + rank] = key;
 }
 
+// Ascending sort of `have` distinct keys in LDS; returns where the sorted keys are (keys or
+// keys + kSortCap / 2).  Up to kRankSortMax keys are ranked (rank[] is LDS scratch of that many
+// words), more take the bitonic network.  The caller has synchronised after filling keys.
+__device__ uint64_t* sort_keys(uint64_t* keys, int have, uint32_t* rank)
+{
+    if (have <= kRankSortMax) {
+        uint64_t* sorted = keys + kSortCap / 2;
+        rank_keys(keys, have, rank);
+        if (static_cast<int>(threadIdx.x) < have) sorted[rank[threadIdx.x]] = keys[threadIdx.x];
+        __syncthreads();
+        return sorted;
+    }
+    const int P = next_pow2(have);
+    for (int i = have + threadIdx.x; i < P; i += kLocalBlock) keys[i] = kPadKey;
+    __syncthreads();
+    bitonic_sort_lds(keys, P);
+    return keys;
+}
+
+// Merge over the whole lists; leaves the K best keys sorted at the returned address.
+__device__ uint64_t* merge_whole_lists(const LocalArgs& a, const uint64_t* lists, uint64_t* keys, uint32_t* hist,
+                                       uint32_t* wave_sum, int* pick, uint32_t* fill)
+{
+    const int sh = 31 - __builtin_clz(static_cast<uint32_t>(next_pow2(a.k)));
+    const int64_t nslots = static_cast<int64_t>(a.groups) << sh;
+    const int64_t mask = (int64_t(1) << sh) - 1;
+    __syncthreads();
+    for (int i = threadIdx.x; i < kFinishBins; i += kLocalBlock) hist[i] = 0;
+    if (threadIdx.x == 0) *fill = 0;
+    __syncthreads();
+    for (int64_t s0 = 0; s0 < nslots; s0 += static_cast<int64_t>(kFinishBatch) * kLocalBlock) {
+        uint64_t k8[kFinishBatch];
+#pragma unroll
+        for (int u = 0; u < kFinishBatch; ++u) {
+            const int64_t slot = s0 + static_cast<int64_t>(u) * kLocalBlock + threadIdx.x;
+            const int g = static_cast<int>(slot >> sh);
+            const int i = static_cast<int>(slot & mask);
+            k8[u] = slot < nslots && i < list_length(a, g) ? lists[static_cast<size_t>(g) * a.list_stride + i] : kPadKey;
+        }
+#pragma unroll
+        for (int u = 0; u < kFinishBatch; ++u)
+            if (k8[u] != kPadKey) atomicAdd(&hist[static_cast<uint32_t>(k8[u] >> 32) >> a.shift2], 1u);
+    }
+    __syncthreads();
+    int within;
+    const uint32_t bin = static_cast<uint32_t>(boundary_of<kFinishBins / kLocalBlock>(hist, a.k, wave_sum, pick, &within));
+    if (within <= kSortCap) {
+        for (int64_t s0 = 0; s0 < nslots; s0 += static_cast<int64_t>(kFinishBatch) * kLocalBlock) {
+            uint64_t k8[kFinishBatch];
+#pragma unroll
+            for (int u = 0; u < kFinishBatch; ++u) {
+                const int64_t slot = s0 + static_cast<int64_t>(u) * kLocalBlock + threadIdx.x;
+                const int g = static_cast<int>(slot >> sh);
+                const int i = static_cast<int>(slot & mask);
+                k8[u] = slot < nslots && i < list_length(a, g) ? lists[static_cast<size_t>(g) * a.list_stride + i] : kPadKey;
+            }
+#pragma unroll
+            for (int u = 0; u < kFinishBatch; ++u) finish_collect(k8[u], bin, a.shift2, keys, fill);
+        }
+        __syncthreads();
+        return sort_keys(keys, static_cast<int>(*fill), hist);
+    }
+    // massive ties at the boundary: every listed key in turn against the K-th best key so far
+    uint64_t thr = kPadKey;
+    for (int g = 0; g < a.groups; ++g) {
+        const int c = list_length(a, g);
+        const uint64_t* list = lists + static_cast<size_t>(g) * a.list_stride;
+        for (int i0 = 0; i0 < c; i0 += kLocalBlock) {
+            const int i = i0 + threadIdx.x;
+            if (i < c) {
+                const uint64_t key = list[i];
+                if (key < thr) keys[atomicAdd(fill, 1u)] = key;
+            }
+            __syncthreads();
+            const int have = static_cast<int>(*fill);
+            if (have > kSortCap - kLocalBlock) {
+                const int P = next_pow2(have);
+                for (int j = have + threadIdx.x; j < P; j += kLocalBlock) keys[j] = kPadKey;
+                __syncthreads();
+                bitonic_sort_lds(keys, P);
+                thr = keys[a.k - 1];                     // have > k here: k <= 1024 < have
+                __syncthreads();
+                if (threadIdx.x == 0) *fill = static_cast<uint32_t>(a.k);
+            }
+            __syncthreads();
+        }
+    }
+    const int have = static_cast<int>(*fill);
+    const int P = next_pow2(have);
+    for (int i = have + threadIdx.x; i < P; i += kLocalBlock) keys[i] = kPadKey;
+    __syncthreads();
+    bitonic_sort_lds(keys, P);
+    return keys;
+}
+
 __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
 {
     __shared__ uint64_t keys[kSortCap];
     __shared__ uint32_t hist[kFinishBins];
-    __shared__ uint32_t cnt_s[kLocalMaxGroups];
     __shared__ uint32_t wave_sum[kLocalWaves];
     __shared__ int pick[2];
-    __shared__ uint32_t fill, longest;
+    __shared__ uint32_t fill, redo;
     const int q = blockIdx.x;
-    const uint64_t* lists = a.lists + static_cast<size_t>(q) * a.groups * a.cap;
-    const uint32_t* counts = a.counts + static_cast<size_t>(q) * a.groups;
-    for (int i = threadIdx.x; i < kFinishBins; i += kLocalBlock) hist[i] = 0;
-    if (threadIdx.x == 0) { fill = 0; longest = 0; }
-    __syncthreads();
-    for (int g = threadIdx.x; g < a.groups; g += kLocalBlock) {
-        const uint32_t c = counts[g];
-        cnt_s[g] = c;
-        atomicMax(&longest, c);
-    }
-    __syncthreads();
-    const int sh = 31 - __builtin_clz(static_cast<uint32_t>(next_pow2(static_cast<int>(longest < 64 ? 64 : longest))));
-    const int64_t nslots = static_cast<int64_t>(a.groups) << sh;
-    const bool in_registers = nslots <= static_cast<int64_t>(kFinishHeld) * kLocalBlock;
+    const uint64_t* lists = a.lists + static_cast<size_t>(q) * a.groups * a.list_stride;
+    const int sh = 31 - __builtin_clz(static_cast<uint32_t>(a.prefix));
+    const int nslots = a.groups << sh;                   // <= kFinishHeld * kLocalBlock (checked by the host)
 
+    // every load is issued before anything waits: slots past the end read key 0 of list 0, and
+    // are masked once the histogram is cleared
+    const int rounds = (nslots + kLocalBlock - 1) / kLocalBlock;     // <= kFinishHeld
     uint64_t held[kFinishHeld];
-    if (in_registers) {
 #pragma unroll
-        for (int u = 0; u < kFinishHeld; ++u)
-            held[u] = finish_slot(a, lists, cnt_s, static_cast<int64_t>(u) * kLocalBlock + threadIdx.x, nslots, sh);
+    for (int u = 0; u < kFinishHeld; ++u) {
+        if (u < rounds) {
+            const int slot = u * kLocalBlock + static_cast<int>(threadIdx.x);
+            const int g = slot >> sh, i = slot & (a.prefix - 1);
+            const bool valid = slot < nslots && i < list_length(a, g);
+            held[u] = lists[valid ? static_cast<size_t>(g) * a.list_stride + i : 0];
+        }
+    }
+    for (int i = threadIdx.x; i < kFinishBins; i += kLocalBlock) hist[i] = 0;
+    if (threadIdx.x == 0) { fill = 0; redo = 0; }
+    __syncthreads();
 #pragma unroll
-        for (int u = 0; u < kFinishHeld; ++u)
+    for (int u = 0; u < kFinishHeld; ++u) {
+        if (u < rounds) {
+            const int slot = u * kLocalBlock + static_cast<int>(threadIdx.x);
+            const int g = slot >> sh, i = slot & (a.prefix - 1);
+            if (!(slot < nslots && i < list_length(a, g))) held[u] = kPadKey;
             if (held[u] != kPadKey) atomicAdd(&hist[static_cast<uint32_t>(held[u] >> 32) >> a.shift2], 1u);
-    } else {
-        for (int64_t s0 = 0; s0 < nslots; s0 += static_cast<int64_t>(kFinishBatch) * kLocalBlock) {
-            uint64_t k8[kFinishBatch];
-#pragma unroll
-            for (int u = 0; u < kFinishBatch; ++u)
-                k8[u] = finish_slot(a, lists, cnt_s, s0 + static_cast<int64_t>(u) * kLocalBlock + threadIdx.x, nslots, sh);
-#pragma unroll
-            for (int u = 0; u < kFinishBatch; ++u)
-                if (k8[u] != kPadKey) atomicAdd(&hist[static_cast<uint32_t>(k8[u] >> 32) >> a.shift2], 1u);
         }
     }
     __syncthreads();
     int within;
     const uint32_t bin = static_cast<uint32_t>(boundary_of<kFinishBins / kLocalBlock>(hist, a.k, wave_sum, pick, &within));
 
+    const uint64_t* best = nullptr;
     if (within <= kSortCap) {
-        if (in_registers) {
 #pragma unroll
-            for (int u = 0; u < kFinishHeld; ++u) finish_collect(held[u], bin, a.shift2, keys, &fill);
-        } else {
-            for (int64_t s0 = 0; s0 < nslots; s0 += static_cast<int64_t>(kFinishBatch) * kLocalBlock) {
-                uint64_t k8[kFinishBatch];
+        for (int u = 0; u < kFinishHeld; ++u)
+            if (u < rounds) finish_collect(held[u], bin, a.shift2, keys, &fill);
+        __syncthreads();
+        best = sort_keys(keys, static_cast<int>(fill), hist);
+        // a longer list whose last key read is not beyond the K-th key may hold more of the result
+        const uint64_t kth = best[a.k - 1];
 #pragma unroll
-                for (int u = 0; u < kFinishBatch; ++u)
-                    k8[u] = finish_slot(a, lists, cnt_s, s0 + static_cast<int64_t>(u) * kLocalBlock + threadIdx.x, nslots, sh);
-#pragma unroll
-                for (int u = 0; u < kFinishBatch; ++u) finish_collect(k8[u], bin, a.shift2, keys, &fill);
+        for (int u = 0; u < kFinishHeld; ++u) {
+            if (u < rounds) {
+                const int slot = u * kLocalBlock + static_cast<int>(threadIdx.x);
+                const int g = slot >> sh, i = slot & (a.prefix - 1);
+                if (i == a.prefix - 1 && held[u] < kth && list_length(a, g) > a.prefix) redo = 1u;
             }
         }
-        __syncthreads();
-        const int have = static_cast<int>(fill);         // == within
-        const int P = next_pow2(have);
-        for (int i = have + threadIdx.x; i < P; i += kLocalBlock) keys[i] = kPadKey;
-        __syncthreads();
-        bitonic_sort_lds(keys, P);
-    } else {
-        // massive ties at the boundary: every listed key in turn against the K-th best key so far
-        uint64_t thr = kPadKey;
-        for (int g = 0; g < a.groups; ++g) {
-            const uint32_t c = cnt_s[g];
-            const uint64_t* list = lists + static_cast<size_t>(g) * a.cap;
-            for (uint32_t i0 = 0; i0 < c; i0 += kLocalBlock) {
-                const uint32_t i = i0 + threadIdx.x;
-                if (i < c) {
-                    const uint64_t key = list[i];
-                    if (key < thr) keys[atomicAdd(&fill, 1u)] = key;
-                }
-                __syncthreads();
-                const int have = static_cast<int>(fill);
-                if (have > kSortCap - kLocalBlock) {
-                    const int P = next_pow2(have);
-                    for (int j = have + threadIdx.x; j < P; j += kLocalBlock) keys[j] = kPadKey;
-                    __syncthreads();
-                    bitonic_sort_lds(keys, P);
-                    thr = keys[a.k - 1];                 // have > k here: k <= 1024 < have
-                    __syncthreads();
-                    if (threadIdx.x == 0) fill = static_cast<uint32_t>(a.k);
-                }
-                __syncthreads();
-            }
-        }
-        const int have = static_cast<int>(fill);
-        const int P = next_pow2(have);
-        for (int i = have + threadIdx.x; i < P; i += kLocalBlock) keys[i] = kPadKey;
-        __syncthreads();
-        bitonic_sort_lds(keys, P);
+    } else if (threadIdx.x == 0) {
+        redo = 1u;
     }
+    __syncthreads();
+    if (redo != 0) best = merge_whole_lists(a, lists, keys, hist, wave_sum, pick, &fill);
+
     const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
     for (int i = threadIdx.x; i < a.k; i += kLocalBlock) {
-        const uint64_t key = keys[i];
+        const uint64_t key = best[i];
         a.idx[static_cast<size_t>(q) * a.k + i] = static_cast<int32_t>(key & 0xffffffffu);
         a.score[static_cast<size_t>(q) * a.k + i] = full - 2 * static_cast<int32_t>(key >> 32);
     }
@@ -554,17 +659,19 @@ size_t local_lds_bytes(int m, int cap)
            (3 * kLocalMaxQueries + kLocalWaves + 2) * sizeof(uint32_t);
 }
 
-template <int BQ, int BD, int WC>
+template <int BQ, int BD, int WC, int MQ>
 static hipError_t launch_scan_local_w(const LocalArgs& a, hipStream_t s)
 {
     const dim3 grid(static_cast<unsigned>(a.groups)), block(kLocalBlock);
     const size_t lds = local_lds_bytes(a.m, a.cap);
-    // whole row in registers (one chunk, exactly W words): next step's rows are prefetched
+    // whole row in registers (one chunk, exactly W words): next step's rows are prefetched, two
+    // bundles per wavefront and step while both sets fit the register file
     if (a.nchunks == 1 && a.W == WC) {
-        if (BD * WC <= 16) hipLaunchKernelGGL((scan_local<BQ, BD, WC, 2, true>), grid, block, lds, s, a);
-        else               hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, true>), grid, block, lds, s, a);
+        if constexpr (BD * WC <= 16)      hipLaunchKernelGGL((scan_local<BQ, BD, WC, 2, true, MQ>), grid, block, lds, s, a);
+        else if constexpr (BD * WC <= 24) hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, true, MQ>), grid, block, lds, s, a);
+        else                              hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, false, MQ>), grid, block, lds, s, a);
     } else {
-        hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, false>), grid, block, lds, s, a);
+        hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, false, MQ>), grid, block, lds, s, a);
     }
     return hipGetLastError();
 }
@@ -573,14 +680,14 @@ template <int BQ, int BD>
 static hipError_t launch_scan_local_b(const LocalArgs& a, hipStream_t s)
 {
     switch (a.wc) {
-    case 1: return launch_scan_local_w<BQ, BD, 1>(a, s);
-    case 2: return launch_scan_local_w<BQ, BD, 2>(a, s);
-    case 3: return launch_scan_local_w<BQ, BD, 3>(a, s);
-    case 4: return launch_scan_local_w<BQ, BD, 4>(a, s);
-    case 5: return launch_scan_local_w<BQ, BD, 5>(a, s);
-    case 6: return launch_scan_local_w<BQ, BD, 6>(a, s);
-    case 7: return launch_scan_local_w<BQ, BD, 7>(a, s);
-    case 8: return launch_scan_local_w<BQ, BD, 8>(a, s);
+    case 1: return a.m == 1 ? launch_scan_local_w<BQ, BD, 1, 1>(a, s) : launch_scan_local_w<BQ, BD, 1, kLocalMaxQueries>(a, s);
+    case 2: return a.m == 1 ? launch_scan_local_w<BQ, BD, 2, 1>(a, s) : launch_scan_local_w<BQ, BD, 2, kLocalMaxQueries>(a, s);
+    case 3: return a.m == 1 ? launch_scan_local_w<BQ, BD, 3, 1>(a, s) : launch_scan_local_w<BQ, BD, 3, kLocalMaxQueries>(a, s);
+    case 4: return a.m == 1 ? launch_scan_local_w<BQ, BD, 4, 1>(a, s) : launch_scan_local_w<BQ, BD, 4, kLocalMaxQueries>(a, s);
+    case 5: return a.m == 1 ? launch_scan_local_w<BQ, BD, 5, 1>(a, s) : launch_scan_local_w<BQ, BD, 5, kLocalMaxQueries>(a, s);
+    case 6: return a.m == 1 ? launch_scan_local_w<BQ, BD, 6, 1>(a, s) : launch_scan_local_w<BQ, BD, 6, kLocalMaxQueries>(a, s);
+    case 7: return a.m == 1 ? launch_scan_local_w<BQ, BD, 7, 1>(a, s) : launch_scan_local_w<BQ, BD, 7, kLocalMaxQueries>(a, s);
+    case 8: return a.m == 1 ? launch_scan_local_w<BQ, BD, 8, 1>(a, s) : launch_scan_local_w<BQ, BD, 8, kLocalMaxQueries>(a, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -589,11 +696,11 @@ hipError_t launch_scan_local(const LocalArgs& a, hipStream_t s)
 {
     if (a.m < 1 || a.m > kLocalMaxQueries || a.n < 1 || a.wc < 1 || a.wc > 8 || a.nchunks < 1 ||
         a.nchunks * a.wc < a.W) return hipErrorInvalidValue;
-    if (a.k < 1 || a.cap < 8 * a.k || a.cap < kLocalBlock || a.cap > 4 * kLocalBlock || (a.cap & (a.cap - 1)) != 0)
+    if (a.k < 1 || a.cap < 8 * a.k || a.cap < kLocalBlock || a.cap > kLocalMaxCap || (a.cap & (a.cap - 1)) != 0)
         return hipErrorInvalidValue;
     if (local_lds_bytes(a.m, a.cap) > 64 * 1024) return hipErrorInvalidValue;
     const int64_t nbundles = (a.n + kLanes - 1) / kLanes;
-    if (a.groups > kLocalMaxGroups) return hipErrorInvalidValue;
+    if (a.groups > kLocalMaxGroups || a.list_stride < a.k) return hipErrorInvalidValue;
     if (a.groups < 1 || a.bundles_per_group < 1 || a.groups * a.bundles_per_group < nbundles ||
         (a.groups - 1) * a.bundles_per_group >= nbundles) return hipErrorInvalidValue;
     const int64_t dmax = static_cast<int64_t>(a.d) * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
@@ -614,6 +721,9 @@ hipError_t launch_scan_local(const LocalArgs& a, hipStream_t s)
 hipError_t launch_local_finish(const LocalArgs& a, hipStream_t s)
 {
     if (a.m < 1 || a.m > kLocalMaxQueries || a.groups < 1 || a.groups > kLocalMaxGroups || a.k < 1 || a.k > kSortCap / 4)
+        return hipErrorInvalidValue;
+    if (a.prefix < 1 || (a.prefix & (a.prefix - 1)) != 0 || a.list_stride < a.k ||
+        static_cast<int64_t>(a.groups) * a.prefix > static_cast<int64_t>(kFinishHeld) * kLocalBlock)
         return hipErrorInvalidValue;
     hipLaunchKernelGGL(local_finish, dim3(static_cast<unsigned>(a.m)), dim3(kLocalBlock), 0, s, a);
     return hipGetLastError();

@@ -1,8 +1,9 @@
-// Measurement aids: what this chip sustains on the two streams the rooflines of the search are
+// Measurement aids: what this chip sustains on the streams the rooflines of the search are
 // quoted against.  probe_xor_popcount issues the scan's credited instruction pair (v_xor_b32
 // with a scalar operand, v_bcnt_u32_b32 with accumulate; Section 3.3, Eq. 6) from registers
-// only; probe_read streams a buffer from memory with 16-byte loads.  Both write a checkable
-// result so that nothing can be optimised away, and both are timed by the caller.
+// only; probe_read streams a buffer from memory with 16-byte loads; probe_encode_traffic moves
+// the encoder's bytes (fp32 rows in, code words out, same access pattern) without quantizing.
+// All write a checkable result so that nothing can be optimised away, and are timed by the caller.
 
 #include "xbq_device.h"
 
@@ -67,6 +68,37 @@ __global__ __launch_bounds__(kBlock) void probe_read(const native_uint4* __restr
     if (threadIdx.x == 0) out[blockIdx.x] = total;
 }
 
+// The encoder's memory traffic without its arithmetic: one workgroup per bundle of 64 rows reads
+// the bundle's fp32 rows (contiguous, 64 * d * 4 bytes) with non-temporal 16-byte loads, eight in
+// flight per lane, and writes the bundle's code words (contiguous, 64 * bits * W * 4 bytes), as
+// encode_bundle_vec4 does.  Thread t stores the sum (mod 2^32) of the 32-bit words it read into
+// every code word t, t + 256, ... of its bundle, so the result can be checked and nothing can be
+// optimised away.
+__global__ __launch_bounds__(kBlock) void probe_encode_traffic(const native_uint4* __restrict__ X4, int64_t n,
+                                                               int f4_per_row, int words, uint32_t* __restrict__ codes)
+{
+    const int64_t bundle = blockIdx.x;
+    const int64_t row0 = bundle * kLanes;
+    const int live = n - row0 < kLanes ? static_cast<int>(n - row0) : kLanes;
+    const int total = live * f4_per_row;
+    const native_uint4* src = X4 + row0 * f4_per_row;
+    constexpr int U = 8;
+    uint32_t s = 0;
+    for (int i0 = threadIdx.x; i0 < total; i0 += kBlock * U) {
+        native_uint4 a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = i0 + u * kBlock;
+            if (i < total) a[u] = __builtin_nontemporal_load(src + i);
+            else a[u] = native_uint4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) s += a[u].x + a[u].y + a[u].z + a[u].w;
+    }
+    uint32_t* out = codes + bundle * static_cast<int64_t>(words);
+    for (int t = threadIdx.x; t < words; t += kBlock) out[t] = s;
+}
+
 size_t probe_out_bytes() { return static_cast<size_t>(kProbeBlocks) * kBlock * sizeof(uint32_t); }
 
 double probe_valu_lane_ops(int iters)
@@ -86,6 +118,16 @@ hipError_t launch_probe_read(const void* buf, size_t bytes, uint32_t* out, hipSt
     const size_t per_block = (n16 + kProbeBlocks - 1) / kProbeBlocks;
     hipLaunchKernelGGL(probe_read, dim3(kProbeBlocks), dim3(kBlock), 0, s, static_cast<const native_uint4*>(buf), n16,
                        per_block, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_encode_traffic(const float* X, int64_t n, int d, int bits, uint32_t* codes, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    if (d % 4 != 0 || reinterpret_cast<uintptr_t>(X) % 16 != 0) return hipErrorInvalidValue;
+    const int words = bits * words32(d) * kLanes;
+    hipLaunchKernelGGL(probe_encode_traffic, dim3(static_cast<unsigned>((n + kLanes - 1) / kLanes)), dim3(kBlock), 0, s,
+                       reinterpret_cast<const native_uint4*>(X), n, d / 4, words, codes);
     return hipGetLastError();
 }
 

@@ -21,7 +21,7 @@ REFINE_MAX_CANDIDATES = 2048
 EXPORTS = (
     "xbq_version", "xbq_strerror", "xbq_last_hip_error", "xbq_code_bytes", "xbq_encode",
     "xbq_search_workspace_bytes", "xbq_search", "xbq_search_asym", "xbq_search_static", "xbq_search_ex", "xbq_search_workspace_bytes_ex", "xbq_options_default", "xbq_search_refine_workspace_bytes", "xbq_search_refine", "xbq_k_select_workspace_bytes", "xbq_k_select", "xbq_trace_enable", "xbq_trace_read",
-    "xbq_probe_out_bytes", "xbq_probe_valu", "xbq_probe_read", "xbq_set_option",
+    "xbq_probe_out_bytes", "xbq_probe_valu", "xbq_probe_read", "xbq_probe_encode_traffic", "xbq_set_option",
 )
 
 _lib = None
@@ -101,6 +101,8 @@ def lib() -> ctypes.CDLL:
         L.xbq_probe_valu.restype = i32
         L.xbq_probe_read.argtypes = [vp, sz, vp, sz, vp]
         L.xbq_probe_read.restype = i32
+        L.xbq_probe_encode_traffic.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.xbq_probe_encode_traffic.restype = i32
         L.xbq_set_option.argtypes = [ctypes.c_char_p, ctypes.c_double]
         L.xbq_set_option.restype = i32
         _lib = L
@@ -341,3 +343,18 @@ def xbq_probe_read(buf, out=None):
                                 ctypes.c_void_p(out.data_ptr()), out.numel() * out.element_size(), _stream()),
            "xbq_probe_read")
     return out[:2048]
+
+
+def xbq_probe_encode_traffic(X, bits: int, codes):
+    """Launch the probe that moves the encoder's bytes without its arithmetic: reads X (fp32 CUDA
+    tensor [n, d]) and overwrites `codes` (a BUNDLE64 codes tensor for n rows)."""
+    import torch
+    if not (X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and X.dim() == 2):
+        raise ValueError("X must be a contiguous fp32 CUDA tensor [n, d]")
+    n, d = X.shape
+    if not (codes.is_cuda and codes.is_contiguous() and
+            codes.numel() * codes.element_size() >= xbq_code_bytes(n, d, bits, BUNDLE64)):
+        raise ValueError("codes too small")
+    _check(lib().xbq_probe_encode_traffic(ctypes.c_void_p(X.data_ptr()), n, d, bits, ctypes.c_void_p(codes.data_ptr()),
+                                          _stream()), "xbq_probe_encode_traffic")
+    return codes

@@ -1,4 +1,4 @@
-"""The two rate probes of the library write a checkable result: compare it with the closed
+"""The rate probes of the library write a checkable result: compare it with the closed
 definition their header comment gives (plain NumPy here, nothing of the method)."""
 import numpy as np
 import pytest
@@ -49,6 +49,27 @@ def test_probe_read_sums_every_word_once(nbytes):
     assert got == want
 
 
+@pytest.mark.parametrize("n,d,bits", [(64, 128, 4), (1000, 200, 3), (130, 96, 4), (1, 4, 1), (4097, 960, 3)])
+def test_probe_encode_traffic_reads_every_word_once_and_writes_every_code_word(n, d, bits):
+    import torch
+    print("probe encode traffic", n, d, bits, flush=True)
+    g = torch.Generator(device="cpu").manual_seed(n + d)
+    words = torch.randint(-2**31, 2**31 - 1, (n, d), dtype=torch.int32, generator=g)
+    X = words.view(torch.float32).cuda()                 # any bit patterns: the probe only adds words
+    W = (d + 31) // 32
+    codes = torch.full((xbq.xbq_code_bytes(n, d, bits, xbq.BUNDLE64) // 4,), -1, dtype=torch.int32, device="cuda")
+    xbq.xbq_probe_encode_traffic(X, bits, codes)
+    torch.cuda.synchronize()
+    got = codes.cpu().numpy().view(np.uint32).reshape(-1, bits * W * 64)
+    w32 = words.numpy().view(np.uint32).astype(np.uint64)
+    for b in range(got.shape[0]):
+        rows = w32[b * 64:(b + 1) * 64].reshape(-1, 4).sum(axis=1)      # one sum per 16-byte group of the bundle
+        want = np.zeros(256, dtype=np.uint64)
+        np.add.at(want, np.arange(rows.shape[0]) % 256, rows)
+        t = np.arange(bits * W * 64) % 256
+        assert np.array_equal(got[b].astype(np.uint64), want[t] & 0xffffffff), f"bundle {b}"
+
+
 def test_probe_argument_errors():
     import ctypes
     import torch
@@ -62,6 +83,10 @@ def test_probe_argument_errors():
     assert L.xbq_probe_read(p(big), 24, p(big), big.numel() * 4, None) == xbq.EINVAL          # not a multiple of 16
     assert L.xbq_probe_read(ctypes.c_void_p(big.data_ptr() + 4), 16, p(big), big.numel() * 4, None) == xbq.EINVAL
     assert L.xbq_probe_read(p(big), 16, p(small), 64, None) == xbq.EWORKSPACE
+    assert L.xbq_probe_encode_traffic(p(big), 64, 130, 4, p(big), None) == xbq.EUNSUPPORTED     # d not a multiple of 4
+    assert L.xbq_probe_encode_traffic(ctypes.c_void_p(big.data_ptr() + 4), 64, 128, 4, p(big), None) == xbq.EINVAL
+    assert L.xbq_probe_encode_traffic(None, 64, 128, 4, p(big), None) == xbq.EINVAL
+    assert L.xbq_probe_encode_traffic(None, 0, 128, 4, None, None) == xbq.OK
 
 
 def test_binding_loaded_before_any_other_gpu_use_shares_one_runtime():
