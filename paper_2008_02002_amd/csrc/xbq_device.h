@@ -122,6 +122,40 @@ __device__ __forceinline__ void count_level(bool pass, uint32_t D, int q, const 
     atomicAdd(&a.levels[static_cast<size_t>(q) * a.level_stride + (D < base ? 0u : D - base + 1u)], 1u);
 }
 
+// By one wavefront: the smallest bin b of h[0 .. kHistBins) such that bins 0..b hold at least k
+// rows, or -1 if all bins together hold fewer; *before = rows in bins below b.  Every lane gets
+// the result.  (Algorithm 1's boundary, Section 4.1 "Histogram and Select", at bin resolution.)
+__device__ __forceinline__ int wave_boundary_bin(const uint32_t* h, uint32_t k, uint32_t* before_out)
+{
+    constexpr int kPer = kHistBins / kLanes;             // 16 consecutive bins per lane
+    const int lane = lane_id();
+    uint32_t mine[kPer];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) { mine[i] = h[lane * kPer + i]; sum += mine[i]; }
+    uint32_t incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    uint32_t before = incl - sum;
+    int bin = -1;
+    uint32_t below = 0;
+    if (before < k && incl >= k) {
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            if (bin < 0 && before + mine[i] >= k) { bin = lane * kPer + i; below = before; }
+            before += mine[i];
+        }
+    }
+    const uint64_t found = __ballot(bin >= 0);
+    if (found == 0) { *before_out = 0; return -1; }
+    const int src = __ffsll(static_cast<long long>(found)) - 1;
+    *before_out = __shfl(below, src);
+    return __shfl(bin, src);
+}
+
 // Workgroup -> (row block, query range) of the scan kernels.  The grid is one-dimensional.
 // Hardware hands consecutive workgroup ids to the 8 XCDs in turn, each XCD with its own L2,
 // so the id is split as (id % 8, id / 8): XCD c works through row blocks c, c + 8, c + 16, ...

@@ -11,6 +11,9 @@
 //                   query whose candidate list overflowed it instead re-scores the group's
 //                   rows with a running threshold and a bounded LDS buffer (slow, always
 //                   exact, and only ever taken when the row order is adversarial)
+// Plain top-K selects with a histogram and orders only the keys of the boundary bin
+// (select_by_histogram); the candidate lists of Algorithm 1 (extra >= 0) stay sorted and are
+// merged with the LDS sorting network.
 
 #include "xbq_cut.h"
 #include "xbq_device.h"
@@ -71,6 +74,130 @@ __device__ void write_topk(const SelectArgs& a, int q, const uint64_t* keys, int
     if (a.final_group && a.extra < 0) write_result(a, q, keys);
 }
 
+// ---------------------------------------------------------------------------------------
+// Plain top-K without sorting what is thrown away.  The keys of one query (at most kSortCap:
+// the K held so far plus the survivors of a group, or the rows of the first group) sit in
+// registers, kSelHeld per thread.  A histogram of D >> shift in LDS gives the bin that holds
+// the K-th smallest distance (Algorithm 1's boundary, Section 4.1, at bin resolution); only
+// the keys of that one bin are ordered to find the K-th smallest key exactly; every key at or
+// below it is kept.  The kept keys go back to the query's list unsorted (nothing downstream
+// of a non-final group needs them sorted) and only the final group sorts its K keys.
+// Returns false, having written nothing, when the boundary bin holds more keys than the tie
+// buffer (massive ties): the caller then sorts everything.
+// ---------------------------------------------------------------------------------------
+constexpr int kSelHeld = kSortCap / kBlock;              // 16 keys per thread
+constexpr int kTieBuf = 1024;                            // keys of the boundary bin that are ordered in LDS; >= XBQ_MAX_K
+
+struct SelectLds {
+    uint32_t hist[kHistBins];
+    uint64_t tie[kTieBuf];
+    uint64_t kth;
+    uint32_t fill;
+    int bin;
+    uint32_t below;
+};
+
+__device__ __forceinline__ void append_wave_lds(bool pass, uint64_t key, uint64_t* list, uint32_t* counter)
+{
+    const uint64_t mask = __ballot(pass);
+    if (mask == 0) return;
+    const int leader = __ffsll(static_cast<long long>(mask)) - 1;
+    uint32_t base = 0;
+    if (lane_id() == leader) base = atomicAdd(counter, static_cast<uint32_t>(__popcll(mask)));
+    base = __shfl(base, leader);
+    const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+    if (pass) list[base + rank] = key;
+}
+
+__device__ bool select_by_histogram(const SelectArgs& a, int q, const uint64_t (&r)[kSelHeld], SelectLds& s)
+{
+    int shift = 0;
+    const int64_t dmax = static_cast<int64_t>(a.d) * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
+    while ((dmax >> shift) >= kHistBins) ++shift;
+    for (int t = threadIdx.x; t < kHistBins; t += kBlock) s.hist[t] = 0;
+    if (threadIdx.x == 0) s.fill = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kSelHeld; ++u)
+        if (r[u] != kPadKey) atomicAdd(&s.hist[static_cast<uint32_t>(r[u] >> 32) >> shift], 1u);
+    __syncthreads();
+    if (threadIdx.x < kLanes) {
+        uint32_t below;
+        const int bin = wave_boundary_bin(s.hist, static_cast<uint32_t>(a.k), &below);
+        if (threadIdx.x == 0) { s.bin = bin; s.below = below; }
+    }
+    __syncthreads();
+    const uint32_t bin = static_cast<uint32_t>(s.bin);   // >= 0: the caller passes at least k keys
+    const int need = a.k - static_cast<int>(s.below);    // 1 .. keys in the boundary bin
+    const int ties = static_cast<int>(s.hist[bin]);
+    if (ties > kTieBuf) return false;
+#pragma unroll
+    for (int u = 0; u < kSelHeld; ++u)
+        append_wave_lds(r[u] != kPadKey && (static_cast<uint32_t>(r[u] >> 32) >> shift) == bin, r[u], s.tie, &s.fill);
+    __syncthreads();
+    if (ties <= kBlock) {                                // one key per thread: its rank among the ties
+        if (static_cast<int>(threadIdx.x) < ties) {
+            const uint64_t key = s.tie[threadIdx.x];
+            int rank = 0;
+            for (int j = 0; j < ties; ++j) rank += s.tie[j] < key ? 1 : 0;
+            if (rank == need - 1) s.kth = key;
+        }
+    } else {
+        const int P = next_pow2(ties);
+        for (int t = ties + threadIdx.x; t < P; t += kBlock) s.tie[t] = kPadKey;
+        __syncthreads();
+        bitonic_sort_lds(s.tie, P);
+        if (threadIdx.x == 0) s.kth = s.tie[need - 1];
+    }
+    __syncthreads();
+    const uint64_t kth = s.kth;
+    if (threadIdx.x == 0) s.fill = 0;
+    __syncthreads();
+    if (!a.final_group) {
+        uint64_t* list = a.topk + static_cast<size_t>(q) * a.keep_max;
+#pragma unroll
+        for (int u = 0; u < kSelHeld; ++u) {             // exactly k keys pass
+            const bool pass = r[u] <= kth;               // the pad key is larger than every real key
+            const uint64_t mask = __ballot(pass);
+            if (mask == 0) continue;
+            const int leader = __ffsll(static_cast<long long>(mask)) - 1;
+            uint32_t base = 0;
+            if (lane_id() == leader) base = atomicAdd(&s.fill, static_cast<uint32_t>(__popcll(mask)));
+            base = __shfl(base, leader);
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                  __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+            if (pass) list[base + rank] = r[u];
+        }
+        if (threadIdx.x == 0) {
+            a.thr[q] = static_cast<uint32_t>(kth >> 32);  // a later row needs a smaller D: an equal one loses the tie
+            a.cnt[q] = 0;
+        }
+        return true;
+    }
+    // final group: the K keys, sorted, are the result
+#pragma unroll
+    for (int u = 0; u < kSelHeld; ++u) append_wave_lds(r[u] <= kth, r[u], s.tie, &s.fill);
+    __syncthreads();
+    const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
+    if (a.k <= kBlock) {
+        if (static_cast<int>(threadIdx.x) < a.k) {
+            const uint64_t key = s.tie[threadIdx.x];
+            int rank = 0;
+            for (int j = 0; j < a.k; ++j) rank += s.tie[j] < key ? 1 : 0;
+            a.idx[static_cast<size_t>(q) * a.k + rank] = static_cast<int32_t>(key & 0xffffffffu);
+            a.score[static_cast<size_t>(q) * a.k + rank] = full - 2 * static_cast<int32_t>(key >> 32);
+        }
+    } else {
+        const int P = next_pow2(a.k);
+        for (int t = a.k + threadIdx.x; t < P; t += kBlock) s.tie[t] = kPadKey;
+        __syncthreads();
+        bitonic_sort_lds(s.tie, P);
+        write_result(a, q, s.tie);
+    }
+    return true;
+}
+
 // The sort buffers of select_dense and select_merge are dynamic LDS sized by the host for the
 // launch at hand (a power of two of keys, at most kSortCap): most launches need far less than
 // kSortCap keys, and the smaller footprint lets more workgroups share a compute unit.
@@ -78,9 +205,19 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
 {
     extern __shared__ uint64_t keys[];
     __shared__ int scratch;
+    __shared__ SelectLds sel;
     const int q = blockIdx.x;
     const int P = next_pow2(a.rows);
     const uint32_t* src = a.dense + static_cast<size_t>(q) * a.dense_stride;
+    if (a.extra < 0) {
+        uint64_t r[kSelHeld];
+#pragma unroll
+        for (int u = 0; u < kSelHeld; ++u) {
+            const int t = u * kBlock + threadIdx.x;
+            r[u] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
+        }
+        if (select_by_histogram(a, q, r, sel)) return;   // same outcome in every thread
+    }
     for (int t = threadIdx.x; t < P; t += blockDim.x)
         keys[t] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
     __syncthreads();
@@ -141,6 +278,7 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int ca
 {
     extern __shared__ uint64_t keys[];               // `capacity` keys
     __shared__ int fill;
+    __shared__ SelectLds sel;
     const SelectArgs& a = r.sel;
     const int q = blockIdx.x;
     const uint32_t c = a.cnt[q];                     // same value in every lane: branches are uniform
@@ -154,8 +292,17 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int ca
     const int P = next_pow2(total);
     const uint64_t* best = a.topk + static_cast<size_t>(q) * a.keep_max;
     const uint64_t* cand = a.cand + static_cast<size_t>(q) * a.cap;
+    if (a.extra < 0) {                               // plain top-K: the held keys are in no particular order
+        uint64_t r[kSelHeld];
+#pragma unroll
+        for (int u = 0; u < kSelHeld; ++u) {
+            const int t = u * kBlock + threadIdx.x;
+            r[u] = t < held ? best[t] : (t < total ? cand[t - held] : kPadKey);
+        }
+        if (select_by_histogram(a, q, r, sel)) return;       // same outcome in every thread
+    }
     const int PB = next_pow2(static_cast<int>(c));
-    if (c != 0 && held + PB <= P) {                  // the kept keys and the padded survivors fit side by side
+    if (a.extra >= 0 && c != 0 && held + PB <= P) {  // the kept keys and the padded survivors fit side by side
         // The kept keys are already sorted.  Sort only the survivors, descending, at the end of the
         // buffer; kept keys (ascending), padding, survivors (descending, their padding first) then
         // form one bitonic sequence, and a single merge stage finishes the job.
@@ -169,7 +316,7 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int ca
         for (int t = threadIdx.x; t < P; t += blockDim.x)
             keys[t] = t < held ? best[t] : (t < total ? cand[t - held] : kPadKey);
         __syncthreads();
-        if (c != 0) bitonic_sort_lds(keys, P);
+        if (c != 0 || a.extra < 0) bitonic_sort_lds(keys, P);
     }
     write_topk(a, q, keys, total, &fill, a.extra >= 0 ? a.thr[q] : 0xffffffffu);
 }
