@@ -7,6 +7,10 @@
  * score every query against every database row with XOR + population count, and
  * select the K best rows per query.
  *
+ * Equation numbers are the paper's own running numbers: Eq. 1 sigma, Eq. 2 the product/XOR
+ * identity (Section 3.1); Eq. 5 x_B y_B from xbar (x) ybar (Section 3.2); Eq. 7 X.Y from
+ * Xbar (x) Ybar, Eq. 9 the bit-plane reconstruction xhat_b, Eq. 10 the POPCNT form (Section 3.3).
+ *
  * Common rules for every entry point
  *   - Every pointer named X, codes, db_codes, q_codes, idx, score or workspace is
  *     a DEVICE pointer owned by the caller.  The library never allocates, frees
@@ -39,7 +43,7 @@ extern "C" {
 
 /* Code layouts (both hold uint32 plane words, W = ceil(d/32) per plane, plane b =
  * bit b of every coordinate's code, coordinate 32w+t at bit t of word w, pad bits 0;
- * Section 3.3, Eq. 5):
+ * Section 3.3, Eq. 9, the bit-plane reconstruction xhat_b):
  *   XBQ_ROWS     [n][bits][W]                    exchange layout, used for queries
  *   XBQ_BUNDLE64 [ceil(n/64)][bits][W][64]       scan layout, used for the database:
  *                rows are grouped 64 at a time (one per wavefront lane) and stored
@@ -66,7 +70,7 @@ size_t xbq_code_bytes(int64_t n, int d, int bits, int layout);
 
 /*
  * Encode (Section 3.2 quantizer f_B after the scaling of Section 3.5, then the
- * bit-plane reconstruction of Section 3.3 / Eq. 5).
+ * bit-plane reconstruction of Section 3.3 / Eq. 9).
  *   X      [n][d] fp32 row-major, device, read only
  *   scale  finite, > 0; every coordinate is multiplied by it in binary32 (round to
  *          nearest even) before quantizing; 1.0f gives the bare f_B
@@ -88,8 +92,8 @@ int xbq_encode(const float* X, int64_t n, int d, int bits, float scale, int layo
 size_t xbq_search_workspace_bytes(int64_t n, int64_t m, int d, int bits, int k);
 
 /*
- * Exhaustive top-K (Section 2 problem statement; Section 3.3 Eq. 6 for the distance,
- * Eq. 2 for the score).
+ * Exhaustive top-K (Section 2 problem statement; Section 3.3, Eq. 10, the POPCNT form,
+ * for the distance; Eq. 7 for the score).
  *   db_codes  XBQ_BUNDLE64 codes of the n database rows
  *   q_codes   XBQ_ROWS codes of the m queries (same d, bits and scale as the database)
  *   idx       [m][k] int32: database row numbers, best first
@@ -221,7 +225,7 @@ int xbq_trace_read(double* scan_ms, int64_t* launches, double* pairs);
  * for quoting a kernel against a measured ceiling beside the published one.  All are
  * asynchronous on `stream` and timed by the caller; `out` (first two) is device memory of at least
  * xbq_probe_out_bytes() bytes (XBQ_EWORKSPACE otherwise) that receives a checkable result.
- *   xbq_probe_valu  the credited instruction pair of the scan (Section 3.3, Eq. 6: XOR with a
+ *   xbq_probe_valu  the credited instruction pair of the scan (Section 3.3, Eq. 10: XOR with a
  *                   scalar operand, population count with accumulate) from registers only, 8
  *                   wavefronts per SIMD.  Thread t (0 <= t < xbq_probe_out_bytes()/4) holds
  *                   x_j = (t+1)*0x9E3779B1 + j*0x85EBCA77 (mod 2^32), j < 16, and writes

@@ -22,10 +22,10 @@ design document):
   * The scale factor of Section 3.5 is one IEEE binary32 multiply before
     quantizing.
   * Plane word layout: coordinate k is bit (k mod 32) of 32-bit word k // 32;
-    pad bits are zero (Eq. 5 of Section 3.3 puts coordinate 0 at the least
+    pad bits are zero (Eq. 9, the bit-plane reconstruction of Section 3.3, puts coordinate 0 at the least
     significant end).
   * The exported score is S = d (2^Bx - 1)(2^By - 1) - 2 (Xbar (x) Ybar), the
-    numerator of Eq. 2 of Section 3.3: larger means more similar.
+    numerator of Eq. 7 (X.Y in terms of Xbar (x) Ybar, Section 3.3): larger means more similar.
   * Ties in the top-K go to the lower index; output sorted by (S desc, idx asc).
   * Algorithm 1 keeps every row within its boundary and is silent about memory.
     Two bounded forms are stated here because the implementation under test
@@ -57,7 +57,7 @@ def sigma(a: int) -> int:
 
 
 def sigma_inv(abar: int) -> int:
-    """Inverse of sigma (Eq. 2 of Section 3.1): a = 1 - 2 abar."""
+    """Inverse of sigma (Section 3.1, used in Eq. 2: a1 a2 = 1 - 2 (abar1 xor abar2)): a = 1 - 2 abar."""
     if abar not in (0, 1):
         raise ValueError("sigma_inv is defined on {0,1}")
     return 1 - 2 * abar
@@ -115,7 +115,7 @@ def decode_value(code: int, B: int) -> float:
 
 
 # --------------------------------------------------------------------------
-# Section 3.2: the scalar (x) operator and the product identity (Eq. 6)
+# Section 3.2: the scalar (x) operator and the product identity (Eq. 5)
 # --------------------------------------------------------------------------
 
 
@@ -129,7 +129,7 @@ def otimes_scalar(xbar: int, ybar: int, Bx: int, By: int) -> int:
 
 
 def product_numerator(xbar: int, ybar: int, Bx: int, By: int) -> int:
-    """Numerator of Eq. 6 (Section 3.2): 2^(Bx+By) * x_B * y_B."""
+    """Numerator of Eq. 5 (x_B y_B in terms of xbar (x) ybar, Section 3.2): 2^(Bx+By) * x_B * y_B."""
     return ((1 << Bx) - 1) * ((1 << By) - 1) - 2 * otimes_scalar(xbar, ybar, Bx, By)
 
 
@@ -168,7 +168,7 @@ def decode(codes: np.ndarray, B: int) -> np.ndarray:
 
 
 def plane_ints(codes_row, B: int) -> list[int]:
-    """Eq. 5 (Section 3.3): xhat_b = (abar_{b,d-1} ... abar_{b,0})_2 as Python ints."""
+    """Eq. 9 (Section 3.3, bit-plane reconstruction): xhat_b = (abar_{b,d-1} ... abar_{b,0})_2 as Python ints."""
     planes = []
     for b in range(B):
         v = 0
@@ -196,12 +196,12 @@ def pack_planes(codes: np.ndarray, B: int) -> np.ndarray:
 
 
 def otimes_vector(codes_x, codes_y, Bx: int, By: int) -> int:
-    """Xbar (x) Ybar = sum_k xbar_k (x) ybar_k (Section 3.3, before Eq. 2)."""
+    """Xbar (x) Ybar = sum_k xbar_k (x) ybar_k (Section 3.3, Eq. 6)."""
     return sum(otimes_scalar(int(cx), int(cy), Bx, By) for cx, cy in zip(codes_x, codes_y))
 
 
 def popcount_distance_ints(planes_x: list[int], planes_y: list[int]) -> int:
-    """Eq. 6 (Section 3.3): sum_i sum_j POPCNT(xhat_i xor yhat_j) << (i + j)."""
+    """Eq. 10 (Section 3.3, the POPCNT form): sum_i sum_j POPCNT(xhat_i xor yhat_j) << (i + j)."""
     total = 0
     for i, xi in enumerate(planes_x):
         for j, yj in enumerate(planes_y):
@@ -210,7 +210,7 @@ def popcount_distance_ints(planes_x: list[int], planes_y: list[int]) -> int:
 
 
 def distance_matrix(planes_q: np.ndarray, planes_db: np.ndarray) -> np.ndarray:
-    """Eq. 6 (Section 3.3) for every (query, database) pair: D[q, r], int64.
+    """Eq. 10 (Section 3.3, the POPCNT form) for every (query, database) pair: D[q, r], int64.
 
     ``planes_q`` is [m, Bq, W], ``planes_db`` is [n, Bd, W] (uint32 words).
     """
@@ -227,7 +227,7 @@ def distance_matrix(planes_q: np.ndarray, planes_db: np.ndarray) -> np.ndarray:
 
 
 def score_from_distance(D, d: int, Bq: int, Bd: int):
-    """Numerator of Eq. 2 (Section 3.3): S = d (2^Bq - 1)(2^Bd - 1) - 2 D."""
+    """Numerator of Eq. 7 (Section 3.3): S = d (2^Bq - 1)(2^Bd - 1) - 2 D."""
     return d * ((1 << Bq) - 1) * ((1 << Bd) - 1) - 2 * D
 
 
@@ -252,7 +252,7 @@ def topk(S: np.ndarray, K: int):
 
 
 def search(X_db, X_q, B: int, K: int, scale: float = 1.0):
-    """Whole path at definition level: encode, planes, Eq. 6 scores, top-K."""
+    """Whole path at definition level: encode, planes, Eq. 10 distances, Eq. 7 scores, top-K."""
     d = X_db.shape[1]
     p_db = pack_planes(encode(X_db, B, scale), B)
     p_q = pack_planes(encode(X_q, B, scale), B)

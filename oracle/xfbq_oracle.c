@@ -10,11 +10,11 @@
  * Steps and the passages they follow:
  *   quantize : Section 3.2 (f_B by successive approximation, sign(0) = +1),
  *              after the binary32 scaling of Section 3.5
- *   pack     : Section 3.3, Eq. 5 (bit-plane b of a vector as one integer,
+ *   pack     : Section 3.3, Eq. 9 (bit-plane b of a vector as one integer,
  *              coordinate 0 at the least significant bit), stored in 64-bit
  *              words as in Section 4.1 "Quantization"
- *   distance : Section 3.3, Eq. 6 (sum_i sum_j POPCNT(xhat_i ^ yhat_j) << (i+j))
- *   score    : numerator of Section 3.3, Eq. 2:  S = d(2^Bq-1)(2^Bd-1) - 2 D
+ *   distance : Section 3.3, Eq. 10 (sum_i sum_j POPCNT(xhat_i ^ yhat_j) << (i+j))
+ *   score    : numerator of Section 3.3, Eq. 7:  S = d(2^Bq-1)(2^Bd-1) - 2 D
  *   top-K    : Section 2 problem statement (K most similar, descending), ties
  *              to the lower index, by bounded sorted insertion
  *
@@ -84,7 +84,7 @@ void xfbq_oracle_pack(const uint8_t *codes, int64_t n, int d, int B, uint64_t *p
     }
 }
 
-/* Eq. 6 of Section 3.3 for one pair. */
+/* Eq. 10 of Section 3.3 (the POPCNT form) for one pair. */
 static int64_t distance_pair(const uint64_t *x, int Bx, const uint64_t *y, int By, int W64)
 {
     int64_t D = 0;

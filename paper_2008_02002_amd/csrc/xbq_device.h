@@ -40,7 +40,7 @@ __device__ __forceinline__ uint32_t popcount_add(uint32_t v, uint32_t acc)
     return r;
 }
 
-// Eq. 6 of Section 3.3 for one row held in x (BD planes) against the uniform query words y
+// Eq. 10 of Section 3.3 (the POPCNT form) for one row held in x (BD planes) against the uniform query words y
 // (BQ planes), WC words per plane: sum_i sum_j POPCNT(x_i ^ y_j) << (i + j), with one running
 // sum per weight class i + j and a Horner combination at the end.
 template <int BQ, int BD, int WC>
@@ -223,7 +223,7 @@ __device__ inline void bitonic_merge_lds(uint64_t* keys, int P)
     }
 }
 
-// Eq. 6 for one (row, query) with run-time sizes; the slow path of the exact rescans.
+// Eq. 10 for one (row, query) with run-time sizes; the slow path of the exact rescans.
 __device__ inline uint32_t distance_generic(const uint32_t* db, int64_t row, const uint32_t* yq, int BQ, int BD, int W)
 {
     const uint32_t* xb = db + (row / kLanes) * (static_cast<int64_t>(BD) * W * kLanes) + (row % kLanes);

@@ -1,7 +1,7 @@
 // Cross-check scan: the same integer distances from packed 4-bit dot products.
 //
 // The decoded value of a B-bit code xbar is m / 2^B with m = (2^B - 1) - 2 xbar (Section 3.2),
-// an odd integer, so the score of Eq. 2 (Section 3.3) is the plain integer inner product
+// an odd integer, so the score of Eq. 7 (Section 3.3) is the plain integer inner product
 // S = sum_k m_xk m_yk.  Writing m = 2u + 1 with u = 2^(B-1) - 1 - xbar, a signed value that
 // fits 4 bits for every B <= 4,
 //     S = 4 sum u v + 2 sum u + 2 sum v + d,      D = (d (2^Bq - 1)(2^Bd - 1) - S) / 2,

@@ -1,5 +1,5 @@
 // Encode kernels: scaling (Section 3.5), the quantizer f_B (Section 3.2) and the bit-plane
-// reconstruction (Section 3.3, Eq. 5), fused in one pass over the fp32 rows.
+// reconstruction (Section 3.3, Eq. 9), fused in one pass over the fp32 rows.
 //
 // A wavefront reads 64 consecutive coordinates of one row (256 contiguous bytes), each
 // lane quantizes its coordinate, and one ballot per plane turns the 64 per-lane bits into

@@ -19,7 +19,7 @@ constexpr int kLocalMaxQueries = 4; // queries per pass of the local selection (
 constexpr int kLocalMaxGroups = 1024;   // most pieces (workgroups) of the local selection
 
 // A candidate is ordered by the 64-bit key (D << 32) | row: smaller key = better
-// (smaller distance D, then lower row number).  D is the Eq. 6 distance.
+// (smaller distance D, then lower row number).  D is the distance of Eq. 10 (Section 3.3, the POPCNT form).
 __host__ __device__ inline uint64_t make_key(uint32_t D, uint32_t row)
 {
     return (static_cast<uint64_t>(D) << 32) | row;

@@ -1,5 +1,5 @@
 // Second cross-check scan: the integer inner product S = sum_k m_qk m_xk of the decoded codes
-// (m = (2^B - 1) - 2 xbar, |m| <= 15; Section 3.2 and Eq. 2 of Section 3.3) as an int8 matrix
+// (m = (2^B - 1) - 2 xbar, |m| <= 15; Section 3.2 and Eq. 7 of Section 3.3) as an int8 matrix
 // product on the matrix cores, D = (d (2^Bq - 1)(2^Bd - 1) - S) / 2.  Like the packed-dot
 // kernel it is opt-in (option "kernel" = 2), serves d <= 256, produces the same D for every
 // pair and shares everything downstream of the scan.  It is not the method of the paper (which

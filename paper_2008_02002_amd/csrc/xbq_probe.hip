@@ -1,6 +1,6 @@
 // Measurement aids: what this chip sustains on the streams the rooflines of the search are
 // quoted against.  probe_xor_popcount issues the scan's credited instruction pair (v_xor_b32
-// with a scalar operand, v_bcnt_u32_b32 with accumulate; Section 3.3, Eq. 6) from registers
+// with a scalar operand, v_bcnt_u32_b32 with accumulate; Section 3.3, Eq. 10) from registers
 // only; probe_read streams a buffer from memory with 16-byte loads; probe_encode_traffic moves
 // the encoder's bytes (fp32 rows in, code words out, same access pattern) without quantizing.
 // All write a checkable result so that nothing can be optimised away, and are timed by the caller.

@@ -1,4 +1,4 @@
-// Scan kernels: Eq. 6 of Section 3.3, D = sum_i sum_j POPCNT(xhat_i ^ yhat_j) << (i + j),
+// Scan kernels: Eq. 10 of Section 3.3 (the POPCNT form), D = sum_i sum_j POPCNT(xhat_i ^ yhat_j) << (i + j),
 // for every (query, database row) pair of a row range, on the vector ALUs of gfx950.
 //
 // Mapping.  One lane owns one database row (two when the code is short): its plane

@@ -1,5 +1,5 @@
 // Selection kernels: exact top-K per query on 64-bit keys (D << 32 | row), smaller first.
-// Smaller D means larger score S = d(2^B-1)^2 - 2D (Eq. 2 of Section 3.3), so ascending
+// Smaller D means larger score S = d(2^B-1)^2 - 2D (Eq. 7 of Section 3.3), so ascending
 // keys are "score descending, ties to the lower row number".
 //
 // The paper selects with a histogram of the integer distances (Section 4.1 "Histogram and

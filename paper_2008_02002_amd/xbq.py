@@ -119,6 +119,38 @@ def _check(code: int, where: str):
         raise XbqError(code, where)
 
 
+def _require_codes(t, n: int, d: int, bits: int, layout: int, name: str):
+    """Host-side check of a codes tensor: the C ABI takes raw pointers and cannot see that a
+    buffer is too small or in the wrong place, and a scan that reads past it faults the GPU."""
+    import torch
+    need = xbq_code_bytes(n, d, bits, layout)
+    if need == 0 and n != 0:
+        raise XbqError(EUNSUPPORTED, "xbq_code_bytes")
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise ValueError(f"{name} must be a contiguous int32 CUDA tensor (uint32 plane words)")
+    if t.numel() * 4 < need:
+        kind = "BUNDLE64" if layout == BUNDLE64 else "ROWS"
+        raise ValueError(f"{name} holds {t.numel() * 4} bytes, but {n} rows of d={d}, bits={bits} in the {kind} layout "
+                         f"take {need}: wrong layout or row count?")
+
+
+def _require_out(t, shape, dtype, name: str):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous() and
+            tuple(t.shape) == tuple(shape)):
+        raise ValueError(f"{name} must be a contiguous CUDA tensor of shape {tuple(shape)} and dtype {dtype}")
+
+
+def _require_workspace(t, need: int):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise ValueError("workspace must be a contiguous CUDA tensor")
+    if t.numel() * t.element_size() < need:
+        raise XbqError(EWORKSPACE, "workspace")
+    if t.data_ptr() % 256:
+        raise ValueError("workspace must be 256-byte aligned")
+
+
 def xbq_version() -> int:
     return lib().xbq_version()
 
@@ -163,12 +195,17 @@ def xbq_search(db_codes, n: int, q_codes, m: int, d: int, bits: int, k: int, wor
     need = xbq_search_workspace_bytes(n, m, d, bits, k)
     if need == 0:
         raise XbqError(EINVAL, "xbq_search_workspace_bytes")
+    _require_codes(db_codes, n, d, bits, BUNDLE64, "db_codes")
+    _require_codes(q_codes, m, d, bits, ROWS, "q_codes")
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     if idx is None:
         idx = torch.empty((m, k), dtype=torch.int32, device=dev)
     if score is None:
         score = torch.empty((m, k), dtype=torch.int32, device=dev)
+    _require_workspace(workspace, need)
+    _require_out(idx, (m, k), torch.int32, "idx")
+    _require_out(score, (m, k), torch.int32, "score")
     rc = lib().xbq_search(ctypes.c_void_p(db_codes.data_ptr()), n, ctypes.c_void_p(q_codes.data_ptr()), m,
                           d, bits, k, ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(score.data_ptr()),
                           ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
@@ -200,12 +237,17 @@ def xbq_search_ex(db_codes, n: int, db_bits: int, q_codes, m: int, q_bits: int, 
     need = xbq_search_workspace_bytes_ex(n, m, d, q_bits, k, options)
     if need == 0:
         raise XbqError(EINVAL, "xbq_search_workspace_bytes_ex")
+    _require_codes(db_codes, n, d, db_bits, BUNDLE64, "db_codes")
+    _require_codes(q_codes, m, d, q_bits, ROWS, "q_codes")
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     if idx is None:
         idx = torch.empty((m, k), dtype=torch.int32, device=dev)
     if score is None:
         score = torch.empty((m, k), dtype=torch.int32, device=dev)
+    _require_workspace(workspace, need)
+    _require_out(idx, (m, k), torch.int32, "idx")
+    _require_out(score, (m, k), torch.int32, "score")
     rc = lib().xbq_search_ex(ctypes.c_void_p(db_codes.data_ptr()), n, db_bits, ctypes.c_void_p(q_codes.data_ptr()), m,
                              q_bits, d, k, ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(score.data_ptr()),
                              ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
@@ -217,6 +259,11 @@ def xbq_search_ex(db_codes, n: int, db_bits: int, q_codes, m: int, q_bits: int, 
 def xbq_search_static(db_codes, n: int, q_codes, m: int, d: int, bits: int, k: int, idx, score):
     """xbq_search without a workspace and without any allocation: idx and score ([m, k] int32
     CUDA tensors) come from the caller, the scratch memory is the library's built-in buffer."""
+    import torch
+    _require_codes(db_codes, n, d, bits, BUNDLE64, "db_codes")
+    _require_codes(q_codes, m, d, bits, ROWS, "q_codes")
+    _require_out(idx, (m, k), torch.int32, "idx")
+    _require_out(score, (m, k), torch.int32, "score")
     rc = lib().xbq_search_static(ctypes.c_void_p(db_codes.data_ptr()), n, ctypes.c_void_p(q_codes.data_ptr()), m,
                                  d, bits, k, ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(score.data_ptr()),
                                  _stream())
@@ -232,12 +279,17 @@ def xbq_search_asym(db_codes, n: int, db_bits: int, q_codes, m: int, q_bits: int
     need = xbq_search_workspace_bytes(n, m, d, q_bits, k)
     if need == 0:
         raise XbqError(EINVAL, "xbq_search_workspace_bytes")
+    _require_codes(db_codes, n, d, db_bits, BUNDLE64, "db_codes")
+    _require_codes(q_codes, m, d, q_bits, ROWS, "q_codes")
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     if idx is None:
         idx = torch.empty((m, k), dtype=torch.int32, device=dev)
     if score is None:
         score = torch.empty((m, k), dtype=torch.int32, device=dev)
+    _require_workspace(workspace, need)
+    _require_out(idx, (m, k), torch.int32, "idx")
+    _require_out(score, (m, k), torch.int32, "score")
     rc = lib().xbq_search_asym(ctypes.c_void_p(db_codes.data_ptr()), n, db_bits, ctypes.c_void_p(q_codes.data_ptr()),
                                m, q_bits, d, k, ctypes.c_void_p(idx.data_ptr()), ctypes.c_void_p(score.data_ptr()),
                                ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
@@ -259,6 +311,10 @@ def xbq_search_refine(X_db, db_codes, db_bits: int, X_q, q_codes, q_bits: int, k
     need = lib().xbq_search_refine_workspace_bytes(n, m, d, q_bits, k)
     if need == 0:
         raise XbqError(EINVAL, "xbq_search_refine_workspace_bytes")
+    if X_q.dim() != 2 or X_db.dim() != 2 or X_q.shape[1] != d:
+        raise ValueError("X_db and X_q must be [n, d] and [m, d] with the same d")
+    _require_codes(db_codes, n, d, db_bits, BUNDLE64, "db_codes")
+    _require_codes(q_codes, m, d, q_bits, ROWS, "q_codes")
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=X_db.device)
     if idx is None:
@@ -267,6 +323,10 @@ def xbq_search_refine(X_db, db_codes, db_bits: int, X_q, q_codes, q_bits: int, k
         sim = torch.empty((m, k), dtype=torch.float32, device=X_db.device)
     if cand is None:
         cand = torch.empty((m,), dtype=torch.int32, device=X_db.device)
+    _require_workspace(workspace, need)
+    _require_out(idx, (m, k), torch.int32, "idx")
+    _require_out(sim, (m, k), torch.float32, "similarity")
+    _require_out(cand, (m,), torch.int32, "candidates")
     p = lambda t: ctypes.c_void_p(t.data_ptr())
     rc = lib().xbq_search_refine(p(X_db), p(db_codes), n, db_bits, p(X_q), p(q_codes), m, q_bits, d, k,
                                  int(extra_distance), p(idx), p(sim), p(cand), p(workspace),
@@ -288,6 +348,10 @@ def xbq_k_select(X_db, db_codes, db_bits: int, X_q, q_codes, q_bits: int, k: int
     need = lib().xbq_k_select_workspace_bytes(n, m, d, q_bits, k, int(extra_distance), int(max_candidates))
     if need == 0:
         raise XbqError(EINVAL, "xbq_k_select_workspace_bytes")
+    if X_q.dim() != 2 or X_db.dim() != 2 or X_q.shape[1] != d:
+        raise ValueError("X_db and X_q must be [n, d] and [m, d] with the same d")
+    _require_codes(db_codes, n, d, db_bits, BUNDLE64, "db_codes")
+    _require_codes(q_codes, m, d, q_bits, ROWS, "q_codes")
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=X_db.device)
     if idx is None:
@@ -296,6 +360,10 @@ def xbq_k_select(X_db, db_codes, db_bits: int, X_q, q_codes, q_bits: int, k: int
         sim = torch.empty((m, k), dtype=torch.float32, device=X_db.device)
     if cand is None:
         cand = torch.empty((m,), dtype=torch.int32, device=X_db.device)
+    _require_workspace(workspace, need)
+    _require_out(idx, (m, k), torch.int32, "idx")
+    _require_out(sim, (m, k), torch.float32, "similarity")
+    _require_out(cand, (m,), torch.int32, "candidates")
     p = lambda t: ctypes.c_void_p(t.data_ptr())
     rc = lib().xbq_k_select(p(X_db), p(db_codes), n, db_bits, p(X_q), p(q_codes), m, q_bits, d, k,
                             int(extra_distance), int(max_candidates), p(idx), p(sim), p(cand), p(workspace),

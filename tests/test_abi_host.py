@@ -270,6 +270,23 @@ def test_set_option_from_two_threads_keeps_a_consistent_default(L):
     assert not errors
 
 
+def test_binding_rejects_tensors_the_library_could_not_check(L):
+    """The C ABI sees raw pointers only; the binding refuses what would make a kernel read or
+    write outside a buffer before anything reaches the GPU (host memory, wrong type)."""
+    import torch
+    cpu_codes = torch.zeros(1 << 16, dtype=torch.int32)
+    with pytest.raises(ValueError, match="db_codes"):
+        xbq.xbq_search(cpu_codes, 1000, cpu_codes, 4, 128, 4, 10)
+    with pytest.raises(ValueError, match="db_codes"):
+        xbq.xbq_search_asym(cpu_codes.float(), 1000, 3, cpu_codes, 4, 4, 128, 10)
+    with pytest.raises(ValueError, match="db_codes"):
+        xbq.xbq_search_ex(cpu_codes, 1000, 4, cpu_codes, 4, 4, 128, 10)
+    with pytest.raises(ValueError, match="contiguous fp32 CUDA"):
+        xbq.xbq_search_refine(torch.zeros(10, 8), cpu_codes, 4, torch.zeros(2, 8), cpu_codes, 4, 2, 0)
+    with pytest.raises(ValueError, match="contiguous fp32 CUDA"):
+        xbq.xbq_encode(torch.zeros(10, 8), 4)
+
+
 def test_missing_library_is_loud(monkeypatch):
     monkeypatch.setattr(xbq, "_lib", None)
     monkeypatch.setattr(xbq, "LIB_PATH", "/nonexistent/libxbq.so")

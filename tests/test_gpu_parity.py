@@ -255,7 +255,7 @@ def test_refine_on_clustered_rows_and_sorted_rows():
 
 def _one_bit_rows_at_distances(D, d, rng):
     """Rows of +-1/sqrt(d) whose one-bit code differs from the all-positive query in exactly
-    D[r] coordinates (Eq. 6 with one plane on each side is the Hamming distance)."""
+    D[r] coordinates (Eq. 10, the POPCNT form, with one plane on each side is the Hamming distance)."""
     n = len(D)
     X = np.full((n, d), 1.0, dtype=np.float32)
     for r in range(n):
@@ -555,6 +555,34 @@ def test_many_queries_cross_the_internal_batch():
     Xdb = _rand(n, d, seed=1)
     Xq = _rand(m, d, seed=2)
     gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 5, 2.0), gu.oracle_search(Xdb, Xq, 4, 5, 2.0), "batches")
+
+
+def test_binding_checks_buffer_sizes_before_the_call():
+    import torch
+    n, d, bits, k, m = 1000, 128, 4, 10, 3
+    Xh = _rand(n, d, seed=1)
+    X = gu.to_dev(Xh)
+    rows = xbq.xbq_encode(X, bits, 1.0, xbq.ROWS)                 # the default layout: not what the scan reads
+    db = xbq.xbq_encode(X, bits, 1.0, xbq.BUNDLE64)
+    q = xbq.xbq_encode(X[:m], bits, 1.0, xbq.ROWS)
+    assert rows.numel() < db.numel()
+    with pytest.raises(ValueError, match="BUNDLE64"):
+        xbq.xbq_search(rows, n, q, m, d, bits, k)                 # too small for n rows in bundles
+    with pytest.raises(ValueError, match="q_codes"):
+        xbq.xbq_search(db, n, q[:-1], m, d, bits, k)
+    with pytest.raises(ValueError, match="db_codes"):
+        xbq.xbq_search(db, n + 64, q, m, d, bits, k)              # more rows claimed than encoded
+    with pytest.raises(ValueError, match="idx"):
+        xbq.xbq_search(db, n, q, m, d, bits, k, idx=torch.empty((m, k + 1), dtype=torch.int32, device="cuda"))
+    with pytest.raises(ValueError, match="score"):
+        xbq.xbq_search(db, n, q, m, d, bits, k, score=torch.empty((m, k), dtype=torch.float32, device="cuda"))
+    with pytest.raises(xbq.XbqError):
+        xbq.xbq_search(db, n, q, m, d, bits, k, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    with pytest.raises(ValueError, match="candidates"):
+        xbq.xbq_k_select(X, db, bits, X[:m], q, bits, k, 5, 100, cand=torch.empty((m + 1,), dtype=torch.int32, device="cuda"))
+    idx, score = xbq.xbq_search(db, n, q, m, d, bits, k)          # and the well-formed call goes through
+    torch.cuda.synchronize()
+    gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), gu.oracle_search(Xh, Xh[:m], bits, k, 1.0), "well-formed call")
 
 
 def test_empty_inputs_are_noops():

@@ -129,10 +129,10 @@ def test_vectorised_encode_matches_scalar_and_uses_fp32_scaling():
     assert int(od.encode(np.array([[x]]), 3, float(s))[0, 0]) == od.quantize_code(0.25, 3)
 
 
-# ------------------------------------------------- Section 3.2, operator and Eq. 6
+# ------------------------------------------------- Section 3.2, operator and Eq. 5
 @pytest.mark.parametrize("Bx,By", [(3, 3), (4, 4), (4, 3), (1, 1), (2, 5), (8, 8)])
 def test_scalar_product_identity_exhaustive(Bx, By):
-    # Eq. 6: x_B * y_B = ((2^Bx-1)(2^By-1) - 2 xbar(x)ybar) / 2^(Bx+By); left side from
+    # Eq. 5: x_B * y_B = ((2^Bx-1)(2^By-1) - 2 xbar(x)ybar) / 2^(Bx+By); left side from
     # the digit sums, right side from the XOR operator, over every pair of codes.
     for xbar in range(1 << Bx):
         for ybar in range(1 << By):
@@ -162,7 +162,7 @@ def test_query4_doc3_affine_relation():
         assert dist == 52.5 * d - 64.0 * ss
 
 
-# ------------------------------------------------------- Section 3.3, planes, Eq. 6
+# ------------------------------------------------------- Section 3.3, planes (Eq. 9), POPCNT form (Eq. 10)
 @pytest.mark.parametrize("d", [1, 5, 31, 32, 33, 64, 65, 96, 100, 200])
 @pytest.mark.parametrize("Bx,By", [(3, 3), (4, 4), (4, 3), (1, 1), (2, 7)])
 def test_popcount_form_equals_per_coordinate_operator_and_integer_dot(d, Bx, By):
@@ -171,8 +171,8 @@ def test_popcount_form_equals_per_coordinate_operator_and_integer_dot(d, Bx, By)
     cy = rng.integers(0, 1 << By, d)
     per_coord = od.otimes_vector(cx, cy, Bx, By)
     planes = od.popcount_distance_ints(od.plane_ints(cx, Bx), od.plane_ints(cy, By))
-    assert planes == per_coord                                              # Eq. 6 = Eq. 3
-    # Eq. 2: the score is the integer dot product of the decoded numerators
+    assert planes == per_coord                                              # Eq. 10 = Eq. 8
+    # Eq. 7: the score is the integer dot product of the decoded numerators
     mx = [sum((1 << i) if not (int(c) >> i) & 1 else -(1 << i) for i in range(Bx)) for c in cx]
     my = [sum((1 << i) if not (int(c) >> i) & 1 else -(1 << i) for i in range(By)) for c in cy]
     dot = sum(a * b for a, b in zip(mx, my))

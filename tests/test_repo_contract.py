@@ -56,3 +56,22 @@ def test_header_cites_the_paper_for_every_compute_entry_point():
         decl = text.index(name + "(")
         block = text[max(0, decl - 3000):decl]
         assert re.search(r"Section|Algorithm|Eq\.", block), name
+
+
+def test_equation_citations_use_the_papers_running_numbers():
+    """The paper numbers its displayed equations 1..11 across sections.  Every citation in the
+    sources must be one of the numbers this build uses, each with one meaning: 1 sigma, 2 the
+    product/XOR identity, 5 the scalar product identity, 6 the vector operator, 7 the vector
+    score relation, 8 the per-coordinate XOR form, 9 the bit-plane reconstruction, 10 the POPCNT
+    form.  Section-relative numbers ("Eq. 6 of Section 3.3") are ambiguous and rejected."""
+    tops = [PKG, os.path.join(ROOT, "oracle"), os.path.join(ROOT, "include"), os.path.join(ROOT, "tests")]
+    meaning = {"1", "2", "5", "6", "7", "8", "9", "10"}
+    for path in [p for t in tops for p in _sources(t, (".py", ".hip", ".h", ".c", ".cpp"))]:
+        if path.endswith("test_repo_contract.py"):
+            continue
+        text = open(path).read()
+        for num in re.findall(r"Eq\. (\d+)", text):
+            assert num in meaning, (path, num)
+        assert not re.search(r"Eq\. (5|6) of Section 3\.3|Eq\. 2 of Section 3\.3|Eq\. 6 \(Section 3\.[23]\)", text), path
+    header = open(os.path.join(ROOT, "include", "xbq.h")).read()
+    assert "Eq. 10" in header and "Eq. 9" in header and "Eq. 7" in header
