@@ -198,12 +198,49 @@ __device__ bool select_by_histogram(const SelectArgs& a, int q, const uint64_t (
     return true;
 }
 
+// Plain top-K of `total` keys (key(t), t < total, in any order) through a bounded LDS buffer:
+// the path for massive ties, when one histogram bin holds more keys than can be ranked.  Keys
+// enter while they beat the K-th best so far; the buffer is sorted and cut to K whenever another
+// round of one key per thread might not fit.  Leaves the K best keys sorted in keys[].
+// capacity >= k + 2 * kBlock.
+template <typename KeyAt>
+__device__ void stream_topk(const SelectArgs& a, int total, KeyAt key_at, uint64_t* keys, int capacity, int* fill)
+{
+    if (threadIdx.x == 0) *fill = 0;
+    __syncthreads();
+    uint64_t bar = kPadKey;                              // only keys below it can still be among the K best
+    for (int t0 = 0; t0 < total; t0 += kBlock) {
+        const int t = t0 + threadIdx.x;
+        if (t < total) {
+            const uint64_t key = key_at(t);
+            if (key < bar) keys[atomicAdd(fill, 1)] = key;
+        }
+        __syncthreads();
+        const int have = *fill;                          // <= capacity: at most capacity - kBlock before this round
+        if (have > capacity - kBlock) {
+            const int P = next_pow2(have);
+            for (int i = have + threadIdx.x; i < P; i += kBlock) keys[i] = kPadKey;
+            __syncthreads();
+            bitonic_sort_lds(keys, P);
+            bar = keys[a.k - 1];                         // have > k here
+            __syncthreads();
+            if (threadIdx.x == 0) *fill = a.k;
+        }
+        __syncthreads();
+    }
+    const int have = *fill;
+    const int P = next_pow2(have);
+    for (int i = have + threadIdx.x; i < P; i += kBlock) keys[i] = kPadKey;
+    __syncthreads();
+    bitonic_sort_lds(keys, P);
+}
+
 // The sort buffers of select_dense and select_merge are dynamic LDS sized by the host for the
 // launch at hand (a power of two of keys, at most kSortCap): most launches need far less than
 // kSortCap keys, and the smaller footprint lets more workgroups share a compute unit.
-__global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
+__global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a, int capacity)
 {
-    extern __shared__ uint64_t keys[];
+    extern __shared__ uint64_t keys[];               // `capacity` keys
     __shared__ int scratch;
     __shared__ SelectLds sel;
     const int q = blockIdx.x;
@@ -217,6 +254,10 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a)
             r[u] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
         }
         if (select_by_histogram(a, q, r, sel)) return;   // same outcome in every thread
+        stream_topk(a, a.rows, [&](int t) { return make_key(src[t], static_cast<uint32_t>(a.row_begin + t)); }, keys,
+                    capacity, &scratch);
+        write_topk(a, q, keys, a.k, &scratch, 0xffffffffu);
+        return;
     }
     for (int t = threadIdx.x; t < P; t += blockDim.x)
         keys[t] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
@@ -300,9 +341,12 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int ca
             r[u] = t < held ? best[t] : (t < total ? cand[t - held] : kPadKey);
         }
         if (select_by_histogram(a, q, r, sel)) return;       // same outcome in every thread
+        stream_topk(a, total, [&](int t) { return t < held ? best[t] : cand[t - held]; }, keys, capacity, &fill);
+        write_topk(a, q, keys, a.k, &fill, 0xffffffffu);
+        return;
     }
     const int PB = next_pow2(static_cast<int>(c));
-    if (a.extra >= 0 && c != 0 && held + PB <= P) {  // the kept keys and the padded survivors fit side by side
+    if (c != 0 && held + PB <= P) {  // the kept keys and the padded survivors fit side by side
         // The kept keys are already sorted.  Sort only the survivors, descending, at the end of the
         // buffer; kept keys (ascending), padding, survivors (descending, their padding first) then
         // form one bitonic sequence, and a single merge stage finishes the job.
@@ -316,9 +360,9 @@ __global__ __launch_bounds__(kBlock) void select_merge(const MergeArgs r, int ca
         for (int t = threadIdx.x; t < P; t += blockDim.x)
             keys[t] = t < held ? best[t] : (t < total ? cand[t - held] : kPadKey);
         __syncthreads();
-        if (c != 0 || a.extra < 0) bitonic_sort_lds(keys, P);
+        if (c != 0) bitonic_sort_lds(keys, P);
     }
-    write_topk(a, q, keys, total, &fill, a.extra >= 0 ? a.thr[q] : 0xffffffffu);
+    write_topk(a, q, keys, total, &fill, a.thr[q]);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -377,13 +421,24 @@ __global__ __launch_bounds__(kBlock) void refine_topk(const RefineArgs a)
     if (a.count != nullptr && threadIdx.x == 0) a.count[q] = have;
 }
 
+// LDS keys of a selection launch.  Plain top-K keeps its keys in registers and needs the buffer
+// only for its slow paths (streaming over massive ties, exact rescan): K plus two rounds of one
+// key per thread.  Candidate lists are sorted whole: list plus survivors (or the dense rows).
+static int select_capacity(const SelectArgs& a, int whole)
+{
+    const int need = a.extra < 0 ? a.k + 2 * kBlock : (whole > a.keep_max + 2 * kBlock ? whole : a.keep_max + 2 * kBlock);
+    int capacity = 1;
+    while (capacity < need) capacity <<= 1;
+    return capacity;
+}
+
 hipError_t launch_select_dense(const SelectArgs& a, hipStream_t s)
 {
     if (a.m <= 0) return hipSuccess;
     if (a.rows < a.k || a.rows > kSortCap) return hipErrorInvalidValue;
-    int keys = 1;
-    while (keys < a.rows) keys <<= 1;
-    hipLaunchKernelGGL(select_dense, dim3(a.m), dim3(kBlock), keys * sizeof(uint64_t), s, a);
+    const int capacity = a.extra < 0 ? select_capacity(a, 0) : select_capacity(a, a.rows);
+    if (capacity > kSortCap) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(select_dense, dim3(a.m), dim3(kBlock), capacity * sizeof(uint64_t), s, a, capacity);
     return hipGetLastError();
 }
 
@@ -400,10 +455,10 @@ hipError_t launch_select_merge(const MergeArgs& r, hipStream_t s)
 {
     if (r.sel.m <= 0) return hipSuccess;
     if (r.sel.keep_max + r.sel.cap > kSortCap || r.row_end > r.n || r.row_begin < 0) return hipErrorInvalidValue;
-    // room for the kept keys plus a full survivor list; the exact rescan of an overflowed query
-    // works in the same buffer and needs the kept keys plus two rounds of one key per thread
-    int capacity = 1;
-    while (capacity < r.sel.keep_max + r.sel.cap || capacity < r.sel.keep_max + 2 * kBlock) capacity <<= 1;
+    // candidate lists: room for the kept keys plus a full survivor list; the exact rescan of an
+    // overflowed query works in the same buffer and needs the kept keys plus two rounds of one key
+    // per thread
+    const int capacity = select_capacity(r.sel, r.sel.keep_max + r.sel.cap);
     hipLaunchKernelGGL(select_merge, dim3(r.sel.m), dim3(kBlock), capacity * sizeof(uint64_t), s, r, capacity);
     return hipGetLastError();
 }
