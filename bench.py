@@ -26,14 +26,13 @@ if ROOT not in sys.path:
 
 
 def source_sha16() -> str:
-    """Fingerprint of the kernel sources and the ABI header: the profile summaries under
-    profiles/ carry the fingerprint of the sources they were taken from, so a figure that
+    """Fingerprint of the kernel and host sources of the library (csrc/): the profile summaries
+    under profiles/ carry the fingerprint of the sources they were taken from, so a figure that
     comes from a stale profile shows."""
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2008_02002_amd", "csrc")
-    names = sorted(f for f in os.listdir(csrc) if f.endswith((".hip", ".h")))
-    for path in [os.path.join(csrc, f) for f in names] + [os.path.join(ROOT, "include", "xbq.h")]:
-        h.update(open(path, "rb").read())
+    for name in sorted(f for f in os.listdir(csrc) if f.endswith((".hip", ".h"))):
+        h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()[:16]
 
 
