@@ -222,7 +222,9 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
     const bool want_local = (o.selector == 3 || (few && !keep_dist && m <= kLocalMaxQueries)) && k <= kLocalMaxK;
     if (!refine && !p.dot && !p.mfma && want_local && m <= p.batch) {
         p.local = true;
-        p.local_cap = next_pow2(8 * k > 1024 ? 8 * k : 1024);
+        // one query: a list of 2048 keys lets all sixteen wavefronts take part in the first epoch
+        const int floor_cap = m == 1 ? 2048 : 1024;
+        p.local_cap = next_pow2(8 * k > floor_cap ? 8 * k : floor_cap);
         p.local_mq = kLocalMaxQueries;
         while (p.local_mq > 1 && local_lds_bytes(p.local_mq, p.local_cap) > 64 * 1024) --p.local_mq;
         if (m < p.local_mq) p.local_mq = static_cast<int>(m);

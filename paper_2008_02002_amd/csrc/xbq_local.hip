@@ -10,10 +10,10 @@
 //                 query, a histogram of D >> shift of the rows it let through and a list of
 //                 their keys, both in LDS.  A row of the global top-K is also in the top-K of
 //                 its own piece, so a row may be dropped as soon as K rows of the same piece
-//                 lie in lower bins.  After 1024 rows, and then every time the rows seen have
-//                 doubled, the workgroup recomputes that boundary from its histogram, lowers
-//                 its threshold and compacts its list; for rows in random order about K rows
-//                 pass between two such points.  At the end the list (a superset of the
+//                 lie in lower bins.  After the first 1024 or 2048 rows, and then every time the
+//                 rows handed out have grown by a quarter, that boundary is recomputed from the
+//                 histogram and the threshold lowered (by whichever wavefront notices first, no
+//                 barrier); for rows in random order about K ln(rows / 1024) rows pass in all.  At the end the list (a superset of the
 //                 piece's K best, typically K plus the ties of one bin) goes to the
 //                 workgroup's own slot: no global atomics, nothing to clear beforehand.
 //                 If a list overflows (rows sorted towards the query, or massive ties) the
@@ -52,6 +52,8 @@ struct LocalLds {
     uint32_t* ovf;        // [kLocalMaxQueries] set when a key did not fit
     uint32_t* wave_sum;   // [kLocalWaves]
     int* pick;            // [2]
+    uint32_t* next;       // next chunk of the piece to hand out
+    uint32_t* mark;       // chunks handed out when the thresholds were last recomputed
 };
 
 __device__ __forceinline__ LocalLds carve(uint64_t* base, int m, int cap)
@@ -64,6 +66,8 @@ __device__ __forceinline__ LocalLds carve(uint64_t* base, int m, int cap)
     s.ovf = s.thr + kLocalMaxQueries;
     s.wave_sum = s.ovf + kLocalMaxQueries;
     s.pick = reinterpret_cast<int*>(s.wave_sum + kLocalWaves);
+    s.next = reinterpret_cast<uint32_t*>(s.pick + 2);
+    s.mark = s.next + 1;
     return s;
 }
 
@@ -204,56 +208,32 @@ __device__ void rank_keys(const uint64_t* keys, int have, uint32_t* rank)
     __syncthreads();
 }
 
-// New boundary of query `t` from its piece histogram, by one wavefront: the smallest bin b such
-// that bins 0..b hold at least k rows (the last bin if there are fewer rows).  Returns the
-// threshold (b + 1) << shift in every lane.
+// New threshold of a query from its piece histogram, by one wavefront: (b + 1) << shift for the
+// smallest bin b such that bins 0..b hold at least k rows; no threshold while there are fewer.
 __device__ __forceinline__ uint32_t wave_boundary(const uint32_t* h, int k, int shift)
 {
-    constexpr int kPer = kHistBins / kLanes;             // 16 consecutive bins per lane
-    const int lane = lane_id();
-    uint32_t mine[kPer];
-    uint32_t sum = 0;
-#pragma unroll
-    for (int i = 0; i < kPer; ++i) { mine[i] = h[lane * kPer + i]; sum += mine[i]; }
-    uint32_t incl = sum;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t v = __shfl_up(incl, off);
-        if (lane >= off) incl += v;
-    }
-    uint32_t before = incl - sum;
-    const uint32_t kk = static_cast<uint32_t>(k);
-    int bin = -1;
-    if (before < kk && incl >= kk) {
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            if (bin < 0 && before + mine[i] >= kk) bin = lane * kPer + i;
-            before += mine[i];
-        }
-    }
-    const uint64_t found = __ballot(bin >= 0);
-    if (found == 0) return static_cast<uint32_t>(kHistBins) << shift;      // fewer than k rows so far
-    bin = __shfl(bin, __ffsll(static_cast<long long>(found)) - 1);
-    return (static_cast<uint32_t>(bin) + 1u) << shift;
-}
-
-// Rows of one step of one wavefront: bundle j of the wavefront is b_begin + j * 16 + wave; step 0
-// is bundle 0 alone (it only has to give K rows), step s >= 1 is bundles 1 + (s-1) R .. s R.
-template <int R>
-__device__ __forceinline__ int64_t step_bundle(int step, int r, int64_t b_begin, int wave)
-{
-    if (step == 0) return r == 0 ? b_begin + wave : -1;
-    return b_begin + (1 + static_cast<int64_t>(step - 1) * R + r) * kLocalWaves + wave;
+    uint32_t below;
+    const int bin = wave_boundary_bin(h, static_cast<uint32_t>(k), &below);
+    return (static_cast<uint32_t>(bin < 0 ? kHistBins - 1 : bin) + 1u) << shift;
 }
 
 }  // namespace
 
 // One workgroup per piece of a.bundles_per_group bundles; MQ >= a.m is the number of queries the
-// register arrays are sized for (1 or kLocalMaxQueries).  PREFETCH (whole row in registers,
-// nchunks == 1): the rows of the next step are requested before the current step is scored, so
-// the stream keeps flowing while the workgroup sits in the barriers of a threshold update.
+// register arrays are sized for (1 or kLocalMaxQueries).
+//
+// The piece is cut into chunks of R bundles which the wavefronts of the workgroup take from an
+// LDS counter: the wavefronts share SIMDs and memory paths unevenly, and with a fixed assignment
+// the slowest one, several chunks behind after a few dozen steps, kept the other fifteen waiting
+// at every threshold update and at the end with nothing left to load.  Chunks are grouped in
+// epochs (the first fills the lists without a threshold, later ones grow sixteenfold): between
+// epochs the workgroup stops to recompute thresholds and compact its lists; inside an epoch the
+// thresholds are lowered without any barrier.
+// PREFETCH (whole row in registers, nchunks == 1): the rows of a wavefront's next chunk are
+// requested before the current one is scored, so the stream keeps flowing while the workgroup
+// sits in the barriers of a threshold update.
 template <int BQ, int BD, int WC, int R, bool PREFETCH, int MQ>
-__global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
+__device__ __forceinline__ void scan_local_body(const LocalArgs& a)
 {
     extern __shared__ uint64_t local_lds[];
     const LocalLds s = carve(local_lds, a.m, a.cap);
@@ -264,24 +244,30 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
         s.thr[threadIdx.x] = 0xffffffffu;
         s.ovf[threadIdx.x] = 0;
     }
+    // the first epoch fills the lists without a threshold: as many chunks as the list holds rows
+    const int warm = a.cap / (R * kLanes) < kLocalWaves ? a.cap / (R * kLanes) : kLocalWaves;
+    if (threadIdx.x == 0) {
+        *s.next = kLocalWaves;                           // chunks 0 .. 15 are handed out by wavefront number
+        *s.mark = static_cast<uint32_t>(warm);
+    }
 
     const int64_t nbundles = (a.n + kLanes - 1) / kLanes;
     const int64_t b_begin = static_cast<int64_t>(blockIdx.x) * a.bundles_per_group;
     const int64_t b_end = b_begin + a.bundles_per_group < nbundles ? b_begin + a.bundles_per_group : nbundles;
-    const int rounds = static_cast<int>((b_end - b_begin + kLocalWaves - 1) / kLocalWaves);   // bundles per wavefront
-    const int steps = 1 + (rounds - 1 + R - 1) / R;
+    const int chunks = static_cast<int>((b_end - b_begin + R - 1) / R);
     const int64_t row_stride = static_cast<int64_t>(BD) * a.W * kLanes;
 
     uint32_t thr[MQ];
 #pragma unroll
     for (int t = 0; t < MQ; ++t) thr[t] = 0xffffffffu;
 
-    uint32_t xn[R][BD][WC];                              // PREFETCH: rows of the step to come
-    if (PREFETCH) {
+    int cur = wave;                                      // chunk this wavefront works on (same in every lane)
+    uint32_t xn[R][BD][WC];                              // PREFETCH: rows of chunk `cur`, on their way
+    if (PREFETCH && cur < chunks) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int64_t bundle = step_bundle<R>(0, r, b_begin, wave);
-            if (bundle >= 0 && bundle < b_end) {
+            const int64_t bundle = b_begin + static_cast<int64_t>(cur) * R + r;
+            if (bundle < b_end) {
                 const uint32_t* xb = a.db + bundle * row_stride + lane;
 #pragma unroll
                 for (int b = 0; b < BD; ++b)
@@ -290,75 +276,71 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
 
-    int64_t seen = 0, seen_at_refresh = 0;
-    for (int step = 0; step < steps; ++step) {
-        uint32_t acc[R][MQ];
-        uint32_t row[R];
-        bool live[R];
+    // epoch: chunks [.., epoch_end).  Between epochs the whole workgroup stops, recomputes the
+    // thresholds and compacts the lists; inside an epoch single wavefronts lower the thresholds
+    // whenever the rows handed out have grown by a quarter (no barrier: a histogram that is being
+    // added to can only give a boundary that is too high, never one that drops a row it should keep).
+    // Epochs grow sixteenfold, and one that would leave less than itself for the next is extended
+    // to the end of the piece.
+    for (int epoch_end = warm; ; epoch_end *= 16) {
+        if (epoch_end > chunks || (epoch_end > warm && chunks < 2 * epoch_end)) epoch_end = chunks;
+        while (cur < epoch_end) {
+            uint32_t acc[R][MQ];
+            uint32_t row[R];
+            bool live[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int64_t bundle = step_bundle<R>(step, r, b_begin, wave);
-            live[r] = bundle >= 0 && bundle < b_end;     // same in every lane
-            row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
+            for (int r = 0; r < R; ++r) {
+                const int64_t bundle = b_begin + static_cast<int64_t>(cur) * R + r;
+                live[r] = bundle < b_end;                // same in every lane
+                row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
 #pragma unroll
-            for (int t = 0; t < MQ; ++t) acc[r][t] = 0;
-        }
-        if (PREFETCH) {
-            uint32_t x[R][BD][WC];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int b = 0; b < BD; ++b)
-#pragma unroll
-                    for (int w = 0; w < WC; ++w) x[r][b][w] = xn[r][b][w];
-            if (step + 1 < steps) {
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const int64_t bundle = step_bundle<R>(step + 1, r, b_begin, wave);
-                    if (bundle >= 0 && bundle < b_end) {
-                        const uint32_t* xb = a.db + bundle * row_stride + lane;
-#pragma unroll
-                        for (int b = 0; b < BD; ++b)
-#pragma unroll
-                            for (int w = 0; w < WC; ++w) xn[r][b][w] = load_stream(xb + (b * WC + w) * kLanes);
+                for (int t = 0; t < MQ; ++t) acc[r][t] = 0;
+            }
+            // the next chunk of this wavefront: one LDS atomic by the first lane
+            int nxt = 0;
+            if (lane == 0) nxt = static_cast<int>(atomicAdd(s.next, 1u));
+            nxt = __builtin_amdgcn_readfirstlane(nxt);
+            // lower the thresholds when enough new rows are out (one wavefront wins the job)
+            const uint32_t mark = *s.mark;
+            if (static_cast<uint32_t>(nxt) >= mark + (mark >> 2) && epoch_end > warm) {
+                int won = 0;
+                if (lane == 0) won = atomicCAS(s.mark, mark, static_cast<uint32_t>(nxt)) == mark ? 1 : 0;
+                if (__builtin_amdgcn_readfirstlane(won)) {
+                    for (int t = 0; t < a.m; ++t) {
+                        const uint32_t edge = wave_boundary(s.hist + t * kHistBins, a.k, a.shift);
+                        if (lane == 0) atomicMin(&s.thr[t], edge);
                     }
                 }
             }
 #pragma unroll
-            for (int t = 0; t < MQ; ++t) {
-                if (t < a.m) {
-                    uniform_ptr yq = (uniform_ptr)(a.q + static_cast<size_t>(t) * (BQ * WC));
-                    uint32_t y[BQ][WC];
-#pragma unroll
-                    for (int b = 0; b < BQ; ++b)
-#pragma unroll
-                        for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-                        if (live[r]) acc[r][t] = xor_popcount<BQ, BD, WC>(x[r], y);
-                }
-            }
-        } else {
-            for (int c = 0; c < a.nchunks; ++c) {
+            for (int t = 0; t < MQ; ++t) thr[t] = s.thr[t < a.m ? t : 0];
+            if (PREFETCH) {
                 uint32_t x[R][BD][WC];
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    if (!live[r]) continue;
-                    const uint32_t* xb = a.db + step_bundle<R>(step, r, b_begin, wave) * row_stride + lane;
+                for (int r = 0; r < R; ++r)
 #pragma unroll
                     for (int b = 0; b < BD; ++b)
 #pragma unroll
-                        for (int w = 0; w < WC; ++w) {
-                            const int ww = c * WC + w;
-                            x[r][b][w] = ww < a.W ? load_stream(xb + (b * a.W + ww) * kLanes) : 0u;
+                        for (int w = 0; w < WC; ++w) x[r][b][w] = xn[r][b][w];
+                if (nxt < chunks) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const int64_t bundle = b_begin + static_cast<int64_t>(nxt) * R + r;
+                        if (bundle < b_end) {
+                            const uint32_t* xb = a.db + bundle * row_stride + lane;
+#pragma unroll
+                            for (int b = 0; b < BD; ++b)
+#pragma unroll
+                                for (int w = 0; w < WC; ++w) xn[r][b][w] = load_stream(xb + (b * WC + w) * kLanes);
                         }
+                    }
                 }
 #pragma unroll
                 for (int t = 0; t < MQ; ++t) {
                     if (t < a.m) {
-                        uniform_ptr yq = (uniform_ptr)(a.q + (static_cast<size_t>(t) * a.nchunks + c) * (BQ * WC));
+                        uniform_ptr yq = (uniform_ptr)(a.q + static_cast<size_t>(t) * (BQ * WC));
                         uint32_t y[BQ][WC];
 #pragma unroll
                         for (int b = 0; b < BQ; ++b)
@@ -366,29 +348,57 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
                             for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
 #pragma unroll
                         for (int r = 0; r < R; ++r)
-                            if (live[r]) acc[r][t] += xor_popcount<BQ, BD, WC>(x[r], y);
+                            if (live[r]) acc[r][t] = xor_popcount<BQ, BD, WC>(x[r], y);
+                    }
+                }
+            } else {
+                for (int c = 0; c < a.nchunks; ++c) {
+                    uint32_t x[R][BD][WC];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        if (!live[r]) continue;
+                        const uint32_t* xb = a.db + (b_begin + static_cast<int64_t>(cur) * R + r) * row_stride + lane;
+#pragma unroll
+                        for (int b = 0; b < BD; ++b)
+#pragma unroll
+                            for (int w = 0; w < WC; ++w) {
+                                const int ww = c * WC + w;
+                                x[r][b][w] = ww < a.W ? load_stream(xb + (b * a.W + ww) * kLanes) : 0u;
+                            }
+                    }
+#pragma unroll
+                    for (int t = 0; t < MQ; ++t) {
+                        if (t < a.m) {
+                            uniform_ptr yq = (uniform_ptr)(a.q + (static_cast<size_t>(t) * a.nchunks + c) * (BQ * WC));
+                            uint32_t y[BQ][WC];
+#pragma unroll
+                            for (int b = 0; b < BQ; ++b)
+#pragma unroll
+                                for (int w = 0; w < WC; ++w) y[b][w] = yq[b * WC + w];
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+                                if (live[r]) acc[r][t] += xor_popcount<BQ, BD, WC>(x[r], y);
+                        }
                     }
                 }
             }
-        }
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if (!live[r]) continue;
-            const bool valid = row[r] < a.n;
+            for (int r = 0; r < R; ++r) {
+                if (!live[r]) continue;
+                const bool valid = row[r] < a.n;
 #pragma unroll
-            for (int t = 0; t < MQ; ++t) {
-                if (t < a.m)
-                    append_lds(valid && acc[r][t] < thr[t], acc[r][t], row[r], s.buf + static_cast<size_t>(t) * a.cap,
-                               &s.cnt[t], static_cast<uint32_t>(a.cap), &s.ovf[t], s.hist + t * kHistBins, a.shift);
+                for (int t = 0; t < MQ; ++t) {
+                    if (t < a.m)
+                        append_lds(valid && acc[r][t] < thr[t], acc[r][t], row[r], s.buf + static_cast<size_t>(t) * a.cap,
+                                   &s.cnt[t], static_cast<uint32_t>(a.cap), &s.ovf[t], s.hist + t * kHistBins, a.shift);
+                }
             }
+            cur = nxt;
         }
-        seen += static_cast<int64_t>(step == 0 ? 1 : R) * kLocalBlock;
-        if (seen < 4 * seen_at_refresh && step + 1 < steps) continue;
 
         // Threshold update, all queries at once: wavefront t finds the new boundary of query t,
         // then the whole workgroup compacts the lists (keys held in registers across the reset).
         // Only LDS is exchanged, so the barriers leave the prefetched rows in flight.
-        seen_at_refresh = seen;
         lds_barrier();
         if (wave < a.m) {
             const uint32_t edge = wave_boundary(s.hist + wave * kHistBins, a.k, a.shift);
@@ -407,6 +417,7 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
         }
         lds_barrier();
         if (threadIdx.x < kLocalMaxQueries) s.cnt[threadIdx.x] = 0;
+        if (threadIdx.x == 0) *s.mark = static_cast<uint32_t>(epoch_end);
         lds_barrier();
 #pragma unroll
         for (int t = 0; t < MQ; ++t) {
@@ -424,7 +435,9 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
             }
         }
         lds_barrier();
+        if (epoch_end >= chunks) break;
     }
+    __syncthreads();
 
     // The piece's list leaves sorted and cut to its K best keys: the merge then needs only the
     // head of each list.  Short lists are ranked (every key counts the keys before it), long
@@ -451,6 +464,12 @@ __global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
             for (int i = threadIdx.x; i < keep; i += kLocalBlock) out[i] = buf[i];
         }
     }
+}
+
+template <int BQ, int BD, int WC, int R, bool PREFETCH, int MQ>
+__global__ __launch_bounds__(kLocalBlock) void scan_local(const LocalArgs a)
+{
+    scan_local_body<BQ, BD, WC, R, PREFETCH, MQ>(a);
 }
 
 // One workgroup per query: merge of the pieces' lists, see the head of this file.
@@ -656,7 +675,7 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
 size_t local_lds_bytes(int m, int cap)
 {
     return static_cast<size_t>(m) * cap * sizeof(uint64_t) + static_cast<size_t>(m) * kHistBins * sizeof(uint32_t) +
-           (3 * kLocalMaxQueries + kLocalWaves + 2) * sizeof(uint32_t);
+           (3 * kLocalMaxQueries + kLocalWaves + 4) * sizeof(uint32_t);   // counters, wave_sum, pick, next, mark
 }
 
 template <int BQ, int BD, int WC, int MQ>
