@@ -222,7 +222,7 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
     const bool want_local = (o.selector == 3 || (few && !keep_dist && m <= kLocalMaxQueries)) && k <= kLocalMaxK;
     if (!refine && !p.dot && !p.mfma && want_local && m <= p.batch) {
         p.local = true;
-        // one query: a list of 2048 keys lets all sixteen wavefronts take part in the first epoch
+        // one query: LDS to spare, so a list of 2048 keys (further from overflowing on ordered rows)
         const int floor_cap = m == 1 ? 2048 : 1024;
         p.local_cap = next_pow2(8 * k > floor_cap ? 8 * k : floor_cap);
         p.local_mq = kLocalMaxQueries;

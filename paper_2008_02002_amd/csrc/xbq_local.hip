@@ -13,9 +13,10 @@
 //                 lie in lower bins.  After the first 1024 or 2048 rows, and then every time the
 //                 rows handed out have grown by a quarter, that boundary is recomputed from the
 //                 histogram and the threshold lowered (by whichever wavefront notices first, no
-//                 barrier); for rows in random order about K ln(rows / 1024) rows pass in all.  At the end the list (a superset of the
-//                 piece's K best, typically K plus the ties of one bin) goes to the
-//                 workgroup's own slot: no global atomics, nothing to clear beforehand.
+//                 barrier); for rows in random order about K ln(rows / 1024) rows pass in all.
+//                 At the end the list (a superset of the piece's K best, typically K plus the
+//                 ties of one bin) goes to the workgroup's own slot: no global atomics, nothing
+//                 to clear beforehand.
 //                 If a list overflows (rows sorted towards the query, or massive ties) the
 //                 workgroup re-selects its piece exactly for that query: bounded buffer, sorted
 //                 and cut to K whenever it fills (slow, always exact).
@@ -40,6 +41,8 @@ constexpr int kLocalWaves = kLocalBlock / kLanes;
 constexpr int kFinishBins = 4096;
 constexpr int kLocalMaxCap = 2048;                    // longest per-piece list (keys); bounds k to 256
 constexpr int kRankSortMax = 512;                     // most keys sorted by ranking instead of the bitonic network
+constexpr int kRankAsIs = 128;                        // a final list this short is ranked without a last compaction
+                                                      // (ranking costs have^2 / 1024 comparisons per thread)
 
 __device__ __forceinline__ uint32_t load_stream(const uint32_t* p) { return __builtin_nontemporal_load(p); }
 
@@ -225,10 +228,11 @@ __device__ __forceinline__ uint32_t wave_boundary(const uint32_t* h, int k, int 
 // The piece is cut into chunks of R bundles which the wavefronts of the workgroup take from an
 // LDS counter: the wavefronts share SIMDs and memory paths unevenly, and with a fixed assignment
 // the slowest one, several chunks behind after a few dozen steps, kept the other fifteen waiting
-// at every threshold update and at the end with nothing left to load.  Chunks are grouped in
-// epochs (the first fills the lists without a threshold, later ones grow sixteenfold): between
-// epochs the workgroup stops to recompute thresholds and compact its lists; inside an epoch the
-// thresholds are lowered without any barrier.
+// at every threshold update and at the end with nothing left to load.  The first chunk of every
+// wavefront is scored without a threshold and only counted (the rows wait in registers until the
+// first thresholds exist); from then on the thresholds are lowered without any barrier.  Only at
+// a few fixed points (after 32 times the first rows, then sixteenfold) does the workgroup stop
+// to compact its lists, which matters only for very long pieces.
 // PREFETCH (whole row in registers, nchunks == 1): the rows of a wavefront's next chunk are
 // requested before the current one is scored, so the stream keeps flowing while the workgroup
 // sits in the barriers of a threshold update.
@@ -244,8 +248,8 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
         s.thr[threadIdx.x] = 0xffffffffu;
         s.ovf[threadIdx.x] = 0;
     }
-    // the first epoch fills the lists without a threshold: as many chunks as the list holds rows
-    const int warm = a.cap / (R * kLanes) < kLocalWaves ? a.cap / (R * kLanes) : kLocalWaves;
+    // the first epoch: one chunk per wavefront, scored without a threshold
+    constexpr int warm = kLocalWaves;
     if (threadIdx.x == 0) {
         *s.next = kLocalWaves;                           // chunks 0 .. 15 are handed out by wavefront number
         *s.mark = static_cast<uint32_t>(warm);
@@ -278,14 +282,23 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
     }
     lds_barrier();
 
-    // epoch: chunks [.., epoch_end).  Between epochs the whole workgroup stops, recomputes the
-    // thresholds and compacts the lists; inside an epoch single wavefronts lower the thresholds
-    // whenever the rows handed out have grown by a quarter (no barrier: a histogram that is being
-    // added to can only give a boundary that is too high, never one that drops a row it should keep).
-    // Epochs grow sixteenfold, and one that would leave less than itself for the next is extended
+    // epoch: chunks [.., epoch_end).  The first one is the chunk every wavefront starts with.
+    // Inside the later ones single wavefronts lower the thresholds whenever the rows handed out
+    // have grown by an eighth (no barrier: a histogram that is being added to can only give a
+    // boundary that is too high, never one that drops a row it should keep).  Between epochs the
+    // whole workgroup stops; an epoch that would leave less than itself for the next is extended
     // to the end of the piece.
-    for (int epoch_end = warm; ; epoch_end *= 16) {
-        if (epoch_end > chunks || (epoch_end > warm && chunks < 2 * epoch_end)) epoch_end = chunks;
+    uint32_t acc0[R][MQ];                                // the first chunk's rows, held until thresholds exist
+    uint32_t row0[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        row0[r] = 0xffffffffu;                           // no row: fails the `< a.n` test below
+#pragma unroll
+        for (int t = 0; t < MQ; ++t) acc0[r][t] = 0;
+    }
+    for (int epoch_end = warm; ; epoch_end *= (epoch_end == warm ? 32 : 16)) {
+        const bool first = epoch_end == warm;
+        if (epoch_end > chunks || (!first && chunks < 2 * epoch_end)) epoch_end = chunks;
         while (cur < epoch_end) {
             uint32_t acc[R][MQ];
             uint32_t row[R];
@@ -304,7 +317,7 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
             nxt = __builtin_amdgcn_readfirstlane(nxt);
             // lower the thresholds when enough new rows are out (one wavefront wins the job)
             const uint32_t mark = *s.mark;
-            if (static_cast<uint32_t>(nxt) >= mark + (mark >> 2) && epoch_end > warm) {
+            if (static_cast<uint32_t>(nxt) >= mark + (mark >> 3) && !first) {
                 int won = 0;
                 if (lane == 0) won = atomicCAS(s.mark, mark, static_cast<uint32_t>(nxt)) == mark ? 1 : 0;
                 if (__builtin_amdgcn_readfirstlane(won)) {
@@ -382,24 +395,67 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
                     }
                 }
             }
+            if (first) {                                 // count only; the rows wait in registers
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (!live[r]) continue;
-                const bool valid = row[r] < a.n;
+                for (int r = 0; r < R; ++r) {
+                    if (!live[r]) continue;
+                    row0[r] = row[r];
 #pragma unroll
-                for (int t = 0; t < MQ; ++t) {
-                    if (t < a.m)
-                        append_lds(valid && acc[r][t] < thr[t], acc[r][t], row[r], s.buf + static_cast<size_t>(t) * a.cap,
-                                   &s.cnt[t], static_cast<uint32_t>(a.cap), &s.ovf[t], s.hist + t * kHistBins, a.shift);
+                    for (int t = 0; t < MQ; ++t) {
+                        acc0[r][t] = acc[r][t];
+                        if (t < a.m && row[r] < a.n) atomicAdd(&s.hist[t * kHistBins + (acc[r][t] >> a.shift)], 1u);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (!live[r]) continue;
+                    const bool valid = row[r] < a.n;
+#pragma unroll
+                    for (int t = 0; t < MQ; ++t) {
+                        if (t < a.m)
+                            append_lds(valid && acc[r][t] < thr[t], acc[r][t], row[r], s.buf + static_cast<size_t>(t) * a.cap,
+                                       &s.cnt[t], static_cast<uint32_t>(a.cap), &s.ovf[t], s.hist + t * kHistBins, a.shift);
+                    }
                 }
             }
             cur = nxt;
         }
 
+        if (first) {
+            // First thresholds: wavefront t finds the boundary of query t among the rows counted so
+            // far, then every wavefront lists those of its held rows that pass (already counted).
+            lds_barrier();
+            if (wave < a.m) {
+                const uint32_t edge = wave_boundary(s.hist + wave * kHistBins, a.k, a.shift);
+                if (lane == 0) s.thr[wave] = edge;
+            }
+            lds_barrier();
+#pragma unroll
+            for (int t = 0; t < MQ; ++t) {
+                if (t < a.m) {
+                    thr[t] = s.thr[t];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        append_lds(row0[r] < a.n && acc0[r][t] < thr[t], acc0[r][t], row0[r],
+                                   s.buf + static_cast<size_t>(t) * a.cap, &s.cnt[t], static_cast<uint32_t>(a.cap),
+                                   &s.ovf[t], nullptr, 0);
+                }
+            }
+            if (epoch_end >= chunks) { lds_barrier(); break; }
+            continue;
+        }
+
         // Threshold update, all queries at once: wavefront t finds the new boundary of query t,
         // then the whole workgroup compacts the lists (keys held in registers across the reset).
-        // Only LDS is exchanged, so the barriers leave the prefetched rows in flight.
+        // Only LDS is exchanged, so the barriers leave the prefetched rows in flight.  At the end
+        // of the piece lists short enough to be ranked as they are skip this.
         lds_barrier();
+        if (epoch_end >= chunks) {
+            bool is_short = true;
+            for (int t = 0; t < a.m; ++t) is_short = is_short && s.cnt[t] <= static_cast<uint32_t>(kRankAsIs);
+            if (is_short) break;                         // same in every thread
+        }
         if (wave < a.m) {
             const uint32_t edge = wave_boundary(s.hist + wave * kHistBins, a.k, a.shift);
             if (lane == 0 && edge < s.thr[wave]) s.thr[wave] = edge;
