@@ -261,7 +261,8 @@ int xbq_probe_encode_traffic(const float* X, int64_t n, int d, int bits, uint32_
  *                       queries), 2 = histogram selection over stored distances (Section 4.1),
  *                       3 = the same selection done per workgroup while the rows stream, nothing
  *                       stored (k <= 256, four queries per pass; the automatic choice for up to
- *                       four queries; a larger k falls back to 2)
+ *                       four queries, and for every few-query search over at least 6 million
+ *                       rows of codes of at most 256 dimensions; a larger k falls back to 2)
  *   "hist_max_queries"  automatic choice: few-query selection up to this many queries (default
  *                       16), twice as many for k > 128, three times for k > 512
  *   "local_groups"      selector 3: most pieces the rows are split into (1..1024, default 256: one per compute unit)

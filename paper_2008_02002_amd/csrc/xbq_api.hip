@@ -218,8 +218,14 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
     const int64_t dmax = static_cast<int64_t>(d) * ((1 << bits) - 1) * ((1 << bits) - 1);
     // local selection: the default for few queries; its lists live in LDS, which bounds k
     // automatic: one pass of it (up to kLocalMaxQueries queries); more queries are served faster by the
-    // histogram selection over stored distances, which scores eight queries per pass
-    const bool want_local = (o.selector == 3 || (few && !keep_dist && m <= kLocalMaxQueries)) && k <= kLocalMaxK;
+    // histogram selection over stored distances, which scores eight queries per pass, unless the
+    // database is so long that writing and re-reading 8 bytes per (query, row) costs more than
+    // streaming short codes once more per four queries (measured at d = 96 and 128, 4 bits, 8 and 16
+    // queries: even at 5 M rows, 5 to 15 % for local passes from 7 M rows on)
+    constexpr int64_t kLocalPassesFromRows = 6'000'000;
+    const bool short_codes = p.wc == 0;
+    const bool want_local = (o.selector == 3 || (few && !keep_dist && (m <= kLocalMaxQueries ||
+                             (n >= kLocalPassesFromRows && short_codes)))) && k <= kLocalMaxK;
     if (!refine && !p.dot && !p.mfma && want_local && m <= p.batch) {
         p.local = true;
         // one query: LDS to spare, so a list of 2048 keys (further from overflowing on ordered rows)
@@ -424,7 +430,7 @@ int run_hist_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s
     return XBQ_OK;
 }
 
-// Local selection: queries in passes of p.local_mq, two launches per pass, nothing cleared.
+// Local selection: queries in passes of at most p.local_mq, two launches per pass, nothing cleared.
 int run_local_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s)
 {
     const int64_t m = job.m;
@@ -436,12 +442,16 @@ int run_local_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t 
         q_all = qc;
     }
     const int64_t q_stride = static_cast<int64_t>(p.hist_nchunks) * job.q_bits * p.hist_wc;
-    for (int64_t qb = 0; qb < m; qb += p.local_mq) {
+    // passes of nearly equal size (five queries: 3 + 2, not 4 + 1: a pass of one query costs as
+    // much HBM time as one of two)
+    const int64_t passes = (m + p.local_mq - 1) / p.local_mq;
+    const int64_t per_pass = passes > 0 ? (m + passes - 1) / passes : 1;
+    for (int64_t qb = 0; qb < m; qb += per_pass) {
         LocalArgs la{};
         la.db = job.db_codes;
         la.n = job.n;
         la.q = q_all + qb * q_stride;
-        la.m = static_cast<int>(m - qb < p.local_mq ? m - qb : p.local_mq);
+        la.m = static_cast<int>(m - qb < per_pass ? m - qb : per_pass);
         la.q_bits = job.q_bits;
         la.db_bits = job.db_bits;
         la.W = p.W;

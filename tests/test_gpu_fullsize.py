@@ -124,7 +124,9 @@ def test_c4_full_size():
 
 
 def test_c5_full_size_few_queries():
+    # 10 M rows of short codes: several passes of the local selection, not stored distances
     _run_few_queries("C5", 4, 100, 5)
+    _run_few_queries("C5", 4, 100, 16)
 
 
 @pytest.mark.parametrize("part", range(4))
