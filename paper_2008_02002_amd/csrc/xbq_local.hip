@@ -10,10 +10,11 @@
 //                 query, a histogram of D >> shift of the rows it let through and a list of
 //                 their keys, both in LDS.  A row of the global top-K is also in the top-K of
 //                 its own piece, so a row may be dropped as soon as K rows of the same piece
-//                 lie in lower bins.  After the first 1024 or 2048 rows, and then every time the
-//                 rows handed out have grown by a quarter, that boundary is recomputed from the
-//                 histogram and the threshold lowered (by whichever wavefront notices first, no
-//                 barrier); for rows in random order about K ln(rows / 1024) rows pass in all.
+//                 lie in lower bins.  Every wavefront's first chunk is scored without a
+//                 threshold and only counted; once the first boundary exists, the boundary is
+//                 recomputed from the histogram every time the rows handed out have grown by an
+//                 eighth and the threshold lowered (by whichever wavefront notices first, no
+//                 barrier); for rows in random order about K ln(rows / first rows) rows pass.
 //                 At the end the list (a superset of the piece's K best, typically K plus the
 //                 ties of one bin) goes to the workgroup's own slot: no global atomics, nothing
 //                 to clear beforehand.
@@ -53,8 +54,6 @@ struct LocalLds {
     uint32_t* cnt;        // [kLocalMaxQueries] keys in buf[t]
     uint32_t* thr;        // [kLocalMaxQueries] a row passes when D < thr[t]
     uint32_t* ovf;        // [kLocalMaxQueries] set when a key did not fit
-    uint32_t* wave_sum;   // [kLocalWaves]
-    int* pick;            // [2]
     uint32_t* next;       // next chunk of the piece to hand out
     uint32_t* mark;       // chunks handed out when the thresholds were last recomputed
 };
@@ -67,9 +66,7 @@ __device__ __forceinline__ LocalLds carve(uint64_t* base, int m, int cap)
     s.cnt = s.hist + m * kHistBins;
     s.thr = s.cnt + kLocalMaxQueries;
     s.ovf = s.thr + kLocalMaxQueries;
-    s.wave_sum = s.ovf + kLocalMaxQueries;
-    s.pick = reinterpret_cast<int*>(s.wave_sum + kLocalWaves);
-    s.next = reinterpret_cast<uint32_t*>(s.pick + 2);
+    s.next = s.ovf + kLocalMaxQueries;
     s.mark = s.next + 1;
     return s;
 }
@@ -731,7 +728,7 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
 size_t local_lds_bytes(int m, int cap)
 {
     return static_cast<size_t>(m) * cap * sizeof(uint64_t) + static_cast<size_t>(m) * kHistBins * sizeof(uint32_t) +
-           (3 * kLocalMaxQueries + kLocalWaves + 4) * sizeof(uint32_t);   // counters, wave_sum, pick, next, mark
+           (3 * kLocalMaxQueries + 2) * sizeof(uint32_t);                 // counters, next, mark
 }
 
 template <int BQ, int BD, int WC, int MQ>
