@@ -520,6 +520,27 @@ def test_local_selection_piece_sizes_and_query_passes():
                 gu.assert_same(got, want, f"local n={n} m={m} k={k} groups={groups}")
 
 
+def test_local_selection_very_long_pieces_compact_their_lists():
+    # one or two pieces of 200 000 to 400 000 rows: thousands of chunks per workgroup, so the lists
+    # are compacted on the way (ordinary data, no overflow: the exact re-selection must not be what
+    # makes this pass), with one query and with three
+    n, d, bits = 400_000, 96, 4
+    Xdb = _rand(n, d, seed=81)
+    for m, k in ((1, 100), (3, 40), (4, 256)):
+        Xq = _rand(m, d, seed=82 + m)
+        want = gu.oracle_search(Xdb, Xq, bits, k, 2.0)
+        for groups in (1, 2):
+            _say(f"local selection, long pieces: m={m} k={k} groups={groups}")
+            try:
+                xbq.xbq_set_option("selector", 3)
+                xbq.xbq_set_option("local_groups", groups)
+                got = gu.gpu_search(Xdb, Xq, bits, k, 2.0)
+            finally:
+                xbq.xbq_set_option("local_groups", 256)
+                xbq.xbq_set_option("selector", 0)
+            gu.assert_same(got, want, f"long pieces m={m} k={k} groups={groups}")
+
+
 def test_search_ex_takes_its_options_per_call():
     import torch
     Xdb = _rand(60_000, 128, seed=51)
