@@ -32,11 +32,13 @@ __global__ void clear_u32(uint32_t* p, int64_t count)
 
 // One wavefront per bundle of 64 rows (grid-stride); queries come from the chunk-major layout
 // [m][nchunks][BQ][WC] (for W <= 8 that is the plain row layout with one chunk).
-// Workgroups of 16 wavefronts share one LDS histogram, so that few workgroups (two per CU)
+// Workgroups of 16 wavefronts share one LDS histogram, so that few workgroups (one per CU)
 // merge into the global one: the merge is atomics on a few hundred hot addresses.
 constexpr int kHistBlock = 1024;
 
-template <int BQ, int BD, int WC>
+// PREFETCH (the whole row fits WC words, one chunk): the rows of the wavefront's next bundle are
+// requested before the current one is scored.
+template <int BQ, int BD, int WC, bool PREFETCH>
 __global__ __launch_bounds__(kHistBlock) void scan_hist(const HistArgs a)
 {
     __shared__ uint32_t lh[kHistMaxQueries * kHistBins];
@@ -44,25 +46,50 @@ __global__ __launch_bounds__(kHistBlock) void scan_hist(const HistArgs a)
     const int wave = threadIdx.x >> 6;
     const int bins = a.m * kHistBins;
     for (int t = threadIdx.x; t < bins; t += blockDim.x) lh[t] = 0;
-    __syncthreads();
 
     const int64_t nbundles = (a.n + kLanes - 1) / kLanes;
     constexpr int kWaves = kHistBlock / kLanes;
     const int64_t waves = static_cast<int64_t>(gridDim.x) * kWaves;
-    for (int64_t bundle = static_cast<int64_t>(blockIdx.x) * kWaves + wave; bundle < nbundles; bundle += waves) {
-        const uint32_t* xb = a.db + bundle * (static_cast<int64_t>(BD) * a.W * kLanes) + lane;
+    const int64_t row_stride = static_cast<int64_t>(BD) * a.W * kLanes;
+    int64_t bundle = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+    uint32_t xn[BD][WC];
+    if (PREFETCH && bundle < nbundles) {
+        const uint32_t* xb = a.db + bundle * row_stride + lane;
+#pragma unroll
+        for (int b = 0; b < BD; ++b)
+#pragma unroll
+            for (int w = 0; w < WC; ++w) xn[b][w] = __builtin_nontemporal_load(xb + (b * WC + w) * kLanes);
+    }
+    __syncthreads();
+
+    for (; bundle < nbundles; bundle += waves) {
+        const uint32_t* xb = a.db + bundle * row_stride + lane;
         uint32_t acc[kHistMaxQueries];
 #pragma unroll
         for (int t = 0; t < kHistMaxQueries; ++t) acc[t] = 0;
-        for (int c = 0; c < a.nchunks; ++c) {
+        for (int c = 0; c < (PREFETCH ? 1 : a.nchunks); ++c) {
             uint32_t x[BD][WC];
+            if (PREFETCH) {
 #pragma unroll
-            for (int b = 0; b < BD; ++b)
+                for (int b = 0; b < BD; ++b)
 #pragma unroll
-                for (int w = 0; w < WC; ++w) {
-                    const int ww = c * WC + w;
-                    x[b][w] = ww < a.W ? xb[(b * a.W + ww) * kLanes] : 0u;
+                    for (int w = 0; w < WC; ++w) x[b][w] = xn[b][w];
+                if (bundle + waves < nbundles) {
+                    const uint32_t* xnb = xb + waves * row_stride;
+#pragma unroll
+                    for (int b = 0; b < BD; ++b)
+#pragma unroll
+                        for (int w = 0; w < WC; ++w) xn[b][w] = __builtin_nontemporal_load(xnb + (b * WC + w) * kLanes);
                 }
+            } else {
+#pragma unroll
+                for (int b = 0; b < BD; ++b)
+#pragma unroll
+                    for (int w = 0; w < WC; ++w) {
+                        const int ww = c * WC + w;
+                        x[b][w] = ww < a.W ? xb[(b * a.W + ww) * kLanes] : 0u;
+                    }
+            }
 #pragma unroll
             for (int t = 0; t < kHistMaxQueries; ++t) {
                 if (t < a.m) {
@@ -245,15 +272,32 @@ __global__ __launch_bounds__(kBlock) void hist_finish(const CollectArgs a)
 template <int BQ, int BD>
 static hipError_t launch_scan_hist_b(const HistArgs& a, dim3 grid, hipStream_t s)
 {
+    const bool pre = a.nchunks == 1 && a.W == a.wc;      // whole row in registers: prefetch the next bundle
     switch (a.wc) {
-    case 1: hipLaunchKernelGGL((scan_hist<BQ, BD, 1>), grid, dim3(kHistBlock), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((scan_hist<BQ, BD, 2>), grid, dim3(kHistBlock), 0, s, a); break;
-    case 3: hipLaunchKernelGGL((scan_hist<BQ, BD, 3>), grid, dim3(kHistBlock), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((scan_hist<BQ, BD, 4>), grid, dim3(kHistBlock), 0, s, a); break;
-    case 5: hipLaunchKernelGGL((scan_hist<BQ, BD, 5>), grid, dim3(kHistBlock), 0, s, a); break;
-    case 6: hipLaunchKernelGGL((scan_hist<BQ, BD, 6>), grid, dim3(kHistBlock), 0, s, a); break;
-    case 7: hipLaunchKernelGGL((scan_hist<BQ, BD, 7>), grid, dim3(kHistBlock), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((scan_hist<BQ, BD, 8>), grid, dim3(kHistBlock), 0, s, a); break;
+    case 1: if (pre) hipLaunchKernelGGL((scan_hist<BQ, BD, 1, true>), grid, dim3(kHistBlock), 0, s, a);
+            else     hipLaunchKernelGGL((scan_hist<BQ, BD, 1, false>), grid, dim3(kHistBlock), 0, s, a);
+            break;
+    case 2: if (pre) hipLaunchKernelGGL((scan_hist<BQ, BD, 2, true>), grid, dim3(kHistBlock), 0, s, a);
+            else     hipLaunchKernelGGL((scan_hist<BQ, BD, 2, false>), grid, dim3(kHistBlock), 0, s, a);
+            break;
+    case 3: if (pre) hipLaunchKernelGGL((scan_hist<BQ, BD, 3, true>), grid, dim3(kHistBlock), 0, s, a);
+            else     hipLaunchKernelGGL((scan_hist<BQ, BD, 3, false>), grid, dim3(kHistBlock), 0, s, a);
+            break;
+    case 4: if (pre) hipLaunchKernelGGL((scan_hist<BQ, BD, 4, true>), grid, dim3(kHistBlock), 0, s, a);
+            else     hipLaunchKernelGGL((scan_hist<BQ, BD, 4, false>), grid, dim3(kHistBlock), 0, s, a);
+            break;
+    case 5: if (pre) hipLaunchKernelGGL((scan_hist<BQ, BD, 5, true>), grid, dim3(kHistBlock), 0, s, a);
+            else     hipLaunchKernelGGL((scan_hist<BQ, BD, 5, false>), grid, dim3(kHistBlock), 0, s, a);
+            break;
+    case 6: if (pre) hipLaunchKernelGGL((scan_hist<BQ, BD, 6, true>), grid, dim3(kHistBlock), 0, s, a);
+            else     hipLaunchKernelGGL((scan_hist<BQ, BD, 6, false>), grid, dim3(kHistBlock), 0, s, a);
+            break;
+    case 7: if (pre) hipLaunchKernelGGL((scan_hist<BQ, BD, 7, true>), grid, dim3(kHistBlock), 0, s, a);
+            else     hipLaunchKernelGGL((scan_hist<BQ, BD, 7, false>), grid, dim3(kHistBlock), 0, s, a);
+            break;
+    case 8: if (pre) hipLaunchKernelGGL((scan_hist<BQ, BD, 8, true>), grid, dim3(kHistBlock), 0, s, a);
+            else     hipLaunchKernelGGL((scan_hist<BQ, BD, 8, false>), grid, dim3(kHistBlock), 0, s, a);
+            break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -272,7 +316,8 @@ hipError_t launch_scan_hist(const HistArgs& a, hipStream_t s)
     if (a.m < 1 || a.m > kHistMaxQueries || a.n < 1 || a.wc < 1 || a.wc > 8 || a.nchunks < 1) return hipErrorInvalidValue;
     const int64_t nbundles = (a.n + kLanes - 1) / kLanes;
     int64_t blocks = (nbundles + 15) / 16;
-    if (blocks > 512) blocks = 512;                      // 2 per CU = 8 wavefronts per SIMD; the rest is grid-stride
+    if (blocks > 256) blocks = 256;                      // one per CU; the rest is grid-stride (measured: 512 is 3-5 % slower,
+                                                         // twice the atomics of the final merge; 128 is far slower)
     dim3 grid(static_cast<unsigned>(blocks));
     switch (a.q_bits * 10 + a.db_bits) {
     case 11: return launch_scan_hist_b<1, 1>(a, grid, s);
