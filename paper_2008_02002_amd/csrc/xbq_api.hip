@@ -250,10 +250,13 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
         p.loff_q = h;
         if (p.wc) h = align_up(h + b * p.nchunks * bits * p.wc * sizeof(uint32_t), 256);
         p.local_stride = (k + 15) / 16 * 16;             // lists start on 128-byte boundaries
-        // a list contributes about k / groups keys to the result: read four times that, at least 4
-        // (the merge proves afterwards that no list needed more, and reads whole lists if one did)
-        p.local_prefix = next_pow2((4 * k + p.local_groups - 1) / p.local_groups);
-        if (p.local_prefix < 4) p.local_prefix = 4;
+        // A list contributes about s = k / groups keys to the result, Poisson-like: read 4 s + 4 keys
+        // of each, rounded up to a power of two and at least 8, so that a list holding that many
+        // of the k best is a one-in-a-million event per list (s = 0.4, 8 keys: 1e-8; s = 2, 16
+        // keys: 1e-10; with 4 keys at s = 0.4 every fourth query found one and merged whole lists).
+        // The merge proves afterwards that no list needed more, and reads whole lists if one did.
+        p.local_prefix = next_pow2((4 * k + p.local_groups - 1) / p.local_groups + 4);
+        if (p.local_prefix < 8) p.local_prefix = 8;
         if (p.local_prefix > next_pow2(k) && next_pow2(k) >= 16) p.local_prefix = next_pow2(k);
         p.loff_lists = h;  h = align_up(h + static_cast<size_t>(p.local_mq) * p.local_groups * p.local_stride * sizeof(uint64_t), 256);
         if (h > p.total) p.total = h;
