@@ -820,3 +820,48 @@ def test_random_shapes_through_every_search_entry_point():
     finally:
         xbq.xbq_set_option("selector", 0)
         xbq.xbq_set_option("kselect_lists_min", 128)
+
+
+def test_random_shapes_local_selection():
+    """Seeded sweep over the local selection (selector 3, options per call): one to nine queries
+    (up to three passes), every supported pair of code widths, piece counts from one to a
+    thousand, k up to its limit of 256, and four kinds of rows including tight clusters, whose
+    near-ties fill boundary bins and whose order puts most of a result into few pieces."""
+    import torch
+    rng = np.random.default_rng(777)
+    dims = [1, 7, 31, 32, 33, 64, 65, 96, 127, 128, 129, 200, 256, 257, 288, 700, 960, 2048]
+    rows = [1, 2, 63, 64, 65, 128, 1000, 1024, 1025, 1536, 4096, 4097, 5121, 9999, 20011, 70001, 150000]
+    pairs = [(1, 1), (2, 2), (3, 3), (4, 4), (2, 1), (3, 2), (4, 3)]
+
+    def draw(n, d, kind):
+        if kind == 0:
+            X = rng.uniform(-0.5, 0.5, (n, d))
+        elif kind == 1:
+            X = rng.standard_normal((n, d))
+        elif kind == 2:
+            X = np.abs(rng.standard_normal((n, d)))
+        else:                                            # clusters, rows of a cluster next to each other
+            base = rng.standard_normal((max(1, n // 50), d))
+            X = base[np.sort(rng.integers(len(base), size=n))] + 0.05 * rng.standard_normal((n, d))
+        return (X / np.maximum(np.linalg.norm(X, axis=1, keepdims=True), 1e-9)).astype(np.float32)
+
+    for trial in range(48):
+        d = int(rng.choice(dims))
+        n = int(rng.choice(rows))
+        if n * d > 40_000_000:
+            n = 40_000_000 // d
+        qb, db_bits = pairs[int(rng.integers(len(pairs)))]
+        m = int(rng.choice([1, 1, 2, 3, 4, 5, 9]))
+        k = int(min(n, rng.choice([1, 2, 10, 64, 100, 200, 256])))
+        groups = int(rng.choice([1, 2, 7, 64, 256, 1000]))
+        kind = int(rng.integers(4))
+        scale = float(rng.choice([1.0, 1.7, 3.3]))
+        _say(f"trial {trial}: local n={n} d={d} m={m} {qb}x{db_bits} k={k} groups={groups} rows={kind} scale={scale}")
+        Xdb, Xq = draw(n, d, kind), draw(m, d, kind)
+        db = xbq.xbq_encode(gu.to_dev(Xdb), db_bits, scale, xbq.BUNDLE64)
+        q = xbq.xbq_encode(gu.to_dev(Xq), qb, scale, xbq.ROWS)
+        idx, score = xbq.xbq_search_ex(db, n, db_bits, q, m, qb, d, k,
+                                       xbq.xbq_options_default(selector=3, local_groups=groups))
+        torch.cuda.synchronize()
+        gu.assert_same((idx.cpu().numpy(), score.cpu().numpy()), gu.oracle_search_asym(Xdb, Xq, db_bits, qb, k, scale),
+                       f"trial {trial}")
