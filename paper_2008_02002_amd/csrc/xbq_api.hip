@@ -228,11 +228,12 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
                              (n >= kLocalPassesFromRows && short_codes)))) && k <= kLocalMaxK;
     if (!refine && !p.dot && !p.mfma && want_local && m <= p.batch) {
         p.local = true;
-        // one query: LDS to spare, so a list of 2048 keys (further from overflowing on ordered rows)
-        const int floor_cap = m == 1 ? 2048 : 1024;
-        p.local_cap = next_pow2(8 * k > floor_cap ? 8 * k : floor_cap);
+        // Lists of 4096 keys: a list asks for a compaction while it still has room for every row in
+        // flight (2048), so bursts of passing rows (rows ordered towards the query, cluster after
+        // cluster) lose nothing.  Four queries take 144 KB of the 160 KB of LDS.
+        p.local_cap = 4096;
         p.local_mq = kLocalMaxQueries;
-        while (p.local_mq > 1 && local_lds_bytes(p.local_mq, p.local_cap) > 64 * 1024) --p.local_mq;
+        while (p.local_mq > 1 && local_lds_bytes(p.local_mq, p.local_cap) > kLocalMaxLds) --p.local_mq;
         if (m < p.local_mq) p.local_mq = static_cast<int>(m);
         const int64_t nbundles = (n + kLanes - 1) / kLanes;
         int64_t bpg = (nbundles + o.local_groups - 1) / o.local_groups;

@@ -16,6 +16,7 @@ constexpr int kTileQ = 16;        // queries per register tile of the word-chunk
 constexpr int kHistBins = 1024;   // histogram bins per query (histogram selection)
 constexpr int kHistMaxQueries = 8;  // queries per pass of the histogram selection
 constexpr int kLocalMaxQueries = 4; // queries per pass of the local selection (few queries, nothing stored)
+constexpr size_t kLocalMaxLds = 152 * 1024;  // LDS one workgroup of the local selection may take (of 160 KB per CU)
 constexpr int kLocalMaxGroups = 1024;   // most pieces (workgroups) of the local selection
 
 // A candidate is ordered by the 64-bit key (D << 32) | row: smaller key = better
@@ -201,7 +202,7 @@ struct LocalArgs {
     int k, d;
     int shift;               // piece histogram: bin = D >> shift  (< kHistBins for every possible D)
     int shift2;              // merge histogram: bin = D >> shift2 (< 4096 for every possible D)
-    int cap;                 // keys per (piece, query) list: power of two, >= 8 k, 1024..4096
+    int cap;                 // keys per (piece, query) list: 4096
     int groups;              // pieces = workgroups of scan_local
     int64_t bundles_per_group;
     uint64_t* lists;         // [m][groups][list_stride]: the min(k, rows of the piece) best keys of every

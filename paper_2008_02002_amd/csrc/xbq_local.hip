@@ -15,18 +15,24 @@
 //                 recomputed from the histogram every time the rows handed out have grown by an
 //                 eighth and the threshold lowered (by whichever wavefront notices first, no
 //                 barrier); for rows in random order about K ln(rows / first rows) rows pass.
+//                 A list that reaches its level (rows ordered towards the query, cluster after
+//                 cluster) asks for a compaction: all wavefronts finish their chunk, the lists
+//                 are cut at the boundary of the moment (exactly, by sorting, when thousands of
+//                 distances share the boundary bin) and the stream goes on; lists of 4096 keys
+//                 leave room for every row in flight, so no key is lost on the way.
 //                 At the end the list (a superset of the piece's K best, typically K plus the
 //                 ties of one bin) goes to the workgroup's own slot: no global atomics, nothing
 //                 to clear beforehand.
-//                 If a list overflows (rows sorted towards the query, or massive ties) the
-//                 workgroup re-selects its piece exactly for that query: bounded buffer, sorted
-//                 and cut to K whenever it fills (slow, always exact).
+//                 If a list overflows all the same (ties at the K-th distance itself that no list
+//                 can hold) the workgroup re-selects its piece exactly for that query: bounded
+//                 buffer, sorted and cut to K whenever it fills (slow, always exact).
 //                 The list leaves sorted and cut to the piece's K best keys.
 //   local_finish  One workgroup per query merges the lists, reading only their heads: histogram
 //                 of D >> shift2 (4096 bins), boundary bin, the keys at or below it sorted by
-//                 (D, row), first K written; whole lists only when a head turns out too short,
-//                 and massive ties at the boundary are streamed with a running threshold on
-//                 the whole key.
+//                 (D, row), first K written.  When a head turns out too short (the result sits in
+//                 a few pieces) the whole lists are read, but only keys up to the K-th key of the
+//                 heads can matter and those are few; massive ties at the boundary are streamed
+//                 with a running threshold on the whole key.
 //
 // Ties go to the lower row: keys are (D << 32) | row and every cut is made on whole keys or
 // keeps whole bins.
@@ -40,7 +46,7 @@ namespace {
 constexpr int kLocalBlock = 1024;                     // threads per workgroup
 constexpr int kLocalWaves = kLocalBlock / kLanes;
 constexpr int kFinishBins = 4096;
-constexpr int kLocalMaxCap = 2048;                    // longest per-piece list (keys); bounds k to 256
+constexpr int kLocalMaxCap = 4096;                    // keys in a per-piece list: room for 2048 rows in flight and more
 constexpr int kRankSortMax = 512;                     // most keys sorted by ranking instead of the bitonic network
 constexpr int kRankAsIs = 128;                        // a final list this short is ranked without a last compaction
                                                       // (ranking costs have^2 / 1024 comparisons per thread)
@@ -54,8 +60,11 @@ struct LocalLds {
     uint32_t* cnt;        // [kLocalMaxQueries] keys in buf[t]
     uint32_t* thr;        // [kLocalMaxQueries] a row passes when D < thr[t]
     uint32_t* ovf;        // [kLocalMaxQueries] set when a key did not fit
+    uint32_t* level;      // [kLocalMaxQueries] a list that reaches this length asks for a compaction
     uint32_t* next;       // next chunk of the piece to hand out
     uint32_t* mark;       // chunks handed out when the thresholds were last recomputed
+    uint32_t* want;       // set when some list asks for a compaction
+    uint32_t* done;       // one bit per wavefront that has no chunk left
 };
 
 __device__ __forceinline__ LocalLds carve(uint64_t* base, int m, int cap)
@@ -66,21 +75,30 @@ __device__ __forceinline__ LocalLds carve(uint64_t* base, int m, int cap)
     s.cnt = s.hist + m * kHistBins;
     s.thr = s.cnt + kLocalMaxQueries;
     s.ovf = s.thr + kLocalMaxQueries;
-    s.next = s.ovf + kLocalMaxQueries;
+    s.level = s.ovf + kLocalMaxQueries;
+    s.next = s.level + kLocalMaxQueries;
     s.mark = s.next + 1;
+    s.want = s.mark + 1;
+    s.done = s.want + 1;
     return s;
 }
 
 // Append the keys of the passing lanes to an LDS list: one LDS atomic per wavefront reserves
-// the slots.  Keys that do not fit raise *ovf.  Passing rows are also counted in hist.
+// the slots.  Keys that do not fit raise *ovf.  Passing rows are also counted in hist.  With
+// level given, the append that takes the list across *level raises *want.
 __device__ __forceinline__ void append_lds(bool pass, uint32_t D, uint32_t row, uint64_t* list, uint32_t* counter,
-                                           uint32_t cap, uint32_t* ovf, uint32_t* hist, int shift)
+                                           uint32_t cap, uint32_t* ovf, uint32_t* hist, int shift,
+                                           const uint32_t* level = nullptr, uint32_t* want = nullptr)
 {
     const uint64_t mask = __ballot(pass);
     if (mask == 0) return;
     const int leader = __ffsll(static_cast<long long>(mask)) - 1;
     uint32_t base = 0;
-    if (lane_id() == leader) base = atomicAdd(counter, static_cast<uint32_t>(__popcll(mask)));
+    if (lane_id() == leader) {
+        const uint32_t count = static_cast<uint32_t>(__popcll(mask));
+        base = atomicAdd(counter, count);
+        if (level != nullptr && base < *level && base + count >= *level) *want = 1u;
+    }
     base = __shfl(base, leader);
     const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
                           __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
@@ -217,6 +235,25 @@ __device__ __forceinline__ uint32_t wave_boundary(const uint32_t* h, int k, int 
     return (static_cast<uint32_t>(bin < 0 ? kHistBins - 1 : bin) + 1u) << shift;
 }
 
+// Exact cut of a list of `have` keys (more than k) by the whole workgroup: sorted, only the keys
+// up to the K-th distance stay, *cnt becomes their number and *thr at most that distance + 1.
+// Kept out of line: it is rare, and inlined its registers crowd the streaming loop.
+__device__ __noinline__ void cut_list_exactly(uint64_t* buf, int have, int k, uint32_t* cnt, uint32_t* thr)
+{
+    const int P = next_pow2(have);
+    for (int i = have + threadIdx.x; i < P; i += kLocalBlock) buf[i] = kPadKey;
+    __syncthreads();
+    bitonic_sort_lds(buf, P);
+    const uint32_t kth = static_cast<uint32_t>(buf[k - 1] >> 32);
+    for (int i = threadIdx.x; i < have; i += kLocalBlock) {
+        const bool in = static_cast<uint32_t>(buf[i] >> 32) <= kth;
+        const bool next_in = i + 1 < have && static_cast<uint32_t>(buf[i + 1] >> 32) <= kth;
+        if (in && !next_in) *cnt = static_cast<uint32_t>(i + 1);
+    }
+    if (threadIdx.x == 0 && kth + 1u < *thr) *thr = kth + 1u;
+    __syncthreads();
+}
+
 }  // namespace
 
 // One workgroup per piece of a.bundles_per_group bundles; MQ >= a.m is the number of queries the
@@ -227,9 +264,11 @@ __device__ __forceinline__ uint32_t wave_boundary(const uint32_t* h, int k, int 
 // the slowest one, several chunks behind after a few dozen steps, kept the other fifteen waiting
 // at every threshold update and at the end with nothing left to load.  The first chunk of every
 // wavefront is scored without a threshold and only counted (the rows wait in registers until the
-// first thresholds exist); from then on the thresholds are lowered without any barrier.  Only at
-// a few fixed points (after 32 times the first rows, then sixteenfold) does the workgroup stop
-// to compact its lists, which matters only for very long pieces.
+// first thresholds exist); from then on the thresholds are lowered without any barrier.  The
+// workgroup stops to compact its lists only when one of them is half full (rows that come
+// ordered towards the query, cluster after cluster): every wavefront then finishes the chunk it
+// is in, and the request comes early enough for all of those rows to fit (lists of 4096 keys,
+// at most 2048 rows in flight), so no key is ever lost.
 // PREFETCH (whole row in registers, nchunks == 1): the rows of a wavefront's next chunk are
 // requested before the current one is scored, so the stream keeps flowing while the workgroup
 // sits in the barriers of a threshold update.
@@ -240,16 +279,23 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
     const LocalLds s = carve(local_lds, a.m, a.cap);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int i = threadIdx.x; i < a.m * kHistBins; i += kLocalBlock) s.hist[i] = 0;
+    // A list asks for a compaction when it reaches its level.  Every wavefront then finishes the
+    // chunk it is in, which may add R * 64 rows each, plus the rest of the append that crossed
+    // the level: a level at most this low leaves room for all of them, so no key is lost.
+    const uint32_t safe_level = static_cast<uint32_t>(a.cap) - static_cast<uint32_t>(kLocalWaves * R * kLanes + 2 * kLanes);
     if (threadIdx.x < kLocalMaxQueries) {
         s.cnt[threadIdx.x] = 0;
         s.thr[threadIdx.x] = 0xffffffffu;
         s.ovf[threadIdx.x] = 0;
+        s.level[threadIdx.x] = safe_level;
     }
     // the first epoch: one chunk per wavefront, scored without a threshold
     constexpr int warm = kLocalWaves;
     if (threadIdx.x == 0) {
         *s.next = kLocalWaves;                           // chunks 0 .. 15 are handed out by wavefront number
         *s.mark = static_cast<uint32_t>(warm);
+        *s.want = 0;
+        *s.done = 0;
     }
 
     const int64_t nbundles = (a.n + kLanes - 1) / kLanes;
@@ -279,12 +325,11 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
     }
     lds_barrier();
 
-    // epoch: chunks [.., epoch_end).  The first one is the chunk every wavefront starts with.
-    // Inside the later ones single wavefronts lower the thresholds whenever the rows handed out
-    // have grown by an eighth (no barrier: a histogram that is being added to can only give a
-    // boundary that is too high, never one that drops a row it should keep).  Between epochs the
-    // whole workgroup stops; an epoch that would leave less than itself for the next is extended
-    // to the end of the piece.
+    // Rounds.  The first is the chunk every wavefront starts with.  In the later ones the
+    // wavefronts stream until the chunks run out or a list asks for a compaction, and single
+    // wavefronts lower the thresholds whenever the chunks handed out have grown by an eighth (no
+    // barrier: a histogram that is being added to can only give a boundary that is too high, never
+    // one that drops a row it should keep).  Between rounds the whole workgroup stops.
     uint32_t acc0[R][MQ];                                // the first chunk's rows, held until thresholds exist
     uint32_t row0[R];
 #pragma unroll
@@ -293,10 +338,8 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
 #pragma unroll
         for (int t = 0; t < MQ; ++t) acc0[r][t] = 0;
     }
-    for (int epoch_end = warm; ; epoch_end *= (epoch_end == warm ? 32 : 16)) {
-        const bool first = epoch_end == warm;
-        if (epoch_end > chunks || (!first && chunks < 2 * epoch_end)) epoch_end = chunks;
-        while (cur < epoch_end) {
+    for (bool first = true; ; ) {
+        while (cur < chunks && (first ? cur < warm : *static_cast<volatile uint32_t*>(s.want) == 0)) {
             uint32_t acc[R][MQ];
             uint32_t row[R];
             bool live[R];
@@ -412,7 +455,8 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
                     for (int t = 0; t < MQ; ++t) {
                         if (t < a.m)
                             append_lds(valid && acc[r][t] < thr[t], acc[r][t], row[r], s.buf + static_cast<size_t>(t) * a.cap,
-                                       &s.cnt[t], static_cast<uint32_t>(a.cap), &s.ovf[t], s.hist + t * kHistBins, a.shift);
+                                       &s.cnt[t], static_cast<uint32_t>(a.cap), &s.ovf[t], s.hist + t * kHistBins, a.shift,
+                                       &s.level[t], s.want);
                     }
                 }
             }
@@ -439,19 +483,23 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
                                    &s.ovf[t], nullptr, 0);
                 }
             }
-            if (epoch_end >= chunks) { lds_barrier(); break; }
+            first = false;
             continue;
         }
 
-        // Threshold update, all queries at once: wavefront t finds the new boundary of query t,
-        // then the whole workgroup compacts the lists (keys held in registers across the reset).
-        // Only LDS is exchanged, so the barriers leave the prefetched rows in flight.  At the end
-        // of the piece lists short enough to be ranked as they are skip this.
+        // End of a round: every wavefront has run out of chunks, or a list asked for a compaction
+        // (the wavefronts finish the chunk they are in and keep the one they have prefetched).
+        // All queries at once: wavefront t finds the new boundary of query t, then the whole
+        // workgroup compacts the lists (keys held in registers across the reset).  Only LDS is
+        // exchanged, so the barriers leave the prefetched rows in flight.  At the end of the piece
+        // lists short enough to be ranked as they are skip the compaction.
+        if (cur >= chunks && lane == 0) atomicOr(s.done, 1u << wave);
         lds_barrier();
-        if (epoch_end >= chunks) {
+        const bool last = *s.done == (1u << kLocalWaves) - 1u;      // same in every thread
+        if (last) {
             bool is_short = true;
             for (int t = 0; t < a.m; ++t) is_short = is_short && s.cnt[t] <= static_cast<uint32_t>(kRankAsIs);
-            if (is_short) break;                         // same in every thread
+            if (is_short) break;
         }
         if (wave < a.m) {
             const uint32_t edge = wave_boundary(s.hist + wave * kHistBins, a.k, a.shift);
@@ -470,7 +518,10 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
         }
         lds_barrier();
         if (threadIdx.x < kLocalMaxQueries) s.cnt[threadIdx.x] = 0;
-        if (threadIdx.x == 0) *s.mark = static_cast<uint32_t>(epoch_end);
+        if (threadIdx.x == 0) {
+            *s.mark = *s.next;
+            *s.want = 0;
+        }
         lds_barrier();
 #pragma unroll
         for (int t = 0; t < MQ; ++t) {
@@ -488,7 +539,25 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
             }
         }
         lds_barrier();
-        if (epoch_end >= chunks) break;
+        if (last) break;
+        // A list that the boundary bin alone keeps more than a quarter full (rows of one tight cluster:
+        // thousands of distances in one bin) is cut exactly: sorted, and only the keys up to the
+        // K-th distance stay; the threshold becomes that distance + 1, finer than any bin edge.
+        for (int t = 0; t < a.m; ++t) {
+            const int have = static_cast<int>(s.cnt[t]);                  // same in every thread
+            if (have <= a.cap / 4 || s.ovf[t] != 0) continue;
+            cut_list_exactly(s.buf + static_cast<size_t>(t) * a.cap, have, a.k, &s.cnt[t], &s.thr[t]);
+        }
+        // The next request comes a quarter of the list later, and always while the list still has
+        // room for every row the wavefronts may add before they see it.  A list that even the exact
+        // cut could not bring that low (ties at the K-th distance itself) asks no more; when it
+        // fills up, it is marked for the exact re-selection at the end.
+        if (threadIdx.x < static_cast<unsigned>(a.m)) {
+            const uint32_t have = s.cnt[threadIdx.x];
+            const uint32_t next = have + static_cast<uint32_t>(a.cap) / 4;
+            s.level[threadIdx.x] = have >= safe_level ? 0xffffffffu : next < safe_level ? next : safe_level;
+        }
+        lds_barrier();
     }
     __syncthreads();
 
@@ -574,6 +643,48 @@ __device__ uint64_t* sort_keys(uint64_t* keys, int have, uint32_t* rank)
     __syncthreads();
     bitonic_sort_lds(keys, P);
     return keys;
+}
+
+// Merge over the whole lists when K keys at or below `bound` are known to exist (the K-th key
+// among the heads): only keys up to the bound can belong to the result, and with the result
+// concentrated in a few pieces (rows ordered by cluster) they are few.  They are collected and
+// sorted; returns null, with nothing decided, if they do not fit the sort buffer.
+__device__ uint64_t* merge_below_bound(const LocalArgs& a, const uint64_t* lists, uint64_t bound, uint64_t* keys,
+                                       uint32_t* rank, uint32_t* fill)
+{
+    const int sh = 31 - __builtin_clz(static_cast<uint32_t>(next_pow2(a.k)));
+    const int64_t nslots = static_cast<int64_t>(a.groups) << sh;
+    const int64_t mask = (int64_t(1) << sh) - 1;
+    __syncthreads();
+    if (threadIdx.x == 0) *fill = 0;
+    __syncthreads();
+    for (int64_t s0 = 0; s0 < nslots; s0 += static_cast<int64_t>(kFinishBatch) * kLocalBlock) {
+        uint64_t k8[kFinishBatch];
+#pragma unroll
+        for (int u = 0; u < kFinishBatch; ++u) {
+            const int64_t slot = s0 + static_cast<int64_t>(u) * kLocalBlock + threadIdx.x;
+            const int g = static_cast<int>(slot >> sh);
+            const int i = static_cast<int>(slot & mask);
+            k8[u] = slot < nslots && i < list_length(a, g) ? lists[static_cast<size_t>(g) * a.list_stride + i] : kPadKey;
+        }
+#pragma unroll
+        for (int u = 0; u < kFinishBatch; ++u) {
+            const bool pass = k8[u] <= bound;            // kPadKey > bound
+            const uint64_t m = __ballot(pass);
+            if (m == 0) continue;
+            const int leader = __ffsll(static_cast<long long>(m)) - 1;
+            uint32_t base = 0;
+            if (lane_id() == leader) base = atomicAdd(fill, static_cast<uint32_t>(__popcll(m)));
+            base = __shfl(base, leader);
+            const uint32_t r = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32),
+                               __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u));
+            if (pass && base + r < static_cast<uint32_t>(kSortCap)) keys[base + r] = k8[u];
+        }
+    }
+    __syncthreads();
+    const int have = static_cast<int>(*fill);
+    if (have > kSortCap) return nullptr;                 // same in every thread
+    return sort_keys(keys, have, rank);
 }
 
 // Merge over the whole lists; leaves the K best keys sorted at the returned address.
@@ -694,6 +805,7 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
     const uint32_t bin = static_cast<uint32_t>(boundary_of<kFinishBins / kLocalBlock>(hist, a.k, wave_sum, pick, &within));
 
     const uint64_t* best = nullptr;
+    uint64_t bound = kPadKey;                            // K keys at or below it are known to exist
     if (within <= kSortCap) {
 #pragma unroll
         for (int u = 0; u < kFinishHeld; ++u)
@@ -702,6 +814,7 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
         best = sort_keys(keys, static_cast<int>(fill), hist);
         // a longer list whose last key read is not beyond the K-th key may hold more of the result
         const uint64_t kth = best[a.k - 1];
+        bound = kth;
 #pragma unroll
         for (int u = 0; u < kFinishHeld; ++u) {
             if (u < rounds) {
@@ -714,7 +827,10 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
         redo = 1u;
     }
     __syncthreads();
-    if (redo != 0) best = merge_whole_lists(a, lists, keys, hist, wave_sum, pick, &fill);
+    if (redo != 0) {
+        best = bound != kPadKey ? merge_below_bound(a, lists, bound, keys, hist, &fill) : nullptr;
+        if (best == nullptr) best = merge_whole_lists(a, lists, keys, hist, wave_sum, pick, &fill);
+    }
 
     const int32_t full = a.d * ((1 << a.q_bits) - 1) * ((1 << a.db_bits) - 1);
     for (int i = threadIdx.x; i < a.k; i += kLocalBlock) {
@@ -728,7 +844,7 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
 size_t local_lds_bytes(int m, int cap)
 {
     return static_cast<size_t>(m) * cap * sizeof(uint64_t) + static_cast<size_t>(m) * kHistBins * sizeof(uint32_t) +
-           (3 * kLocalMaxQueries + 2) * sizeof(uint32_t);                 // counters, next, mark
+           (4 * kLocalMaxQueries + 4) * sizeof(uint32_t);                 // counters, levels, next, mark, want, done
 }
 
 template <int BQ, int BD, int WC, int MQ>
@@ -736,16 +852,26 @@ static hipError_t launch_scan_local_w(const LocalArgs& a, hipStream_t s)
 {
     const dim3 grid(static_cast<unsigned>(a.groups)), block(kLocalBlock);
     const size_t lds = local_lds_bytes(a.m, a.cap);
+#define XBQ_LAUNCH_SCAN_LOCAL(R, PREFETCH)                                                                      \
+    do {                                                                                                        \
+        if (lds > 64 * 1024) {                           /* more than the default limit has to be asked for */   \
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_local<BQ, BD, WC, R, PREFETCH, MQ>), \
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)); \
+            if (e != hipSuccess) return e;                                                                      \
+        }                                                                                                       \
+        hipLaunchKernelGGL((scan_local<BQ, BD, WC, R, PREFETCH, MQ>), grid, block, lds, s, a);                   \
+    } while (0)
     // whole row in registers (one chunk, exactly W words): next step's rows are prefetched, two
     // bundles per wavefront and step while both sets fit the register file
     if (a.nchunks == 1 && a.W == WC) {
-        if constexpr (BD * WC <= 16)      hipLaunchKernelGGL((scan_local<BQ, BD, WC, 2, true, MQ>), grid, block, lds, s, a);
-        else if constexpr (BD * WC <= 24) hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, true, MQ>), grid, block, lds, s, a);
-        else                              hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, false, MQ>), grid, block, lds, s, a);
+        if constexpr (BD * WC <= 16)      XBQ_LAUNCH_SCAN_LOCAL(2, true);
+        else if constexpr (BD * WC <= 24) XBQ_LAUNCH_SCAN_LOCAL(1, true);
+        else                              XBQ_LAUNCH_SCAN_LOCAL(1, false);
     } else {
-        hipLaunchKernelGGL((scan_local<BQ, BD, WC, 1, false, MQ>), grid, block, lds, s, a);
+        XBQ_LAUNCH_SCAN_LOCAL(1, false);
     }
     return hipGetLastError();
+#undef XBQ_LAUNCH_SCAN_LOCAL
 }
 
 template <int BQ, int BD>
@@ -768,9 +894,9 @@ hipError_t launch_scan_local(const LocalArgs& a, hipStream_t s)
 {
     if (a.m < 1 || a.m > kLocalMaxQueries || a.n < 1 || a.wc < 1 || a.wc > 8 || a.nchunks < 1 ||
         a.nchunks * a.wc < a.W) return hipErrorInvalidValue;
-    if (a.k < 1 || a.cap < 8 * a.k || a.cap < kLocalBlock || a.cap > kLocalMaxCap || (a.cap & (a.cap - 1)) != 0)
+    if (a.k < 1 || a.cap < 8 * a.k || a.cap < 4 * kLocalBlock || a.cap > kLocalMaxCap || (a.cap & (a.cap - 1)) != 0)
         return hipErrorInvalidValue;
-    if (local_lds_bytes(a.m, a.cap) > 64 * 1024) return hipErrorInvalidValue;
+    if (local_lds_bytes(a.m, a.cap) > kLocalMaxLds) return hipErrorInvalidValue;
     const int64_t nbundles = (a.n + kLanes - 1) / kLanes;
     if (a.groups > kLocalMaxGroups || a.list_stride < a.k) return hipErrorInvalidValue;
     if (a.groups < 1 || a.bundles_per_group < 1 || a.groups * a.bundles_per_group < nbundles ||

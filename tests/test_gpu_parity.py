@@ -541,6 +541,35 @@ def test_local_selection_very_long_pieces_compact_their_lists():
             gu.assert_same(got, want, f"long pieces m={m} k={k} groups={groups}")
 
 
+def test_local_selection_on_rows_ordered_by_cluster():
+    """Rows of a cluster next to each other, clusters in random order: inside a piece, whenever a
+    cluster closer to the query begins, a burst of rows passes the threshold of the moment.  The
+    lists then ask for compactions on the way (no key may be lost), tight clusters put thousands
+    of distances into one histogram bin (the exact cut), and the result sits in one or two pieces
+    (the merge has to read whole lists)."""
+    rng = np.random.default_rng(91)
+    n, d, bits = 300_000, 96, 4
+    for ncl, spread in ((30, 0.25), (300, 0.05), (6, 0.02)):
+        base = rng.standard_normal((ncl, d))
+        lab = np.sort(rng.integers(ncl, size=n))
+        X = base[lab] + spread * rng.standard_normal((n, d))
+        Xdb = (X / np.linalg.norm(X, axis=1, keepdims=True)).astype(np.float32)
+        Q = base[rng.integers(ncl, size=4)] + spread * rng.standard_normal((4, d))
+        Xq = (Q / np.linalg.norm(Q, axis=1, keepdims=True)).astype(np.float32)
+        for m, k in ((1, 100), (4, 100), (2, 256), (3, 10)):
+            want = gu.oracle_search(Xdb, Xq[:m], bits, k, 2.0)
+            for groups in (256, 8, 2):
+                _say(f"rows ordered by cluster: clusters={ncl} spread={spread} m={m} k={k} groups={groups}")
+                try:
+                    xbq.xbq_set_option("selector", 3)
+                    xbq.xbq_set_option("local_groups", groups)
+                    got = gu.gpu_search(Xdb, Xq[:m], bits, k, 2.0)
+                finally:
+                    xbq.xbq_set_option("local_groups", 256)
+                    xbq.xbq_set_option("selector", 0)
+                gu.assert_same(got, want, f"clusters={ncl} m={m} k={k} groups={groups}")
+
+
 def test_search_ex_takes_its_options_per_call():
     import torch
     Xdb = _rand(60_000, 128, seed=51)
