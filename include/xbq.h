@@ -138,6 +138,8 @@ typedef struct xbq_options {
     int32_t hist_max_queries;
     int32_t kselect_lists_min;
     int32_t local_groups;
+    int32_t row_order;
+    int32_t reserved;            /* keeps the doubles aligned; ignored */
     double growth;
     double refine_growth;
 } xbq_options;
@@ -266,6 +268,11 @@ int xbq_probe_encode_traffic(const float* X, int64_t n, int d, int bits, uint32_
  *   "hist_max_queries"  automatic choice: few-query selection up to this many queries (default
  *                       16), twice as many for k > 128, three times for k > 512
  *   "local_groups"      selector 3: most pieces the rows are split into (1..1024, default 256: one per compute unit)
+ *   "row_order"         selector 1: 0 (default) = every row group of the schedule is spread evenly over
+ *                       the database (bundle n of the order is bundle n * c mod the number of
+ *                       full bundles), so thresholds found on one group hold for the next even when
+ *                       the rows lie sorted or cluster by cluster; 1 = groups of consecutive rows.
+ *                       Results do not depend on it
  *   "refine_growth"     the same bound for the bounded candidate search of xbq_search_refine and
  *                       xbq_k_select (default 1.5: safe when the lists reach their bound of 2048 rows;
  *                       2.0 is a few percent faster when they stay well below it and up to

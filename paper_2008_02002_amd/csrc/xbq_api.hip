@@ -37,6 +37,7 @@ struct Options {
     double refine_growth = 1.5;      // growth bound of the bounded candidate search
     int kselect_lists_min = 128;     // xbq_k_select: batches of at least this many queries start from bounded lists
     int local_groups = 256;          // local selection: most pieces (workgroups) the rows are split into
+    int row_order = 0;               // threshold schedule: 0 = row groups spread over the database, 1 = consecutive rows
 };
 
 std::mutex g_opt_mutex;
@@ -59,6 +60,7 @@ bool set_knob(Options& o, const char* name, double value)
     if (!std::strcmp(name, "refine_growth")) { if (!(value >= 1.25 && value <= 64.0)) return false; o.refine_growth = value; return true; }
     if (!std::strcmp(name, "kselect_lists_min")) { if (!(value >= 0 && value <= (1 << 20))) return false; o.kselect_lists_min = static_cast<int>(value); return true; }
     if (!std::strcmp(name, "qsplit")) { if (!(value >= 0 && value <= 65536)) return false; o.qsplit = static_cast<int>(value); return true; }
+    if (!std::strcmp(name, "row_order")) { if (!(value == 0 || value == 1)) return false; o.row_order = static_cast<int>(value); return true; }
     if (!std::strcmp(name, "local_groups")) { if (!(value >= 1 && value <= kLocalMaxGroups)) return false; o.local_groups = static_cast<int>(value); return true; }
     return false;
 }
@@ -72,7 +74,8 @@ bool options_from(const xbq_options* in, Options& o)
     return set_knob(o, "growth", in->growth) && set_knob(o, "first", in->first) && set_knob(o, "qsplit", in->qsplit) &&
            set_knob(o, "selector", in->selector) && set_knob(o, "hist_max_queries", in->hist_max_queries) &&
            set_knob(o, "kernel", in->kernel) && set_knob(o, "refine_growth", in->refine_growth) &&
-           set_knob(o, "kselect_lists_min", in->kselect_lists_min) && set_knob(o, "local_groups", in->local_groups);
+           set_knob(o, "kselect_lists_min", in->kselect_lists_min) && set_knob(o, "local_groups", in->local_groups) &&
+           set_knob(o, "row_order", in->row_order);
 }
 
 // Scan timing record of xbq_trace_*: one per calling thread.
@@ -135,6 +138,7 @@ constexpr int64_t kQueryBatch = 16384;
 
 struct Plan {
     int W = 0, wc = 0, nchunks = 0;      // wc == 0: register-resident scan
+    int64_t bundle_mul = 1;              // order of the row groups of the threshold schedule, see spread_bundle()
     int first = 0;                       // rows of the dense group
     int cap = 0;                         // candidate slots per query
     int64_t batch = 0;                   // queries per batch
@@ -208,6 +212,17 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
         p.off_dbb = off; off = align_up(off + static_cast<size_t>((n + kLanes - 1) / kLanes) * kLanes * row_bytes, 256);
     }
     p.total = off;
+
+    // Row groups spread over the database (the cross-check scans keep consecutive rows): a
+    // multiplier coprime to the number of full bundles, near its golden section.
+    if (o.row_order == 0 && !p.dot && !p.mfma) {
+        const int64_t full = n / kLanes;
+        for (int64_t mul = static_cast<int64_t>(static_cast<double>(full) * 0.6180339887); mul > 1 && mul < full; ++mul) {
+            int64_t x = mul, y = full;
+            while (y != 0) { const int64_t t = x % y; x = y; y = t; }
+            if (x == 1) { p.bundle_mul = mul; break; }
+        }
+    }
 
     // histogram selection: eligible for plain top-K when the stored distances stay moderate
     // the threshold schedule pays per query for sorting O(k) keys in every row group, the histogram
@@ -524,6 +539,7 @@ int run_search(const Options& o, const SearchJob& job, const Plan& p, char* ws, 
         ScanArgs sa{};
         sa.db = db_codes;
         sa.n = n;
+        sa.bundle_mul = p.bundle_mul;
         sa.m = mb;
         sa.q_bits = q_bits;
         sa.db_bits = db_bits;
@@ -589,6 +605,8 @@ int run_search(const Options& o, const SearchJob& job, const Plan& p, char* ws, 
         }
 
         SelectArgs sel{};
+        sel.n = n;
+        sel.bundle_mul = p.bundle_mul;
         sel.m = mb;
         sel.k = k;
         sel.d = d;
@@ -959,6 +977,8 @@ void xbq_options_default(xbq_options* options)
     options->hist_max_queries = o.hist_max_queries;
     options->kselect_lists_min = o.kselect_lists_min;
     options->local_groups = o.local_groups;
+    options->row_order = o.row_order;
+    options->reserved = 0;
     options->growth = o.growth;
     options->refine_growth = o.refine_growth;
 }

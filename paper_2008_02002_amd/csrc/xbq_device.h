@@ -156,6 +156,22 @@ __device__ __forceinline__ int wave_boundary_bin(const uint32_t* h, uint32_t k, 
     return __shfl(bin, src);
 }
 
+// Order in which the threshold schedule takes the bundles of the database.  Its row groups are
+// ranges of this order, and thresholds found on one group filter the next: on rows that come
+// sorted or cluster by cluster, groups of consecutive rows would see, again and again, whole
+// runs of rows better than anything before (survivor lists overflow, queries are re-scored
+// exactly: measured ten times slower).  So step n of the order is full bundle (n * mul) mod
+// (number of full bundles), mul coprime to that number and near its golden section: every
+// range of steps is spread evenly over the database.  The last, partial bundle keeps its
+// place.  mul <= 1 is the plain order.  Results do not depend on the order.
+__host__ __device__ inline int64_t spread_bundle(int64_t step, int64_t mul, int64_t full_bundles)
+{
+    return mul > 1 && step < full_bundles
+               ? static_cast<int64_t>((static_cast<uint64_t>(step) * static_cast<uint64_t>(mul)) %
+                                      static_cast<uint64_t>(full_bundles))
+               : step;
+}
+
 // Workgroup -> (row block, query range) of the scan kernels.  The grid is one-dimensional.
 // Hardware hands consecutive workgroup ids to the 8 XCDs in turn, each XCD with its own L2,
 // so the id is split as (id % 8, id / 8): XCD c works through row blocks c, c + 8, c + 16, ...

@@ -34,6 +34,8 @@ struct ScanArgs {
     int64_t n;               // rows in the database
     int64_t row_begin;       // multiple of 64
     int64_t row_end;         // <= n
+    int64_t bundle_mul;      // the range counts steps of the order spread_bundle() defines (<= 1: rows as they lie);
+                             // keys carry the rows' own numbers, dense columns count from row_begin in steps
     const uint32_t* q;       // XBQ_ROWS codes (register-resident scan) or chunk-major
                              // padded codes [m][nchunks][B][WC] (word-chunked scan)
     int m;                   // queries in this batch
@@ -94,6 +96,8 @@ struct SelectArgs {
     int dense_stride;
     int64_t row_begin;       // first row of the group just scanned
     int rows;                // rows in the dense group
+    int64_t n;               // rows in the database
+    int64_t bundle_mul;      // as in ScanArgs
     int final_group;         // 1 = last group: plain mode also writes idx / score
     int32_t* idx;            // [m][k]
     int32_t* score;          // [m][k]

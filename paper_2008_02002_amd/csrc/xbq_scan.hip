@@ -37,19 +37,24 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
     const int64_t bundle0 = a.row_begin / kLanes + (static_cast<int64_t>(row_block) * 4 + wave) * R;
     if (bundle0 * kLanes >= a.row_end) return;
     const int64_t last_bundle = (a.n - 1) / kLanes;
+    const int64_t full_bundles = a.n / kLanes;
 
     uint32_t x[R][BD][W];
-    uint32_t row[R];
+    uint32_t row[R];                                 // the row's own number (in the keys)
+    uint32_t col[R];                                 // its place in the range, counted from row_begin (dense columns)
+    bool ok[R];                                      // inside the range
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int64_t bundle = bundle0 + r;
-        const int64_t ld = bundle <= last_bundle ? bundle : last_bundle;   // stay inside the buffer
-        const uint32_t* p = a.db + ld * (BD * W * kLanes) + lane;
+        const int64_t step = bundle0 + r;
+        const int64_t bundle = spread_bundle(step <= last_bundle ? step : last_bundle, a.bundle_mul, full_bundles);
+        const uint32_t* p = a.db + bundle * (BD * W * kLanes) + lane;   // inside the buffer in any case
 #pragma unroll
         for (int b = 0; b < BD; ++b)
 #pragma unroll
             for (int w = 0; w < W; ++w) x[r][b][w] = p[(b * W + w) * kLanes];
         row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
+        ok[r] = step * kLanes + lane < a.row_end;
+        col[r] = static_cast<uint32_t>(step * kLanes + lane - a.row_begin);
     }
 
     const int q0 = qrange * a.qsplit;
@@ -69,8 +74,7 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
         if (DENSE) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
-                if (row[r] < a.row_end)
-                    a.dense[static_cast<size_t>(q) * a.dense_stride + (row[r] - a.row_begin)] = D[r];
+                if (ok[r]) a.dense[static_cast<size_t>(q) * a.dense_stride + col[r]] = D[r];
         } else {
             const uint32_t t = ((uniform_ptr)a.thr)[q];
             bool any = false;
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(kBlock) void scan_resident(const ScanArgs a)
             if (__builtin_expect(__ballot(any) != 0, 0)) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    const bool pass = D[r] < t && row[r] < a.row_end;
+                    const bool pass = D[r] < t && ok[r];
                     append_keys(pass, D[r], row[r], &a.cnt[q], a.cand + static_cast<size_t>(q) * a.cap,
                                 static_cast<uint32_t>(a.cap));
                     if (a.levels != nullptr) count_level(pass, D[r], q, a);
@@ -104,12 +108,14 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
     int row_block, qrange;
     if (!decode_tile(a.row_blocks, a.qranges, row_block, qrange)) return;
     if (!DENSE && a.run_flag != nullptr && ((uniform_ptr)a.run_flag)[0] == 0) return;
-    const int64_t bundle = a.row_begin / kLanes + static_cast<int64_t>(row_block) * 4 + wave;
-    if (bundle * kLanes >= a.row_end) return;
+    const int64_t step = a.row_begin / kLanes + static_cast<int64_t>(row_block) * 4 + wave;
+    if (step * kLanes >= a.row_end) return;
+    const int64_t bundle = spread_bundle(step, a.bundle_mul, a.n / kLanes);
     const int W = a.W;
     const uint32_t* xb = a.db + bundle * (static_cast<int64_t>(BD) * W * kLanes) + lane;
-    const uint32_t row = static_cast<uint32_t>(bundle * kLanes + lane);
-    const bool valid = row < a.row_end;
+    const uint32_t row = static_cast<uint32_t>(bundle * kLanes + lane);              // the row's own number
+    const bool valid = step * kLanes + lane < a.row_end;
+    const uint32_t col = static_cast<uint32_t>(step * kLanes + lane - a.row_begin);  // its place in the range
 
     const int q0 = qrange * a.qsplit;
     const int q1 = q0 + a.qsplit < a.m ? q0 + a.qsplit : a.m;
@@ -149,7 +155,7 @@ __global__ __launch_bounds__(kBlock) void scan_chunked(const ScanArgs a)
             const int q = qt + t;
             if (q < q1) {
                 if (DENSE) {
-                    if (valid) a.dense[static_cast<size_t>(q) * a.dense_stride + (row - a.row_begin)] = acc[t];
+                    if (valid) a.dense[static_cast<size_t>(q) * a.dense_stride + col] = acc[t];
                 } else {
                     const uint32_t thr = ((uniform_ptr)a.thr)[q];
                     append_keys(acc[t] < thr && valid, acc[t], row, &a.cnt[q], a.cand + static_cast<size_t>(q) * a.cap,

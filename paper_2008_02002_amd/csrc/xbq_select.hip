@@ -48,7 +48,8 @@ __device__ int count_within(const uint64_t* keys, int have, uint32_t bound, int*
 
 // Store the head of the sorted keys as the query's new list and derive its threshold.
 // Plain top-K: the first k keys; later rows matter only if D < D_k (an equal D loses the tie
-// to the rows already held, which all have lower numbers).  Candidate mode (extra >= 0):
+// to the rows already held, which all have lower numbers) -- or, when the row groups are spread
+// over the database (bundle_mul > 1) and a later row may have a lower number, if D <= D_k.  Candidate mode (extra >= 0):
 // every key with D <= D_k + extra, at most keep_max (the best by key); see candidate_list_cut.
 // `have` sorted keys are in LDS; all threads call this, with a barrier before it.
 // thr_before: the threshold the keys were collected under (0xffffffff for the first group).
@@ -59,7 +60,7 @@ __device__ void write_topk(const SelectArgs& a, int q, const uint64_t* keys, int
     if (a.extra >= 0) {
         const uint32_t bound = dk + static_cast<uint32_t>(a.extra);
         const int within = count_within(keys, have, bound, scratch);
-        const ListCut cut = candidate_list_cut(keys, within, a.keep_max, bound, thr_before);
+        const ListCut cut = candidate_list_cut(keys, within, a.keep_max, bound, thr_before, a.bundle_mul > 1);
         keep = cut.keep;
         if (threadIdx.x == 0) {
             a.len[q] = static_cast<uint32_t>(keep);
@@ -67,7 +68,8 @@ __device__ void write_topk(const SelectArgs& a, int q, const uint64_t* keys, int
             a.cnt[q] = 0;
         }
     } else if (threadIdx.x == 0) {
-        a.thr[q] = dk;
+        const uint32_t now = dk + (a.bundle_mul > 1 ? 1u : 0u);
+        a.thr[q] = now < thr_before ? now : thr_before;
         a.cnt[q] = 0;
     }
     for (int t = threadIdx.x; t < keep; t += blockDim.x) a.topk[static_cast<size_t>(q) * a.keep_max + t] = keys[t];
@@ -170,7 +172,8 @@ __device__ bool select_by_histogram(const SelectArgs& a, int q, const uint64_t (
             if (pass) list[base + rank] = r[u];
         }
         if (threadIdx.x == 0) {
-            a.thr[q] = static_cast<uint32_t>(kth >> 32);  // a later row needs a smaller D: an equal one loses the tie
+            // a later row needs a smaller D: an equal one loses the tie, unless rows come in any order
+            a.thr[q] = static_cast<uint32_t>(kth >> 32) + (a.bundle_mul > 1 ? 1u : 0u);
             a.cnt[q] = 0;
         }
         return true;
@@ -246,21 +249,27 @@ __global__ __launch_bounds__(kBlock) void select_dense(const SelectArgs a, int c
     const int q = blockIdx.x;
     const int P = next_pow2(a.rows);
     const uint32_t* src = a.dense + static_cast<size_t>(q) * a.dense_stride;
+    // column t of the dense group is step row_begin + t of the scan's order: the key takes the row's own number
+    const int64_t full_bundles = a.n / kLanes;
+    auto key_at = [&](int t) {
+        const int64_t step = a.row_begin + t;
+        const int64_t row = spread_bundle(step / kLanes, a.bundle_mul, full_bundles) * kLanes + step % kLanes;
+        return make_key(src[t], static_cast<uint32_t>(row));
+    };
     if (a.extra < 0) {
         uint64_t r[kSelHeld];
 #pragma unroll
         for (int u = 0; u < kSelHeld; ++u) {
             const int t = u * kBlock + threadIdx.x;
-            r[u] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
+            r[u] = t < a.rows ? key_at(t) : kPadKey;
         }
         if (select_by_histogram(a, q, r, sel)) return;   // same outcome in every thread
-        stream_topk(a, a.rows, [&](int t) { return make_key(src[t], static_cast<uint32_t>(a.row_begin + t)); }, keys,
-                    capacity, &scratch);
+        stream_topk(a, a.rows, key_at, keys, capacity, &scratch);
         write_topk(a, q, keys, a.k, &scratch, 0xffffffffu);
         return;
     }
     for (int t = threadIdx.x; t < P; t += blockDim.x)
-        keys[t] = t < a.rows ? make_key(src[t], static_cast<uint32_t>(a.row_begin + t)) : kPadKey;
+        keys[t] = t < a.rows ? key_at(t) : kPadKey;
     __syncthreads();
     bitonic_sort_lds(keys, P);
     write_topk(a, q, keys, a.rows, &scratch, 0xffffffffu);
@@ -278,9 +287,11 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int capac
     if (threadIdx.x == 0) *fill = held;
     __syncthreads();
     uint32_t thr = a.thr[q];
+    const int64_t full_bundles = r.n / kLanes;
     for (int64_t base = r.row_begin; base < r.row_end; base += blockDim.x) {
-        const int64_t row = base + threadIdx.x;
-        if (row < r.row_end) {
+        const int64_t step = base + threadIdx.x;         // place in the scan's order; the row's own number follows
+        if (step < r.row_end) {
+            const int64_t row = spread_bundle(step / kLanes, a.bundle_mul, full_bundles) * kLanes + step % kLanes;
             const uint32_t D = distance_generic(r.db, row, yq, a.q_bits, a.db_bits, r.W);
             if (D < thr) keys[atomicAdd(fill, 1)] = make_key(D, static_cast<uint32_t>(row));
         }
@@ -297,11 +308,12 @@ __device__ void rescan_rows(const MergeArgs& r, int q, uint64_t* keys, int capac
             if (a.extra >= 0) {
                 const uint32_t bound = dk + static_cast<uint32_t>(a.extra);
                 const int within = count_within(keys, have, bound, fill);
-                const ListCut cut = candidate_list_cut(keys, within, a.keep_max, bound, thr);
+                const ListCut cut = candidate_list_cut(keys, within, a.keep_max, bound, thr, a.bundle_mul > 1);
                 keep = cut.keep;
                 thr = cut.thr;
             } else {
-                thr = dk < thr ? dk : thr;
+                const uint32_t now = dk + (a.bundle_mul > 1 ? 1u : 0u);
+                thr = now < thr ? now : thr;
             }
             if (threadIdx.x == 0) *fill = keep;
         }

@@ -32,6 +32,7 @@ class XbqOptions(ctypes.Structure):
     _fields_ = [("struct_bytes", ctypes.c_uint32), ("selector", ctypes.c_int32), ("kernel", ctypes.c_int32),
                 ("first", ctypes.c_int32), ("qsplit", ctypes.c_int32), ("hist_max_queries", ctypes.c_int32),
                 ("kselect_lists_min", ctypes.c_int32), ("local_groups", ctypes.c_int32),
+                ("row_order", ctypes.c_int32), ("reserved", ctypes.c_int32),
                 ("growth", ctypes.c_double), ("refine_growth", ctypes.c_double)]
 
 

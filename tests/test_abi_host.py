@@ -229,6 +229,7 @@ def test_options_struct_is_validated(L):
     o = xbq.xbq_options_default()
     assert o.struct_bytes == ctypes.sizeof(xbq.XbqOptions) and o.growth == 4.0 and o.first == 1024
     assert o.selector == 0 and o.kernel == 0 and o.local_groups == 256 and o.refine_growth == 1.5
+    assert o.row_order == 0
     fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
 
     def search(opt):
@@ -236,7 +237,7 @@ def test_options_struct_is_validated(L):
                                ctypes.byref(opt) if opt is not None else None, null)
 
     for field, bad in (("growth", 1.0), ("selector", 7), ("kernel", -1), ("first", 5), ("qsplit", -2),
-                       ("local_groups", 0), ("hist_max_queries", -1), ("refine_growth", 100.0), ("struct_bytes", 8)):
+                       ("local_groups", 0), ("row_order", 2), ("hist_max_queries", -1), ("refine_growth", 100.0), ("struct_bytes", 8)):
         opt = xbq.xbq_options_default(**{field: bad})
         assert xbq.xbq_search_workspace_bytes_ex(1000, 10, 128, 4, 10, opt) == 0, field
         assert search(opt) == xbq.EINVAL, field

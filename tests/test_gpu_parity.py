@@ -654,14 +654,59 @@ def test_options_do_not_change_results():
     xbq.xbq_set_option("selector", 1)
     try:
         for growth, first, qsplit in ((1.5, 1024, 0), (4.0, 512, 16), (8.0, 4096, 1000), (2.0, 64, 7)):
-            xbq.xbq_set_option("growth", growth)
-            xbq.xbq_set_option("first", first)
-            xbq.xbq_set_option("qsplit", qsplit)
-            gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 100, 2.0), want, f"growth={growth} first={first}")
+            for row_order in (0, 1):
+                xbq.xbq_set_option("growth", growth)
+                xbq.xbq_set_option("first", first)
+                xbq.xbq_set_option("qsplit", qsplit)
+                xbq.xbq_set_option("row_order", row_order)
+                gu.assert_same(gu.gpu_search(Xdb, Xq, 4, 100, 2.0), want,
+                               f"growth={growth} first={first} row_order={row_order}")
     finally:
         xbq.xbq_set_option("growth", 4.0)
         xbq.xbq_set_option("first", 1024)
         xbq.xbq_set_option("qsplit", 0)
+        xbq.xbq_set_option("row_order", 0)
+        xbq.xbq_set_option("selector", 0)
+
+
+def test_row_groups_in_either_order_on_ties_and_ordered_rows():
+    """The threshold schedule with its row groups spread over the database (default) and as
+    consecutive rows: same results on tie-heavy codes (a later group may hold a lower row with the
+    same distance), on rows sorted towards the query, on rows ordered by cluster, through the plain
+    search, the bounded candidate search and the whole-list K-select."""
+    rng = np.random.default_rng(101)
+    n, d = 50_000, 64
+    base = rng.standard_normal((40, d))
+    lab = np.sort(rng.integers(40, size=n))
+    X = base[lab] + 0.1 * rng.standard_normal((n, d))
+    Xcl = (X / np.linalg.norm(X, axis=1, keepdims=True)).astype(np.float32)
+    Xq = _rand(40, d, seed=102)
+    Xq[:8] = Xcl[rng.integers(n, size=8)]
+    order = np.argsort(-(Xcl @ Xq[0]))                   # rows sorted towards query 0, best last
+    Xsorted = np.ascontiguousarray(Xcl[order[::-1]])
+    try:
+        xbq.xbq_set_option("selector", 1)
+        for row_order in (0, 1):
+            xbq.xbq_set_option("row_order", row_order)
+            for name, Xdb in (("clusters", Xcl), ("sorted", Xsorted)):
+                for bits, k in ((1, 100), (2, 10), (4, 100), (3, 1000)):
+                    _say(f"row_order={row_order} rows={name} bits={bits} k={k}")
+                    gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 2.0), gu.oracle_search(Xdb, Xq, bits, k, 2.0),
+                                   f"row_order={row_order} {name} bits={bits} k={k}")
+                sub = np.arange(16)
+                for bits, k, extra in ((4, 10, 30), (1, 20, 0), (3, 50, 200)):
+                    _say(f"row_order={row_order} rows={name} refine bits={bits} k={k} extra={extra}")
+                    D = gu.oracle_distances(Xdb, Xq[sub], bits, bits, 2.0)
+                    got = gu.gpu_search_refine(Xdb, Xq, bits, bits, k, extra, 2.0)
+                    gu.assert_refined_matches(tuple(x[sub] for x in got), Xdb, Xq[sub], D, k, extra,
+                                              xbq.REFINE_MAX_CANDIDATES)
+                    xbq.xbq_set_option("kselect_lists_min", 0)
+                    got = gu.gpu_k_select(Xdb, Xq, bits, bits, k, extra, n, 2.0)
+                    xbq.xbq_set_option("kselect_lists_min", 128)
+                    gu.assert_refined_matches(tuple(x[sub] for x in got), Xdb, Xq[sub], D, k, extra, n, by_levels=True)
+    finally:
+        xbq.xbq_set_option("kselect_lists_min", 128)
+        xbq.xbq_set_option("row_order", 0)
         xbq.xbq_set_option("selector", 0)
 
 
