@@ -303,6 +303,22 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
     const int64_t b_end = b_begin + a.bundles_per_group < nbundles ? b_begin + a.bundles_per_group : nbundles;
     const int chunks = static_cast<int>((b_end - b_begin + R - 1) / R);
     const int64_t row_stride = static_cast<int64_t>(BD) * a.W * kLanes;
+    // Which chunk of the piece the n-th chunk handed out is.  The first 16 (one per wavefront,
+    // scored without a threshold) lie evenly spaced over the piece, so that the first thresholds
+    // come from a sample of all of it, not from its beginning (rows ordered by cluster); the others
+    // follow in the order they lie, the stream staying sequential.
+    const int spacing = chunks / warm;                   // >= 2 for this to matter
+    const float per_gap = 1.0f / static_cast<float>(spacing > 1 ? spacing - 1 : 1);
+    auto place_of = [&](int c) -> int {
+        if (spacing < 2 || c >= chunks) return c;
+        if (c < warm) return c * spacing;
+        const int j = c - warm;                          // j-th of the chunks that are no multiple of the spacing, or lie behind them
+        if (j >= warm * (spacing - 1)) return j + warm;
+        int gap = static_cast<int>(static_cast<float>(j) * per_gap);   // j / (spacing - 1), by multiplication: j < 2^24
+        if ((gap + 1) * (spacing - 1) <= j) ++gap;
+        if (gap * (spacing - 1) > j) --gap;
+        return gap * spacing + 1 + (j - gap * (spacing - 1));
+    };
 
     uint32_t thr[MQ];
 #pragma unroll
@@ -313,7 +329,7 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
     if (PREFETCH && cur < chunks) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int64_t bundle = b_begin + static_cast<int64_t>(cur) * R + r;
+            const int64_t bundle = b_begin + static_cast<int64_t>(place_of(cur)) * R + r;
             if (bundle < b_end) {
                 const uint32_t* xb = a.db + bundle * row_stride + lane;
 #pragma unroll
@@ -345,7 +361,7 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
             bool live[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const int64_t bundle = b_begin + static_cast<int64_t>(cur) * R + r;
+                const int64_t bundle = b_begin + static_cast<int64_t>(place_of(cur)) * R + r;
                 live[r] = bundle < b_end;                // same in every lane
                 row[r] = static_cast<uint32_t>(bundle * kLanes + lane);
 #pragma unroll
@@ -380,7 +396,7 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
                 if (nxt < chunks) {
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
-                        const int64_t bundle = b_begin + static_cast<int64_t>(nxt) * R + r;
+                        const int64_t bundle = b_begin + static_cast<int64_t>(place_of(nxt)) * R + r;
                         if (bundle < b_end) {
                             const uint32_t* xb = a.db + bundle * row_stride + lane;
 #pragma unroll
@@ -410,7 +426,7 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
                         if (!live[r]) continue;
-                        const uint32_t* xb = a.db + (b_begin + static_cast<int64_t>(cur) * R + r) * row_stride + lane;
+                        const uint32_t* xb = a.db + (b_begin + static_cast<int64_t>(place_of(cur)) * R + r) * row_stride + lane;
 #pragma unroll
                         for (int b = 0; b < BD; ++b)
 #pragma unroll
