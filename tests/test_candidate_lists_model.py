@@ -25,14 +25,19 @@ def model():
     subprocess.run(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", "-I",
                     os.path.join(ROOT, "paper_2008_02002_amd", "csrc"), "-o", LIB, SRC], check=True)
     L = ctypes.CDLL(LIB)
-    L.model_candidate_lists.argtypes = [ctypes.c_void_p, ctypes.c_int64] + [ctypes.c_int] * 9 + [ctypes.c_void_p] * 2
+    L.model_candidate_lists.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64] + [ctypes.c_int] * 9 + \
+                                       [ctypes.c_void_p] * 2
     L.model_candidate_lists.restype = ctypes.c_int
 
-    def run(D, k, extra, keep_max=2048, first=1024, group=4096, cap=2048, capacity=4096, block=256, force_rescan=0):
+    def run(D, k, extra, keep_max=2048, first=1024, group=4096, cap=2048, capacity=4096, block=256, force_rescan=0,
+            rows=None):
+        """rows: the row numbers in the order they are taken (a permutation); D is in that order."""
         D = np.ascontiguousarray(D, dtype=np.uint32)
+        rows = None if rows is None else np.ascontiguousarray(rows, dtype=np.uint32)
         out = np.zeros(keep_max, dtype=np.uint64)
         thr = ctypes.c_uint32()
-        n = L.model_candidate_lists(D.ctypes.data, len(D), k, extra, keep_max, first, group, cap, capacity, block,
+        n = L.model_candidate_lists(D.ctypes.data, None if rows is None else rows.ctypes.data, len(D), k, extra,
+                                    keep_max, first, group, cap, capacity, block,
                                     force_rescan, out.ctypes.data, ctypes.byref(thr))
         assert n >= 0, f"model refused the case ({n})"
         return out[:n], thr.value
@@ -117,3 +122,44 @@ def test_nothing_cut_is_algorithm_1_unchanged(model):
     keys, thr = _check(model, D, 10, 30)
     d_k = od.kth_distance_by_histogram(D, 10)
     assert thr == d_k + 30 + 1                     # every row within the printed boundary is of interest
+
+
+def test_rows_taken_in_any_order(model):
+    """The threshold schedule takes its row groups spread over the database, so a later group may
+    hold a lower row with the same distance: the cut must let it in (threshold one higher once the
+    list is full).  Same tie-heavy sequences as above, the rows taken in a random order and in
+    the schedule's own order (bundles of 64 rows, step s -> bundle s * c mod F)."""
+    rng = np.random.default_rng(29)
+    old_rule_wrong = 0
+    for trial in range(80):
+        n = int(rng.integers(1100, 20_000))
+        levels = int(rng.integers(2, 40))
+        D_by_row = rng.integers(0, levels, size=n) + 5
+        if trial % 3 == 0:
+            D_by_row = np.sort(D_by_row)[::-1]
+        if trial % 2 == 0:
+            order = rng.permutation(n)
+        else:
+            full = n // 64
+            c = next(c for c in range(max(2, int(full * 0.618)), full + 2) if np.gcd(c, full) == 1) if full > 2 else 1
+            steps = np.arange(full)
+            bundles = np.concatenate([(steps * c) % full if full > 2 else steps, np.arange(full, (n + 63) // 64)])
+            order = (bundles[:, None] * 64 + np.arange(64)[None, :]).reshape(-1)
+            order = order[order < n]
+        assert np.array_equal(np.sort(order), np.arange(n))
+        k = int(rng.choice([1, 5, 10, 100, 1000]))
+        extra = int(rng.integers(0, 6))
+        keep_max = int(rng.choice([2048, 1024 + 512, max(k, 64)]))
+        kw = dict(keep_max=keep_max, cap=int(rng.choice([2048, 300])), capacity=4096,
+                  group=int(rng.choice([512, 4096, 9000])), force_rescan=int(trial % 2))
+        keys, _ = model(D_by_row[order], k, extra, rows=order, **kw)
+        want = od.k_select_candidates(D_by_row, k, extra, limit=keep_max)
+        assert np.array_equal((keys & np.uint64(0xffffffff)).astype(np.int64), want), trial
+        # the rule for ascending rows, applied to the same order, must get some of these wrong:
+        # otherwise this test would not see the difference
+        D = np.ascontiguousarray(D_by_row[order], dtype=np.uint32)
+        fake = np.ascontiguousarray(order, dtype=np.uint32)
+        old_keys, _ = model(D, k, extra, **kw)                       # rows = places: ascending rule
+        old_rows = fake[(old_keys & np.uint64(0xffffffff)).astype(np.int64)]
+        old_rule_wrong += int(not np.array_equal(np.sort(old_rows), np.sort(want)))
+    assert old_rule_wrong > 0
