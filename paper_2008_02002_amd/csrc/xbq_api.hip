@@ -291,7 +291,7 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
         p.hoff_zero = h;
         p.zero_words = static_cast<size_t>(hq) * (kHistBins + 1);
         h = align_up(h + p.zero_words * sizeof(uint32_t), 256);
-        p.hoff_cand = h;  h = align_up(h + static_cast<size_t>(hq) * kSortCap * sizeof(uint64_t), 256);
+        p.hoff_cand = h;  h = align_up(h + static_cast<size_t>(hq) * kHistCandCap * sizeof(uint64_t), 256);
         p.hoff_dist = h;  h = align_up(h + static_cast<size_t>(hq) * n * sizeof(uint32_t), 256);
         if (h > p.total) p.total = h;
     }

@@ -165,6 +165,44 @@ __device__ void stream_select(const CollectArgs& a, int q, uint64_t* keys, int* 
     write_result_h(a, q, keys);
 }
 
+// Exact top-K of one query from a list of `total` candidate keys in global memory, in any order
+// (every row up to the boundary bin, more than the sort buffer holds: thousands of rows of one
+// tight cluster in the boundary bin): a running threshold on the whole key and a bounded buffer.
+__device__ void stream_list(const CollectArgs& a, int q, const uint64_t* list, int total, uint64_t* keys, int* fill)
+{
+    if (threadIdx.x == 0) *fill = 0;
+    __syncthreads();
+    uint64_t thr = kPadKey;                              // nothing excluded until K keys are held
+    for (int base = 0; base < total; base += 4 * blockDim.x) {
+        uint64_t k4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = base + u * blockDim.x + threadIdx.x;
+            k4[u] = t < total ? list[t] : kPadKey;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (k4[u] < thr) keys[atomicAdd(fill, 1)] = k4[u];
+        __syncthreads();
+        const int have = *fill;                          // at most 4 * blockDim.x more than before
+        if (have > kSortCap - 4 * static_cast<int>(blockDim.x)) {
+            const int P = next_pow2(have);
+            for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
+            __syncthreads();
+            bitonic_sort_lds(keys, P);
+            thr = keys[a.k - 1];                         // have >= K here: K <= 1024 < have
+            if (threadIdx.x == 0) *fill = a.k;
+        }
+        __syncthreads();
+    }
+    const int have = *fill;
+    const int P = next_pow2(have);
+    for (int t = have + threadIdx.x; t < P; t += blockDim.x) keys[t] = kPadKey;
+    __syncthreads();
+    bitonic_sort_lds(keys, P);
+    write_result_h(a, q, keys);
+}
+
 // Boundary bin of one query: the smallest b whose bins 0..b hold at least k rows (Algorithm
 // 1's boundary at bin resolution), and the number of rows in those bins.  All threads of a
 // 256-thread workgroup call this; the result is returned to every thread.
@@ -214,10 +252,10 @@ __global__ __launch_bounds__(kBlock) void hist_collect(const CollectArgs a)
     uint32_t bin;
     int total;
     boundary_bin(a.hist + static_cast<size_t>(q) * kHistBins, a.k, wave_sum, &s_bin, &s_total, bin, total);
-    if (total > kSortCap) return;                        // too many ties: hist_finish streams instead
+    if (total > kHistCandCap) return;                    // too many ties even for the list: hist_finish streams over the rows
 
     const uint32_t* dq = a.dist + static_cast<size_t>(q) * a.n;
-    uint64_t* list = a.cand + static_cast<size_t>(q) * kSortCap;
+    uint64_t* list = a.cand + static_cast<size_t>(q) * kHistCandCap;
     const int64_t r_begin = static_cast<int64_t>(chunk) * a.rows_per_block;
     const int64_t r_end = r_begin + a.rows_per_block < a.n ? r_begin + a.rows_per_block : a.n;
     // 16 rows per thread per step: the four 16-byte loads are issued before any is looked at
@@ -240,7 +278,7 @@ __global__ __launch_bounds__(kBlock) void hist_collect(const CollectArgs a)
             for (int e = 0; e < 4; ++e) {
                 const int64_t row = r0 + (static_cast<int64_t>(u) * kBlock + threadIdx.x) * 4 + e;
                 const bool pass = row < r_end && (D[u][e] >> a.shift) <= bin;
-                append_keys(pass, D[u][e], static_cast<uint32_t>(row), &a.cand_cnt[q], list, static_cast<uint32_t>(kSortCap));
+                append_keys(pass, D[u][e], static_cast<uint32_t>(row), &a.cand_cnt[q], list, static_cast<uint32_t>(kHistCandCap));
             }
         }
     }
@@ -256,11 +294,15 @@ __global__ __launch_bounds__(kBlock) void hist_finish(const CollectArgs a)
     uint32_t bin;
     int total;
     boundary_bin(a.hist + static_cast<size_t>(q) * kHistBins, a.k, wave_sum, &s_bin, &s_total, bin, total);
-    if (total > kSortCap) {
+    if (total > kHistCandCap) {
         stream_select(a, q, keys, &fill);
         return;
     }
-    const uint64_t* list = a.cand + static_cast<size_t>(q) * kSortCap;
+    const uint64_t* list = a.cand + static_cast<size_t>(q) * kHistCandCap;
+    if (total > kSortCap) {
+        stream_list(a, q, list, total, keys, &fill);
+        return;
+    }
     const int P = next_pow2(total);
     for (int t = threadIdx.x; t < P; t += blockDim.x) keys[t] = t < total ? list[t] : kPadKey;
     __syncthreads();

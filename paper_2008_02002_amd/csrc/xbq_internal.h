@@ -14,6 +14,7 @@ constexpr int kBlock = 256;       // threads per workgroup (4 wavefronts, one pe
 constexpr int kSortCap = 4096;    // most 64-bit keys one workgroup sorts in LDS
 constexpr int kTileQ = 16;        // queries per register tile of the word-chunked scan
 constexpr int kHistBins = 1024;   // histogram bins per query (histogram selection)
+constexpr int kHistCandCap = 65536;   // rows up to the boundary bin that the histogram selection collects per query
 constexpr int kHistMaxQueries = 8;  // queries per pass of the histogram selection
 constexpr int kLocalMaxQueries = 4; // queries per pass of the local selection (few queries, nothing stored)
 constexpr size_t kLocalMaxLds = 152 * 1024;  // LDS one workgroup of the local selection may take (of 160 KB per CU)
@@ -185,7 +186,7 @@ struct CollectArgs {
     int m, k, d, q_bits, db_bits, shift;
     int rows_per_block;      // rows of dist one workgroup filters
     int blocks_per_query;    // ceil(n / rows_per_block)
-    uint64_t* cand;          // [m][kSortCap]
+    uint64_t* cand;          // [m][kHistCandCap]
     uint32_t* cand_cnt;      // [m], zero on entry
     int32_t* idx;            // [m][k]
     int32_t* score;          // [m][k]

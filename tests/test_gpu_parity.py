@@ -470,13 +470,28 @@ def test_rows_sorted_by_similarity_forces_exact_rescan(selector):
 
 def test_massive_ties_take_the_streaming_path_of_the_histogram_selector():
     # one bit, low dimension: a handful of distinct distances over 300k rows, so the boundary
-    # bin holds far more rows than the sort buffer
+    # bin holds far more rows than the sort buffer and than the candidate list (the selection
+    # streams over all stored distances)
     Xdb = _rand(300_000, 8, seed=41)
     Xq = _rand(5, 8, seed=42)
     xbq.xbq_set_option("selector", 2)
     try:
         for bits, k in ((1, 100), (2, 1000)):
             gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 1.5), gu.oracle_search(Xdb, Xq, bits, k, 1.5), "ties")
+        # a tight cluster around the query: some ten thousand rows up to the boundary bin, more than
+        # the sort buffer and fewer than the candidate list holds (the selection streams over the list)
+        rng = np.random.default_rng(43)
+        n, d = 200_000, 96
+        centre = rng.standard_normal(d)
+        X = rng.standard_normal((n, d))
+        X[:30_000] = centre + 0.02 * rng.standard_normal((30_000, d))
+        X = X[rng.permutation(n)]
+        Xdb = (X / np.linalg.norm(X, axis=1, keepdims=True)).astype(np.float32)
+        Q = centre + 0.02 * rng.standard_normal((6, d))
+        Xq = (Q / np.linalg.norm(Q, axis=1, keepdims=True)).astype(np.float32)
+        for bits, k in ((4, 100), (3, 1000), (4, 1)):
+            _say(f"tight cluster, stored distances: bits={bits} k={k}")
+            gu.assert_same(gu.gpu_search(Xdb, Xq, bits, k, 2.0), gu.oracle_search(Xdb, Xq, bits, k, 2.0), "tight cluster")
     finally:
         xbq.xbq_set_option("selector", 0)
 
