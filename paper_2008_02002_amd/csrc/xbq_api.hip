@@ -151,7 +151,7 @@ struct Plan {
     size_t off_dbb = 0, off_qb = 0;
     // histogram selection (aliases the regions above: one call runs one of the two paths)
     bool hist = false;
-    int hist_wc = 0, hist_nchunks = 0, hist_shift = 0;
+    int hist_wc = 0, hist_nchunks = 0, hist_shift = 0, hist_cand_cap = 0;
     size_t hoff_q = 0, hoff_zero = 0, hoff_dist = 0, hoff_cand = 0;
     size_t zero_words = 0;               // hist + cand_cnt, cleared in one go
     // local selection (few queries, nothing stored; aliases the regions above as well)
@@ -291,7 +291,8 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
         p.hoff_zero = h;
         p.zero_words = static_cast<size_t>(hq) * (kHistBins + 1);
         h = align_up(h + p.zero_words * sizeof(uint32_t), 256);
-        p.hoff_cand = h;  h = align_up(h + static_cast<size_t>(hq) * kHistCandCap * sizeof(uint64_t), 256);
+        p.hist_cand_cap = n >= kHistCandCap ? kHistCandCap : next_pow2(static_cast<int>(n) > kSortCap ? static_cast<int>(n) : kSortCap);
+        p.hoff_cand = h;  h = align_up(h + static_cast<size_t>(hq) * p.hist_cand_cap * sizeof(uint64_t), 256);
         p.hoff_dist = h;  h = align_up(h + static_cast<size_t>(hq) * n * sizeof(uint32_t), 256);
         if (h > p.total) p.total = h;
     }
@@ -441,6 +442,7 @@ int run_hist_search(const SearchJob& job, const Plan& p, char* ws, hipStream_t s
         ca.rows_per_block = 4 * 16 * kBlock;          // 16384 rows per workgroup: four rounds of loads
         ca.blocks_per_query = static_cast<int>((n + ca.rows_per_block - 1) / ca.rows_per_block);
         ca.cand = reinterpret_cast<uint64_t*>(ws + p.hoff_cand);
+        ca.cand_cap = p.hist_cand_cap;
         ca.cand_cnt = zero + static_cast<size_t>(kHistMaxQueries < m ? kHistMaxQueries : m) * kHistBins;
         ca.idx = job.idx + qb * job.k;
         ca.score = job.score + qb * job.k;

@@ -252,10 +252,10 @@ __global__ __launch_bounds__(kBlock) void hist_collect(const CollectArgs a)
     uint32_t bin;
     int total;
     boundary_bin(a.hist + static_cast<size_t>(q) * kHistBins, a.k, wave_sum, &s_bin, &s_total, bin, total);
-    if (total > kHistCandCap) return;                    // too many ties even for the list: hist_finish streams over the rows
+    if (total > a.cand_cap) return;                      // too many ties even for the list: hist_finish streams over the rows
 
     const uint32_t* dq = a.dist + static_cast<size_t>(q) * a.n;
-    uint64_t* list = a.cand + static_cast<size_t>(q) * kHistCandCap;
+    uint64_t* list = a.cand + static_cast<size_t>(q) * a.cand_cap;
     const int64_t r_begin = static_cast<int64_t>(chunk) * a.rows_per_block;
     const int64_t r_end = r_begin + a.rows_per_block < a.n ? r_begin + a.rows_per_block : a.n;
     // 16 rows per thread per step: the four 16-byte loads are issued before any is looked at
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(kBlock) void hist_collect(const CollectArgs a)
             for (int e = 0; e < 4; ++e) {
                 const int64_t row = r0 + (static_cast<int64_t>(u) * kBlock + threadIdx.x) * 4 + e;
                 const bool pass = row < r_end && (D[u][e] >> a.shift) <= bin;
-                append_keys(pass, D[u][e], static_cast<uint32_t>(row), &a.cand_cnt[q], list, static_cast<uint32_t>(kHistCandCap));
+                append_keys(pass, D[u][e], static_cast<uint32_t>(row), &a.cand_cnt[q], list, static_cast<uint32_t>(a.cand_cap));
             }
         }
     }
@@ -294,11 +294,11 @@ __global__ __launch_bounds__(kBlock) void hist_finish(const CollectArgs a)
     uint32_t bin;
     int total;
     boundary_bin(a.hist + static_cast<size_t>(q) * kHistBins, a.k, wave_sum, &s_bin, &s_total, bin, total);
-    if (total > kHistCandCap) {
+    if (total > a.cand_cap) {
         stream_select(a, q, keys, &fill);
         return;
     }
-    const uint64_t* list = a.cand + static_cast<size_t>(q) * kHistCandCap;
+    const uint64_t* list = a.cand + static_cast<size_t>(q) * a.cand_cap;
     if (total > kSortCap) {
         stream_list(a, q, list, total, keys, &fill);
         return;
@@ -375,8 +375,8 @@ hipError_t launch_scan_hist(const HistArgs& a, hipStream_t s)
 
 hipError_t launch_hist_collect(const CollectArgs& a, hipStream_t s)
 {
-    if (a.m < 1 || a.blocks_per_query < 1 || a.rows_per_block < 1 || a.rows_per_block % (16 * kBlock) != 0)
-        return hipErrorInvalidValue;
+    if (a.m < 1 || a.blocks_per_query < 1 || a.rows_per_block < 1 || a.rows_per_block % (16 * kBlock) != 0 ||
+        a.cand_cap < kSortCap || a.cand_cap > kHistCandCap) return hipErrorInvalidValue;
     if (static_cast<int64_t>(a.blocks_per_query) * a.rows_per_block < a.n) return hipErrorInvalidValue;
     hipLaunchKernelGGL(hist_collect, dim3(static_cast<unsigned>(a.m * a.blocks_per_query)), dim3(kBlock), 0, s, a);
     hipError_t e = hipGetLastError();

@@ -186,7 +186,8 @@ struct CollectArgs {
     int m, k, d, q_bits, db_bits, shift;
     int rows_per_block;      // rows of dist one workgroup filters
     int blocks_per_query;    // ceil(n / rows_per_block)
-    uint64_t* cand;          // [m][kHistCandCap]
+    uint64_t* cand;          // [m][cand_cap]
+    int cand_cap;            // kSortCap .. kHistCandCap (no more than the database has rows, rounded up)
     uint32_t* cand_cnt;      // [m], zero on entry
     int32_t* idx;            // [m][k]
     int32_t* score;          // [m][k]
