@@ -237,13 +237,28 @@ __device__ __forceinline__ uint32_t wave_boundary(const uint32_t* h, int k, int 
 
 // Exact cut of a list of `have` keys (more than k) by the whole workgroup: sorted, only the keys
 // up to the K-th distance stay, *cnt becomes their number and *thr at most that distance + 1.
-// Kept out of line: it is rare, and inlined its registers crowd the streaming loop.
-__device__ __noinline__ void cut_list_exactly(uint64_t* buf, int have, int k, uint32_t* cnt, uint32_t* thr)
+// Kept out of line: it is rare, and inlined its registers crowd the streaming loop.  Its
+// pointers say that they point into LDS: across a call that knowledge would be lost otherwise,
+// and the sort would go through the generic address path.
+using lds_u64 = __attribute__((address_space(3))) uint64_t;
+using lds_u32 = __attribute__((address_space(3))) uint32_t;
+__device__ __noinline__ void cut_list_exactly(lds_u64* buf, int have, int k, lds_u32* cnt, lds_u32* thr)
 {
     const int P = next_pow2(have);
     for (int i = have + threadIdx.x; i < P; i += kLocalBlock) buf[i] = kPadKey;
     __syncthreads();
-    bitonic_sort_lds(buf, P);
+    for (int kk = 2; kk <= P; kk <<= 1) {                // ascending bitonic network, as bitonic_sort_lds
+        for (int j = kk >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (P >> 1); t += kLocalBlock) {
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int l = i | j;
+                const bool up = (i & kk) == 0;
+                const uint64_t x = buf[i], y = buf[l];
+                if ((x > y) == up) { buf[i] = y; buf[l] = x; }
+            }
+            __syncthreads();
+        }
+    }
     const uint32_t kth = static_cast<uint32_t>(buf[k - 1] >> 32);
     for (int i = threadIdx.x; i < have; i += kLocalBlock) {
         const bool in = static_cast<uint32_t>(buf[i] >> 32) <= kth;
@@ -562,7 +577,8 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
         for (int t = 0; t < a.m; ++t) {
             const int have = static_cast<int>(s.cnt[t]);                  // same in every thread
             if (have <= a.cap / 4 || s.ovf[t] != 0) continue;
-            cut_list_exactly(s.buf + static_cast<size_t>(t) * a.cap, have, a.k, &s.cnt[t], &s.thr[t]);
+            cut_list_exactly((lds_u64*)(s.buf + static_cast<size_t>(t) * a.cap), have, a.k, (lds_u32*)&s.cnt[t],
+                             (lds_u32*)&s.thr[t]);
         }
         // The next request comes a quarter of the list later, and always while the list still has
         // room for every row the wavefronts may add before they see it.  A list that even the exact
