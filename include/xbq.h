@@ -157,7 +157,7 @@ int xbq_search_ex(const uint32_t* db_codes, int64_t n, int db_bits, const uint32
  * holds one until the process ends).  The call allocates and frees nothing.
  *   - A request whose xbq_search_workspace_bytes(n, m, d, bits, k) exceeds
  *     XBQ_STATIC_SCRATCH_BYTES returns XBQ_ESTATIC before anything is enqueued (32 MiB serves,
- *     e.g., up to 4 queries at k <= 256 whatever n, 8 queries x 1 M rows, 1 000 queries at
+ *     e.g., up to 4 queries at k <= 256 whatever n, 8 queries x 900 000 rows, 1 000 queries at
  *     k = 100 or 2 000 at k = 10 whatever n; it uses the process-wide default options).
  *   - All calls on one GPU share that GPU's buffer, which keeps the previous call's contents
  *     (the kernels clear what they need zeroed): two calls that overlap in time on one GPU --
