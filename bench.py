@@ -273,6 +273,50 @@ def few_queries_leg(xbq, cm, w, Xdb, Xq, db, q, bits, db_bits, k, mq, reps=30):
                 "a few microseconds to a launch this short)"}
 
 
+def ordered_rows_leg(xbq, wl, bits=4, k=100):
+    """What the order of the rows costs: the same mixture (1 M x 128, 1000 clusters) with its rows
+    shuffled and lying cluster by cluster; 10 000 queries in one call, and single-query requests."""
+    import torch
+    n, d, m = 1_000_000, 128, 10_000
+    out = {"rows": f"{n} x {d}, Gaussian mixture of 1000 clusters (spread 0.25), {bits}-bit, K={k}"}
+    for name, ordered in (("shuffled", False), ("by_cluster", True)):
+        X, Q = wl.clustered_rows(n, d, m, 1000, 0.25, 11, ordered)
+        db = xbq.xbq_encode(torch.from_numpy(X).cuda(), bits, 2.0, xbq.BUNDLE64)
+        q = xbq.xbq_encode(torch.from_numpy(Q).cuda(), bits, 2.0, xbq.ROWS)
+        del X, Q
+        ws = torch.empty(xbq.xbq_search_workspace_bytes(n, m, d, bits, k), dtype=torch.uint8, device="cuda")
+        idx = torch.empty((m, k), dtype=torch.int32, device="cuda")
+        sc = torch.empty_like(idx)
+        xbq.xbq_search(db, n, q, m, d, bits, k, workspace=ws, idx=idx, score=sc)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            xbq.xbq_search(db, n, q, m, d, bits, k, workspace=ws, idx=idx, score=sc)
+        e1.record()
+        torch.cuda.synchronize()
+        batched_ms = e0.elapsed_time(e1) / 3
+        W = (d + 31) // 32
+        lat = []
+        for i in range(16):                              # sixteen different single-query requests
+            qi = q[i * bits * W:(i + 1) * bits * W]
+            for _ in range(2):
+                xbq.xbq_search(db, n, qi, 1, d, bits, k, workspace=ws, idx=idx[:1], score=sc[:1])
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(10):
+                xbq.xbq_search(db, n, qi, 1, d, bits, k, workspace=ws, idx=idx[:1], score=sc[:1])
+            e1.record()
+            torch.cuda.synchronize()
+            lat.append(e0.elapsed_time(e1) / 10)
+        lat.sort()
+        out[name] = {"search_10000_queries_ms": batched_ms, "one_query_median_ms": lat[len(lat) // 2],
+                     "one_query_max_ms": lat[-1]}
+        del db, q, ws, idx, sc
+        torch.cuda.empty_cache()
+    return out
+
+
 def workload_summary(xbq, cm, wl, name, bits, k, steps, warmup):
     """One line of all_workloads: the same step as the headline on another workload."""
     import torch
@@ -324,6 +368,7 @@ def main():
     ap.add_argument("--no-recall", action="store_true")
     ap.add_argument("--no-all", action="store_true", help="skip the all_workloads leg (the other workloads)")
     ap.add_argument("--no-few", action="store_true", help="skip the few-query and cross-check legs")
+    ap.add_argument("--no-ordered", action="store_true", help="skip the leg that compares shuffled rows with rows ordered by cluster")
     ap.add_argument("--refine", type=int, default=-1, metavar="EXTRA",
                     help="time the candidate search + fp32 refine (xbq_search_refine) with this extra distance")
     ap.add_argument("--k-select", type=int, default=-1, metavar="EXTRA",
@@ -545,6 +590,8 @@ def main():
     # the same step on the other workloads (fewer steps each; the headline fields above stay C2)
     if plain and w.name == "C2" and not args.no_all and not args.queries and not args.set:
         out["all_workloads"] = [workload_summary(xbq, cm, wl, name, b, kk, st, 1) for name, b, kk, st in ALL_WORKLOADS]
+    if plain and w.name == "C2" and not args.no_ordered and not args.no_all and not args.queries and not args.set:
+        out["ordered_rows"] = ordered_rows_leg(xbq, wl)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, bits, db_bits, k, scale)
     else:

@@ -137,3 +137,19 @@ def choose_scale(db_head: np.ndarray, quantile: float = 0.98) -> float:
 
 def workload_scale(w: Workload, quantile: float = 0.98) -> float:
     return choose_scale(database(w, 0, min(w.n, 100_000)), quantile)
+
+
+def clustered_rows(n: int, d: int, m: int, clusters: int, spread: float, seed: int, ordered: bool):
+    """Rows and queries of a Gaussian mixture whose rows lie cluster by cluster (ordered) or
+    shuffled: real collections are often stored in an order that correlates with their content,
+    the workloads above are not.  Returns (rows [n, d], queries [m, d]), L2-normalised fp32."""
+    rng = np.random.default_rng([seed, 7])
+    centres = rng.standard_normal((clusters, d)).astype(np.float32)
+    label = rng.integers(clusters, size=n)
+    if ordered:
+        label = np.sort(label)
+    X = centres[label] + np.float32(spread) * rng.standard_normal((n, d), dtype=np.float32)
+    X /= np.linalg.norm(X, axis=1, keepdims=True)
+    Q = centres[rng.integers(clusters, size=m)] + np.float32(spread) * rng.standard_normal((m, d), dtype=np.float32)
+    Q /= np.linalg.norm(Q, axis=1, keepdims=True)
+    return X.astype(np.float32), Q.astype(np.float32)
