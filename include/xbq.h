@@ -85,7 +85,8 @@ int xbq_encode(const float* X, int64_t n, int d, int bits, float scale, int layo
 /* Bytes of scratch xbq_search needs for these sizes; 0 if arguments are invalid.  Depends on
  * the process-wide options in force (xbq_set_option; xbq_search_workspace_bytes_ex takes them as
  * an argument instead).  With more than a handful of queries it depends on n only through
- * min(n, small constant) and on m only up to an internal query batch (below ~0.3 GiB); with few
+ * min(n, small constant) and on m only up to an internal query batch (about 0.33 GiB at k = 100,
+ * 0.75 GiB at k = 1000); with few
  * queries it holds per-workgroup candidate lists (at most ~25 MB), or for k > 256 four bytes per
  * (query, row) for up to 8 queries, at most 1 GiB; the cross-check kernels add a copy of the
  * database codes. */
@@ -158,7 +159,7 @@ int xbq_search_ex(const uint32_t* db_codes, int64_t n, int db_bits, const uint32
  *   - A request whose xbq_search_workspace_bytes(n, m, d, bits, k) exceeds
  *     XBQ_STATIC_SCRATCH_BYTES returns XBQ_ESTATIC before anything is enqueued (32 MiB serves,
  *     e.g., up to 4 queries at k <= 256 whatever n, 8 queries x 900 000 rows, 1 000 queries at
- *     k = 100 or 2 000 at k = 10 whatever n; it uses the process-wide default options).
+ *     k = 100 or 1 500 at k = 10 whatever n; it uses the process-wide default options).
  *   - All calls on one GPU share that GPU's buffer, which keeps the previous call's contents
  *     (the kernels clear what they need zeroed): two calls that overlap in time on one GPU --
  *     different streams, or different threads -- race.  Serialise them on one stream.

@@ -184,7 +184,7 @@ Plan make_plan(const Options& o, int64_t n, int64_t m, int d, int bits, int k, b
     if (first > kSortCap) first = kSortCap;
     first = first / kLanes * kLanes;
     p.first = static_cast<int>(n < first ? n : first);
-    p.cap = refine ? kRefineCap : (3 * kpad > 1024 ? 3 * kpad : 1024);
+    p.cap = refine ? kRefineCap : (3 * kpad > 2048 ? 3 * kpad : 2048);
     p.keep_max = refine ? kRefineKeep : k;
     const int64_t max_batch = refine ? kQueryBatch / 2 : kQueryBatch;
     p.batch = m < max_batch ? m : max_batch;
