@@ -746,7 +746,7 @@ def test_search_can_be_captured_in_a_hip_graph_and_replayed():
     Xdb = _rand(n, d, seed=51)
     db = xbq.xbq_encode(gu.to_dev(Xdb), bits, 2.0, xbq.BUNDLE64)
     planes = oc.encode(Xdb, bits, 2.0)
-    for m in (1, 300):                                   # histogram selector, threshold selector
+    for m in (1, 3, 300):                                # local selection (one query; three: 108 KB of LDS), threshold selector
         xq = torch.zeros((m, d), dtype=torch.float32, device="cuda")
         q = torch.zeros(xbq.xbq_code_bytes(m, d, bits, xbq.ROWS) // 4, dtype=torch.int32, device="cuda")
         ws = torch.empty(xbq.xbq_search_workspace_bytes(n, m, d, bits, k), dtype=torch.uint8, device="cuda")
