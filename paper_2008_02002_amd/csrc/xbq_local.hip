@@ -30,9 +30,9 @@
 //   local_finish  One workgroup per query merges the lists, reading only their heads: histogram
 //                 of D >> shift2 (4096 bins), boundary bin, the keys at or below it sorted by
 //                 (D, row), first K written.  When a head turns out too short (the result sits in
-//                 a few pieces) the whole lists are read, but only keys up to the K-th key of the
-//                 heads can matter and those are few; massive ties at the boundary are streamed
-//                 with a running threshold on the whole key.
+//                 a few pieces) the rest of those lists is read, but only keys up to the K-th key
+//                 of the heads can matter and those are few; massive ties at the boundary are
+//                 streamed with a running threshold on the whole key.
 //
 // Ties go to the lower row: keys are (D << 32) | row and every cut is made on whole keys or
 // keeps whole bins.
@@ -677,46 +677,19 @@ __device__ uint64_t* sort_keys(uint64_t* keys, int have, uint32_t* rank)
     return keys;
 }
 
-// Merge over the whole lists when K keys at or below `bound` are known to exist (the K-th key
-// among the heads): only keys up to the bound can belong to the result, and with the result
-// concentrated in a few pieces (rows ordered by cluster) they are few.  They are collected and
-// sorted; returns null, with nothing decided, if they do not fit the sort buffer.
-__device__ uint64_t* merge_below_bound(const LocalArgs& a, const uint64_t* lists, uint64_t bound, uint64_t* keys,
-                                       uint32_t* rank, uint32_t* fill)
+// Append a key to the sort buffer if it passes; one LDS atomic per wavefront.  Keys past the
+// buffer are dropped (the counter still counts them).
+__device__ __forceinline__ void collect_if(bool pass, uint64_t key, uint64_t* keys, uint32_t* fill)
 {
-    const int sh = 31 - __builtin_clz(static_cast<uint32_t>(next_pow2(a.k)));
-    const int64_t nslots = static_cast<int64_t>(a.groups) << sh;
-    const int64_t mask = (int64_t(1) << sh) - 1;
-    __syncthreads();
-    if (threadIdx.x == 0) *fill = 0;
-    __syncthreads();
-    for (int64_t s0 = 0; s0 < nslots; s0 += static_cast<int64_t>(kFinishBatch) * kLocalBlock) {
-        uint64_t k8[kFinishBatch];
-#pragma unroll
-        for (int u = 0; u < kFinishBatch; ++u) {
-            const int64_t slot = s0 + static_cast<int64_t>(u) * kLocalBlock + threadIdx.x;
-            const int g = static_cast<int>(slot >> sh);
-            const int i = static_cast<int>(slot & mask);
-            k8[u] = slot < nslots && i < list_length(a, g) ? lists[static_cast<size_t>(g) * a.list_stride + i] : kPadKey;
-        }
-#pragma unroll
-        for (int u = 0; u < kFinishBatch; ++u) {
-            const bool pass = k8[u] <= bound;            // kPadKey > bound
-            const uint64_t m = __ballot(pass);
-            if (m == 0) continue;
-            const int leader = __ffsll(static_cast<long long>(m)) - 1;
-            uint32_t base = 0;
-            if (lane_id() == leader) base = atomicAdd(fill, static_cast<uint32_t>(__popcll(m)));
-            base = __shfl(base, leader);
-            const uint32_t r = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32),
-                               __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u));
-            if (pass && base + r < static_cast<uint32_t>(kSortCap)) keys[base + r] = k8[u];
-        }
-    }
-    __syncthreads();
-    const int have = static_cast<int>(*fill);
-    if (have > kSortCap) return nullptr;                 // same in every thread
-    return sort_keys(keys, have, rank);
+    const uint64_t m = __ballot(pass);
+    if (m == 0) return;
+    const int leader = __ffsll(static_cast<long long>(m)) - 1;
+    uint32_t base = 0;
+    if (lane_id() == leader) base = atomicAdd(fill, static_cast<uint32_t>(__popcll(m)));
+    base = __shfl(base, leader);
+    const uint32_t r = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(m >> 32),
+                       __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(m), 0u));
+    if (pass && base + r < static_cast<uint32_t>(kSortCap)) keys[base + r] = key;
 }
 
 // Merge over the whole lists; leaves the K best keys sorted at the returned address.
@@ -802,6 +775,7 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
     __shared__ uint32_t wave_sum[kLocalWaves];
     __shared__ int pick[2];
     __shared__ uint32_t fill, redo;
+    __shared__ uint32_t longer[kLocalMaxGroups / 32];    // one bit per list that may hold more of the result than was read
     const int q = blockIdx.x;
     const uint64_t* lists = a.lists + static_cast<size_t>(q) * a.groups * a.list_stride;
     const int sh = 31 - __builtin_clz(static_cast<uint32_t>(a.prefix));
@@ -822,6 +796,7 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
     }
     for (int i = threadIdx.x; i < kFinishBins; i += kLocalBlock) hist[i] = 0;
     if (threadIdx.x == 0) { fill = 0; redo = 0; }
+    if (threadIdx.x < kLocalMaxGroups / 32) longer[threadIdx.x] = 0;
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < kFinishHeld; ++u) {
@@ -852,7 +827,10 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
             if (u < rounds) {
                 const int slot = u * kLocalBlock + static_cast<int>(threadIdx.x);
                 const int g = slot >> sh, i = slot & (a.prefix - 1);
-                if (i == a.prefix - 1 && held[u] < kth && list_length(a, g) > a.prefix) redo = 1u;
+                if (i == a.prefix - 1 && held[u] < kth && list_length(a, g) > a.prefix) {
+                    redo = 1u;
+                    atomicOr(&longer[g >> 5], 1u << (g & 31));
+                }
             }
         }
     } else if (threadIdx.x == 0) {
@@ -860,7 +838,30 @@ __global__ __launch_bounds__(kLocalBlock) void local_finish(const LocalArgs a)
     }
     __syncthreads();
     if (redo != 0) {
-        best = bound != kPadKey ? merge_below_bound(a, lists, bound, keys, hist, &fill) : nullptr;
+        // Some lists hold more of the result than their heads (the result sits in a few pieces: rows
+        // ordered by cluster).  K keys at or below `bound` exist, so only keys up to it matter:
+        // those among the heads, still in registers, and those in the rest of the marked lists,
+        // which the wavefronts read list by list.  They are few; sorted, their first K are the result.
+        best = nullptr;
+        if (bound != kPadKey) {
+            if (threadIdx.x == 0) fill = 0;
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kFinishHeld; ++u)
+                if (u < rounds) collect_if(held[u] <= bound, held[u], keys, &fill);      // the pad key is above any bound
+            const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+            for (int g = wave; g < a.groups; g += kLocalWaves) {
+                if ((longer[g >> 5] >> (g & 31) & 1u) == 0) continue;                  // same in every lane
+                const int len = list_length(a, g);
+                for (int i0 = a.prefix; i0 < len; i0 += kLanes) {
+                    const int i = i0 + lane;
+                    const uint64_t key = i < len ? lists[static_cast<size_t>(g) * a.list_stride + i] : kPadKey;
+                    collect_if(key <= bound, key, keys, &fill);
+                }
+            }
+            __syncthreads();
+            if (fill <= static_cast<uint32_t>(kSortCap)) best = sort_keys(keys, static_cast<int>(fill), hist);
+        }
         if (best == nullptr) best = merge_whole_lists(a, lists, keys, hist, wave_sum, pick, &fill);
     }
 
