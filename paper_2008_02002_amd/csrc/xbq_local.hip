@@ -329,7 +329,11 @@ __device__ __forceinline__ void scan_local_body(const LocalArgs& a)
         if (c < warm) return c * spacing;
         const int j = c - warm;                          // j-th of the chunks that are no multiple of the spacing, or lie behind them
         if (j >= warm * (spacing - 1)) return j + warm;
-        int gap = static_cast<int>(static_cast<float>(j) * per_gap);   // j / (spacing - 1), by multiplication: j < 2^24
+        if (chunks >= (1 << 23)) {                       // beyond what a float counts exactly: divide
+            const int gap = j / (spacing - 1);
+            return gap * spacing + 1 + (j - gap * (spacing - 1));
+        }
+        int gap = static_cast<int>(static_cast<float>(j) * per_gap);   // j / (spacing - 1) by multiplication, then set right
         if ((gap + 1) * (spacing - 1) <= j) ++gap;
         if (gap * (spacing - 1) > j) --gap;
         return gap * spacing + 1 + (j - gap * (spacing - 1));
