@@ -63,3 +63,17 @@ def test_cost_model_reproduces_printed_ratios(golden_dir):
     assert cm.credited_lane_ops_per_pair(32, 3, 3) == 18         # 9 XOR + 9 POPCNT (Section 3.3 example)
     assert cm.code_bytes_per_row(200, 3) == 84 and cm.code_bytes_per_row(128, 4) == 64
     assert abs(cm.VALU_INT_LANE_OPS_PER_S - 39.3e12) < 0.05e12
+
+
+def test_clustered_rows_are_seeded_normalised_and_ordered_on_request():
+    X1, Q1 = wl.clustered_rows(5000, 32, 7, 20, 0.25, 3, True)
+    X2, Q2 = wl.clustered_rows(5000, 32, 7, 20, 0.25, 3, True)
+    assert np.array_equal(X1, X2) and np.array_equal(Q1, Q2)
+    assert X1.dtype == np.float32 and X1.shape == (5000, 32) and Q1.shape == (7, 32)
+    assert np.allclose(np.linalg.norm(X1, axis=1), 1.0, atol=1e-5)
+    assert np.allclose(np.linalg.norm(Q1, axis=1), 1.0, atol=1e-5)
+    # ordered: neighbouring rows mostly belong to one cluster, so they are far more alike than
+    # rows of the shuffled variant
+    Xs, _ = wl.clustered_rows(5000, 32, 7, 20, 0.25, 3, False)
+    near = lambda X: float(np.mean(np.sum(X[:-1] * X[1:], axis=1)))
+    assert near(X1) > 0.4 and near(Xs) < 0.2
